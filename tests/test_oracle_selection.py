@@ -1,0 +1,230 @@
+"""Pins for the oracle's region map, cosine similarity and greedy facility-location selection.
+
+Each check compares the oracle with something it does not compute itself: a numpy/itertools
+construction, a closed form, or a theorem the paper states (Sec. 3.2, Sec. 4.1, Alg. 1/2, App. A.1).
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+
+def _np_fl(S, subset):
+    """Eq. 2 shifted by +1 per token, written with numpy (independent of the C code)."""
+    if len(subset) == 0:
+        return 0.0
+    return float((S[:, list(subset)].max(axis=1) + 1.0).sum())
+
+
+def _rand_S(rng, n, C=8):
+    X = rng.standard_normal((n, C))
+    Xn = X / np.linalg.norm(X, axis=1, keepdims=True)
+    return X, Xn @ Xn.T
+
+
+def test_region_map_matches_reshape(oracle):
+    H, W, th, tw = 12, 20, 4, 5
+    region, local, token_of = oracle.region_map(H, W, th, tw)
+    grid = np.arange(H * W).reshape(H // th, th, W // tw, tw).transpose(0, 2, 1, 3).reshape(-1, th * tw)
+    assert np.array_equal(token_of, grid)
+    for p in range(grid.shape[0]):
+        for l in range(grid.shape[1]):
+            assert region[grid[p, l]] == p and local[grid[p, l]] == l
+
+
+def test_region_map_stripes(oracle):
+    # a stripe region is tile_h rows by the full width: contiguous token ranges
+    H, W = 8, 6
+    _, _, token_of = oracle.region_map(H, W, 2, W)
+    assert np.array_equal(token_of, np.arange(H * W).reshape(4, 12))
+
+
+def test_cosine_matches_numpy(oracle):
+    rng = np.random.default_rng(1)
+    X, S_np = _rand_S(rng, 19, 7)
+    S = oracle.cosine(X)
+    assert np.allclose(S, S_np, atol=1e-14)
+    assert np.allclose(np.diag(S), 1.0, atol=1e-14)
+    assert np.array_equal(S, S.T)
+
+
+def test_cosine_zero_vector_and_fp32_rounding(oracle):
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((6, 5))
+    X[3] = 0.0
+    S = oracle.cosine(X)
+    assert np.all(S[3] == 0.0) and np.all(S[:, 3] == 0.0) and np.all(np.isfinite(S))
+    S32 = oracle.cosine(X, round_f32=True)
+    assert np.array_equal(S32, S32.astype(np.float32).astype(np.float64))
+    assert np.array_equal(S32, S.astype(np.float32).astype(np.float64))
+
+
+def test_fl_value_matches_numpy_and_bounds(oracle):
+    rng = np.random.default_rng(3)
+    _, S = _rand_S(rng, 15)
+    for size in (0, 1, 4, 15):
+        sub = rng.permutation(15)[:size]
+        assert oracle.fl_value(S, sub) == pytest.approx(_np_fl(S, sub), abs=1e-12)
+    assert oracle.fl_value(S, np.arange(15)) == pytest.approx(2 * 15, abs=1e-12)  # f'(V) = sum (S_ii + 1)
+    assert oracle.fl_value(S, [2, 7]) <= 2 * 15
+
+
+def test_monotone_and_diminishing_returns(oracle):
+    # Sec. 3.2: f(v|A) >= f(v|B) for A subset of B, and f is monotone (gains >= 0)
+    rng = np.random.default_rng(4)
+    _, S = _rand_S(rng, 14)
+    for _ in range(200):
+        perm = rng.permutation(14)
+        a, b = sorted(rng.integers(0, 12, size=2))
+        A, Bset, v = perm[:a], perm[:b], perm[13]
+        gA = oracle.fl_value(S, list(A) + [v]) - oracle.fl_value(S, A)
+        gB = oracle.fl_value(S, list(Bset) + [v]) - oracle.fl_value(S, Bset)
+        assert gA >= gB - 1e-12
+        assert gB >= -1e-12
+
+
+def test_cached_gain_equals_direct_marginal(oracle):
+    # App. A.1: sum_j max(0, S_ij - m_j) is f(A + v) - f(A).  Two code paths.  Exact ties are
+    # structural (two candidates that only improve each other's coverage have equal gains), and
+    # rounding may break them differently, so picks are compared up to the first step whose
+    # runner-up gap is at rounding level, and the direct picks are then checked teacher-forced.
+    rng = np.random.default_rng(5)
+    for n, k in ((12, 12), (30, 11), (64, 32)):
+        _, S = _rand_S(rng, n)
+        p1, g1, gaps = oracle.greedy_fl(S, k)
+        p2, g2 = oracle.greedy_direct(S, k)
+        tie = np.nonzero(gaps[:k - 1] < 1e-12)[0]
+        upto = int(tie[0]) if len(tie) else k
+        assert upto >= 5
+        assert np.array_equal(p1[:upto], p2[:upto])
+        # first value: row sum (cached form) vs f'({v}) = row sum + n (direct form)
+        assert g1[0] + n == pytest.approx(g2[0], abs=1e-10)
+        assert np.allclose(g1[1:upto], g2[1:upto], atol=1e-10)
+        bad, deficit, _ = oracle.check_picks(S, p2)
+        assert bad == -1 and np.all(deficit < 1e-12)
+        # and the cached values agree with numpy's evaluation of the objective along the way
+        for q in range(1, k):
+            assert g1[q] == pytest.approx(_np_fl(S, p1[:q + 1]) - _np_fl(S, p1[:q]), abs=1e-10)
+
+
+def test_structural_ties_resolve_to_lowest_index_in_fp32_decision_precision(oracle):
+    # With similarities rounded to single and values accumulated in double, the sums of a tie's
+    # two sides are exact, so a mathematical tie is an exact tie and the lowest index wins.
+    rng = np.random.default_rng(55)
+    hits = 0
+    for _ in range(20):
+        X = rng.standard_normal((40, 6))
+        S = oracle.cosine(X, round_f32=True)
+        picks, gains, gaps = oracle.greedy_fl(S, 30)
+        for q in np.nonzero(gaps[:29] == 0.0)[0]:
+            _, deficit, first = oracle.check_picks(S, picks[:q + 1])
+            assert first[q] == 1 and deficit[q] == 0.0
+            hits += 1
+    assert hits > 0
+
+
+def test_greedy_within_1_minus_1_over_e_of_brute_force(oracle):
+    # Sec. 3.2 / Alg. 1: greedy >= (1 - 1/e) OPT for a monotone submodular f with f({}) = 0
+    rng = np.random.default_rng(6)
+    for trial in range(12):
+        n = int(rng.integers(8, 15))
+        k = int(rng.integers(1, 5))
+        _, S = _rand_S(rng, n, C=3)
+        picks, _, _ = oracle.greedy_fl(S, k)
+        opt = max(_np_fl(S, c) for c in itertools.combinations(range(n), k))
+        got = _np_fl(S, picks)
+        assert got >= (1 - 1 / np.e) * opt - 1e-12
+        assert got <= opt + 1e-12
+
+
+def test_first_pick_is_largest_row_sum(oracle):
+    rng = np.random.default_rng(7)
+    _, S = _rand_S(rng, 40)
+    picks, gains, gaps = oracle.greedy_fl(S, 1)
+    rs = S.sum(axis=1)
+    assert picks[0] == int(np.argmax(rs))
+    assert gains[0] == pytest.approx(rs.max(), abs=1e-12)
+    assert gaps[0] == pytest.approx(rs.max() - np.sort(rs)[-2], abs=1e-12)
+
+
+def test_select_all_is_a_permutation_and_gains_shrink(oracle):
+    rng = np.random.default_rng(8)
+    n = 48
+    _, S = _rand_S(rng, n)
+    picks, gains, gaps = oracle.greedy_fl(S, n)
+    assert sorted(picks.tolist()) == list(range(n))
+    fgain = gains.copy()
+    fgain[0] += n  # value of the first step in terms of f'
+    assert np.all(np.diff(fgain) <= 1e-12)  # submodularity along the greedy chain
+    assert np.all(gaps[:-1] >= 0) and np.isinf(gaps[-1])
+
+
+def test_identical_tokens_pick_in_index_order(oracle):
+    S = np.ones((9, 9))
+    picks, gains, gaps = oracle.greedy_fl(S, 9)
+    assert picks.tolist() == list(range(9))  # every step is an exact tie -> lowest index
+    assert np.all(gains[1:] == 0.0) and np.all(gaps[:-1] == 0.0)
+
+
+def test_tie_break_with_duplicated_tokens(oracle):
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((10, 4))
+    X[7] = X[2]  # exact duplicates: always tie, index 2 must win over 7
+    S = oracle.cosine(X)
+    picks, _, _ = oracle.greedy_fl(S, 10)
+    assert picks.tolist().index(2) < picks.tolist().index(7)
+
+
+def test_separated_clusters_are_each_hit_first(oracle):
+    rng = np.random.default_rng(10)
+    c, per, C = 5, 6, 16
+    centers = np.eye(C)[:c] * 10.0
+    X = np.concatenate([centers[i] + 0.05 * rng.standard_normal((per, C)) for i in range(c)])
+    order = rng.permutation(c * per)
+    X, label = X[order], np.repeat(np.arange(c), per)[order]
+    picks, _, _ = oracle.greedy_fl(oracle.cosine(X), c)
+    assert sorted(label[picks].tolist()) == list(range(c))
+
+
+def test_negative_coverage_does_not_reselect(oracle):
+    # m_j < 0 for some j: a zeroed row would still have a positive value; the mask must exclude it
+    X = np.array([[1.0, 0.0], [-1.0, 0.0], [-0.9, 0.1], [0.9, 0.1]])
+    picks, _, _ = oracle.greedy_fl(oracle.cosine(X), 4)
+    assert sorted(picks.tolist()) == [0, 1, 2, 3]
+
+
+def test_check_picks_accepts_greedy_and_flags_a_wrong_pick(oracle):
+    rng = np.random.default_rng(11)
+    _, S = _rand_S(rng, 25)
+    picks, _, _ = oracle.greedy_fl(S, 10)
+    bad, deficit, first = oracle.check_picks(S, picks)
+    assert bad == -1 and np.all(deficit == 0.0) and np.all(first == 1)
+    wrong = picks.copy()
+    others = [i for i in range(25) if i not in picks[:5].tolist() and i != picks[4]]
+    wrong[4] = others[0]
+    wrong[5:] = [i for i in others[1:]][:5]
+    bad, deficit, first = oracle.check_picks(S, wrong)
+    assert bad == -1 and first[4] == 0 and deficit[4] > 0
+    dup = picks.copy()
+    dup[6] = dup[1]
+    assert oracle.check_picks(S, dup)[0] == 6
+
+
+def test_select_per_region_matches_single_region_runs(oracle):
+    rng = np.random.default_rng(12)
+    B, H, W, C, th, tw, k = 2, 8, 12, 5, 4, 6, 7
+    X = rng.standard_normal((B, H * W, C))
+    d = oracle.make_desc(B, H, W, C, th, tw, k, 1, 0.1, sim_fp32=False)
+    idx, gain, gap = oracle.select(d, X)
+    _, _, token_of = oracle.region_map(H, W, th, tw)
+    for b in range(B):
+        for p in range(token_of.shape[0]):
+            S = oracle.cosine(X[b, token_of[p]])
+            picks, g, _ = oracle.greedy_fl(S, k)
+            assert np.array_equal(idx[b, p], token_of[p][picks])
+            assert np.allclose(gain[b, p], g)
+    # decision precision: with sim_fp32 the similarities are rounded to single first
+    d32 = oracle.make_desc(B, H, W, C, th, tw, k, 1, 0.1, sim_fp32=True)
+    idx32, _, _ = oracle.select(d32, X)
+    S32 = oracle.cosine(X[1, token_of[2]], round_f32=True)
+    assert np.array_equal(idx32[1, 2], token_of[2][oracle.greedy_fl(S32, k)[0]])
