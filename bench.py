@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the ToMA layer path on one MI355X.
+
+A step is one whole layer call (select -> merge weights -> merge -> attention -> unmerge, nothing
+cached) on seeded synthetic hidden states of the SDXL stage-1 shape (B=2, 64x64 tokens, width 640).
+Prints ONE JSON line: microseconds per layer call, the roofline of the kernel that takes the most
+time (per-kernel durations measured live with HIP events on the launch stream), the cached-pattern
+variants, and the fp64 CPU oracle timed on the same inputs on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload sdxl1] [--merge-regions global|tile]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "µs per merge+attn+unmerge layer call (SDXL 4096×640); % bf16 MFMA / HBM roofline"
+PEAK = {"hbm": 8000.0, "bf16": 2500.0, "f32": 157.3, "f64": 78.6}   # GB/s, TFLOP/s (MI355X, dense)
+
+
+def kernel_work(w, R, esize):
+    """Algorithmic work per launch of each kernel: (bound, amount, unit-scale) with flops for the
+    matrix-core kernels and bytes for the streaming ones."""
+    from paper_2509_10918_amd import costs
+    f = costs.stage_flops(w.B, w.N, w.C, w.P, w.d_loc, R, w.T_extra)
+    L = w.D + w.T_extra
+    mm = "bf16" if w.dtype == "bf16" else "f32"
+    a_bytes = w.B * w.D * (w.N // R) * esize
+    return {
+        "norms": ("hbm", w.B * w.N * w.C * esize + w.B * w.N * 8),
+        "gram": ("f64", f["similarity"]),
+        "greedy": ("hbm", costs.greedy_stream_bytes(w.B, w.P, w.n_loc, w.d_loc)),
+        "weights_stats": (mm, f["weights"]),
+        "lse": ("hbm", w.B * w.N * 12),
+        "weights_write": (mm, f["weights"]),
+        "zsum": ("hbm", w.B * w.D * 8),
+        "merge": (mm, f["merge"]),
+        "qkv": (mm, f["qkv"]),
+        "attention": (mm, f["attention"]),
+        "proj": (mm, 2 * w.B * L * w.C * w.C),
+        "scale_rows": ("hbm", 2 * w.B * w.D * w.C * esize),
+        "unmerge": (mm, f["unmerge"]),
+        "copy_extra": ("hbm", 2 * w.B * w.T_extra * w.C * esize),
+        "_a_bytes": ("hbm", a_bytes),
+    }
+
+
+def roofline_entry(name, work, avg_us):
+    bound, amount = work[name]
+    if bound == "hbm":
+        achieved = amount / (avg_us * 1e-6) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": PEAK["hbm"], "unit": "GB/s",
+                "frac": achieved / PEAK["hbm"], "traffic": None}
+    achieved = amount / (avg_us * 1e-6) / 1e12
+    return {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": PEAK[bound], "unit": "TFLOP/s",
+            "frac": achieved / PEAK[bound], "traffic": None, "mfma_dtype": bound}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="sdxl1")
+    ap.add_argument("--merge-regions", default="global", choices=["global", "tile"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report", default=None, help="also write a per-kernel table (text) to this path")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_10918_amd import binding as tb
+    from paper_2509_10918_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    R = 1 if args.merge_regions == "global" else w.P
+    inp = synth.make_inputs(w)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    esize = 2 if w.dtype == "bf16" else 4
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(tdt).contiguous()
+
+    desc = tb.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, R, w.tau, w.dtype)
+    attn = tb.toma_attn_desc(w.heads, w.head_dim, w.T_extra)
+    X = dev(inp["X"])
+    Xe = dev(inp["X_extra"]) if inp["X_extra"] is not None else None
+    Wq, Wk, Wv = dev(inp["Wq"]), dev(inp["Wk"]), dev(inp["Wv"])
+    ws = tb.alloc_workspace(desc, attn)
+    idx, A, Z = tb.alloc_cache(desc)
+    Y = torch.empty((w.B, w.N, w.C), dtype=tdt, device="cuda")
+    Ye = torch.empty((w.B, w.T_extra, w.C), dtype=tdt, device="cuda") if w.T_extra else None
+
+    def call(flags):
+        tb.toma_layer(desc, attn, flags, X, Xe, idx, A, Z, Wq, Wk, Wv, None, Y, Ye, ws)
+
+    def timed(flags, steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            call(flags)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps     # ms per step
+
+    for _ in range(args.warmup):
+        call(0)
+    ms = timed(0, args.steps)
+    ms_idx = timed(tb.TOMA_REUSE_IDX, args.steps)
+    ms_a = timed(tb.TOMA_REUSE_A, args.steps)
+
+    # per-kernel durations: the same K steps with every launch bracketed by HIP events
+    tb.toma_profile_enable(True)
+    timed(0, args.steps)
+    per_kernel = {}
+    for name in tb.toma_profile_kernel_names():
+        n, total = tb.toma_profile_read(name)
+        if n:
+            per_kernel[name] = {"launches_per_step": n / args.steps, "avg_us": total * 1e3 / n,
+                                "us_per_step": total * 1e3 / args.steps}
+    tb.toma_profile_enable(False)
+    work = kernel_work(w, R, esize)
+    for name, rec in per_kernel.items():
+        rec.update({k: v for k, v in roofline_entry(name, work, rec["avg_us"]).items() if k != "kernel"})
+    dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
+    roofline = roofline_entry(dominant, work, per_kernel[dominant]["avg_us"])
+    roofline["avg_us"] = per_kernel[dominant]["avg_us"]
+    mfma_k = [k for k in per_kernel if per_kernel[k]["bound"] == "mfma" and k != "gram"]
+    mfma_flops = sum(work[k][1] * per_kernel[k]["launches_per_step"] for k in mfma_k)
+    mfma_us = sum(per_kernel[k]["us_per_step"] for k in mfma_k)
+
+    out = {
+        "metric": METRIC, "value": ms * 1e3, "unit": "us", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B}, {w.H}x{w.W} tokens (N={w.N}), C={w.C}, "
+                               f"{w.tile_h}x{w.tile_w} regions (P={w.P}), keep {w.keep:g} (D={w.D}), tau={w.tau}, "
+                               f"{w.heads} heads x {w.head_dim}, extra tokens {w.T_extra}, "
+                               f"merge_regions={R} ({args.merge_regions})",
+                   "call": "toma_layer, nothing cached (select + weights + merge + attention + unmerge)"},
+        "roofline": roofline,
+        "us_idx_cached": ms_idx * 1e3, "us_idx_and_weights_cached": ms_a * 1e3,
+        "mfma_stages": {"tflops": mfma_flops / (mfma_us * 1e-6) / 1e12 if mfma_us else None,
+                        "frac_of_peak": (mfma_flops / (mfma_us * 1e-6) / 1e12) / PEAK["bf16" if w.dtype == "bf16" else "f32"]
+                        if mfma_us else None, "us_per_step": mfma_us},
+        "kernels": per_kernel,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import toma_oracle as orc
+        f64 = lambda a: None if a is None else np.asarray(a, dtype=np.float64)
+        od = orc.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, R, w.tau)
+        t0 = time.perf_counter()
+        ref = orc.layer(od, f64(inp["X"]), f64(inp["Wq"]), f64(inp["Wk"]), f64(inp["Wv"]), heads=w.heads,
+                        Xe=f64(inp["X_extra"]))
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": cpu_s * 1e6, "unit": "us", "cores": orc.threads(), "kind": "oracle",
+                               "sample": "1 full layer call of the same workload (all samples, all regions)"}
+        call(0)
+        torch.cuda.synchronize()
+        idx_gpu = idx.cpu().numpy()
+        rel_gap = ref["gap"] / np.maximum(ref["gain"], 1e-30)
+        y = Y.to(torch.float64).cpu().numpy()
+        out["parity"] = {
+            "regions_with_different_picks": int((~np.all(idx_gpu == ref["idx"], axis=2)).sum()),
+            "near_tie_steps": int((rel_gap[..., :-1] < 1e-6).sum()), "exact_tie_steps": int((ref["gap"][..., :-1] == 0).sum()),
+            "clamped_destinations": int(ref["clamps"]),
+            "max_rel_err_Y": float(np.abs(y - ref["Y"]).max() / np.abs(ref["Y"]).max()),
+        }
+    out["context"] = {"paper": "merge 38.8 us / unmerge 40.5 us at N=1024 on RTX6000 (Table 6); SDXL/Flux "
+                               "end-to-end latency -24% / -23% (abstract); other hardware, context only"}
+    if args.report:
+        with open(args.report, "w") as fh:
+            fh.write(f"# {out['config']['workload']}\n# {args.steps} steps, {ms * 1e3:.1f} us per layer call; "
+                     f"idx cached {ms_idx * 1e3:.1f}; idx+weights cached {ms_a * 1e3:.1f}\n")
+            fh.write(f"{'kernel':<15}{'launch/step':>12}{'avg us':>10}{'achieved':>12}{'unit':>9}{'frac':>8}\n")
+            for k, r in sorted(per_kernel.items(), key=lambda kv: -kv[1]["us_per_step"]):
+                fh.write(f"{k:<15}{r['launches_per_step']:>12.1f}{r['avg_us']:>10.2f}{r['achieved']:>12.2f}"
+                         f"{r['unit']:>9}{r['frac']:>8.3f}\n")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

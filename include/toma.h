@@ -1,0 +1,164 @@
+/*
+ * toma.h -- C ABI of libtoma: one ToMA layer (Token Merge with Attention) on one AMD MI355X.
+ *
+ * The calls follow the paper's statement of the method (ToMA: Token Merge with Attention for
+ * Diffusion Models): destinations are selected per local region by greedy facility location
+ * (Sec. 4.1, Alg. 2), tokens are merged with an attention-like weight matrix (Sec. 4.2.1), a core
+ * module runs on the merged tokens (here multi-head attention, Eq. 1), and the result is unmerged
+ * by the transpose of the merge matrix (Sec. 4.2.2); Alg. 3 strings these together per region and
+ * Sec. 4.3.2 reuses destinations and weights across steps.
+ *
+ * Conventions for every call
+ *   - Data pointers are DEVICE pointers owned by the caller, 16-byte aligned, dense, row-major,
+ *     last dimension contiguous.  Descriptors are host structs, read during the call only.
+ *   - The library allocates nothing, frees nothing and never synchronises: all work is queued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and the call returns at
+ *     once; outputs are valid after the caller synchronises the stream.
+ *   - `ws` is caller-owned device scratch of at least toma_workspace_bytes() bytes, 256-byte
+ *     aligned; its contents are undefined between calls.  Calls sharing one workspace must be
+ *     ordered on one stream.
+ *   - The return value is a toma_status.  Argument errors are found on the host before anything
+ *     is launched; nothing is written in that case.  TOMA_ERR_LAUNCH reports a failed launch.
+ *   - Tokens lie on a row-major H x W grid, token n = r*W + c.  Region p and local position l of a
+ *     token: p = (r / tile_h) * (W / tile_w) + (c / tile_w), l = (r % tile_h) * tile_w + c % tile_w
+ *     (tile-shaped regions, Sec. 4.3.1; tile_w == W gives stripe-shaped regions).
+ *     P = regions per sample, N_loc = tile_h * tile_w, D = P * d_loc destinations per sample.
+ *   - Limits: C % 32 == 0; N_loc % 16 == 0 and N_loc <= 256; 1 <= d_loc <= N_loc;
+ *     merge_regions is 1 or P; head_dim is 64 or 128 (or C when heads == 1 and C <= 128).
+ *     Anything else returns TOMA_ERR_UNSUPPORTED or TOMA_ERR_SHAPE.
+ */
+#ifndef TOMA_H
+#define TOMA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TOMA_OK = 0,
+  TOMA_ERR_NULL = 1,        /* a required pointer is NULL */
+  TOMA_ERR_SHAPE = 2,       /* sizes are non-positive or do not divide as required */
+  TOMA_ERR_ALIGN = 3,       /* a data pointer is not 16-byte aligned (workspace: 256) */
+  TOMA_ERR_WORKSPACE = 4,   /* ws_bytes is smaller than toma_workspace_bytes() */
+  TOMA_ERR_UNSUPPORTED = 5, /* a valid request outside the limits listed above */
+  TOMA_ERR_LAUNCH = 6       /* the HIP runtime refused a launch */
+} toma_status;
+
+typedef enum { TOMA_F32 = 0, TOMA_BF16 = 1 } toma_dtype;
+
+/* Shape of one layer call (inputs of Alg. 3: X in R^{B x N x d}, D, tau). */
+typedef struct {
+  int32_t B, H, W, C;    /* batch, grid height and width (N = H*W), channel width */
+  int32_t tile_h, tile_w;/* region shape; must divide H and W */
+  int32_t d_loc;         /* destinations kept per region */
+  int32_t merge_regions; /* 1: merge weights over all tokens of a sample (the paper's "ToMA");
+                            P: weights inside each region ("ToMA_tile", Alg. 3) */
+  float tau;             /* merge temperature, > 0 */
+  float logit_scale;     /* 0: use 1/tau (Sec. 4.2.1's display formula); else the multiplier */
+  int32_t dtype;         /* toma_dtype of X, Xm, O, Y, the projection weights and A */
+} toma_desc;
+
+/* The core module: multi-head attention on [merged ; extra] tokens.  heads * head_dim == C.
+ * t_extra tokens per sample (e.g. text tokens) join the attention unmerged. */
+typedef struct {
+  int32_t heads, head_dim, t_extra;
+} toma_attn_desc;
+
+/* Bytes of scratch any call with these descriptors needs (attn may be NULL for calls that take
+ * no toma_attn_desc).  Returns 0 when the descriptors are invalid. */
+size_t toma_workspace_bytes(const toma_desc *desc, const toma_attn_desc *attn);
+
+/* Static string naming a status. */
+const char *toma_status_string(int status);
+
+/*
+ * Destination selection (Sec. 4.1, Alg. 2; per region as in Alg. 3 step 1).
+ * For every (sample, region): S_ij = cos(x_i, x_j) over the region's tokens; first pick = largest
+ * row sum; every later pick maximises sum_j max(0, S_ij - m_j) over tokens not yet picked, with
+ * m_j the largest similarity of token j to the picks so far.  Ties go to the lowest index.
+ * Similarities are evaluated in double precision from the stored token values, rounded once to
+ * single precision, and the sums over them are accumulated in double precision.
+ *   X        in   [B, N, C]         tokens (dtype)
+ *   idx      out  [B, P, d_loc]     int32 grid index of each pick, in pick order
+ *   gain_opt out  [B, P, d_loc]     float value of each winning candidate, or NULL
+ */
+int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt, void *ws,
+                size_t ws_bytes, void *stream);
+
+/*
+ * Merge weights and merge (Sec. 4.2.1; Alg. 3 step 2).  Inside each merge region (all tokens
+ * of the sample, or one region) with destinations j = rows idx of X and sources s:
+ *   A_js = softmax over j of (logit_scale * <x_idx[j], x_s>)   per source s,
+ *   Z_j  = sum_s A_js,   Xm_j = (1 / Z_j) * sum_s A_js x_s          (A~ = A / Z, Xm = A~ X)
+ * Z_j is clamped below at 1e-20.  A is stored in dtype; Z sums the stored values of A.
+ *   idx  in   [B, P, d_loc]             destinations (from toma_select or a cache)
+ *   A    out  [B, R, D/R, N/R] dtype    R = merge_regions; sources of a region in local order
+ *   Z    out  [B, D] float
+ *   Xm   out  [B, D, C] dtype           merged tokens, rows in idx order
+ * (A, Z) is the cache that toma_merge_cached / toma_unmerge take; treat it as opaque.
+ */
+int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx, void *A, float *Z,
+               void *Xm, void *ws, size_t ws_bytes, void *stream);
+
+/* Merge with cached weights (Sec. 4.3.2): Xm = (A / Z) X for the CURRENT X and an (A, Z) computed
+ * earlier by toma_merge with the same descriptor. */
+int toma_merge_cached(const toma_desc *desc, const void *X, const void *A, const float *Z,
+                      void *Xm, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Attention on the merged tokens (Eq. 1 with tau = 1; Alg. 3 "computational layer").
+ * U = [Xm ; X_extra] (L = D + t_extra rows per sample); Q = U Wq, K = U Wk, V = U Wv; head h owns
+ * channels [h*head_dim, (h+1)*head_dim); O_h = softmax(Q_h K_h^T / sqrt(head_dim)) V_h; heads are
+ * concatenated; O = O Wo when Wo_opt is given.  Weights are [C, C] row-major, y = x W.
+ *   Xm          in   [B, D, C]
+ *   X_extra_opt in   [B, t_extra, C] (NULL iff t_extra == 0)
+ *   O           out  [B, D + t_extra, C]
+ */
+int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *Xm,
+                const void *X_extra_opt, const void *Wq, const void *Wk, const void *Wv,
+                const void *Wo_opt, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Transpose unmerge (Sec. 4.2.2; Alg. 3 step 3): Y[token(s)] = sum_j (A_js / Z_j) O_j for every
+ * source s, written at the token's grid position (the region split is undone by addressing).
+ *   O  in   [B, o_rows, C]   o_rows >= D; only rows [0, D) of each sample are read
+ *   Y  out  [B, N, C]
+ */
+int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *O,
+                 int32_t o_rows, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One whole layer with pattern reuse (Alg. 3 + Sec. 4.3.2).  reuse_flags says what is taken from
+ * the caller's cache instead of being recomputed from X:
+ *   0                  select, weights, merge, attention, unmerge; idx, A, Z are written
+ *   TOMA_REUSE_IDX     idx is read; weights are recomputed; A, Z are written
+ *   TOMA_REUSE_A       idx is ignored, A and Z are read (implies TOMA_REUSE_IDX)
+ *   Y            out  [B, N, C]
+ *   Y_extra_opt  out  [B, t_extra, C]  rows of O that belong to the extra tokens (NULL iff none)
+ */
+enum { TOMA_REUSE_IDX = 1, TOMA_REUSE_A = 2 };
+int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse_flags,
+               const void *X, const void *X_extra_opt, int32_t *idx, void *A, float *Z,
+               const void *Wq, const void *Wk, const void *Wv, const void *Wo_opt, void *Y,
+               void *Y_extra_opt, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Profiling aid for benchmarks (not part of the method; for callers that want per-kernel times).
+ * While enabled, every kernel the library launches is bracketed by two HIP events recorded on the
+ * launch stream (this is the one place where the library creates HIP objects: events, kept in a
+ * pool until the process ends).  toma_profile_read waits for the recorded events of all kernels,
+ * then returns and clears the launch count and summed duration (ms) of the named kernel.
+ * toma_profile_kernel_name(i) enumerates the names (NULL past the last).  Enabling or disabling
+ * clears all totals.  Not meant to be enabled under HIP graph capture.
+ */
+int toma_profile_enable(int on);
+const char *toma_profile_kernel_name(int i);
+int toma_profile_read(const char *kernel, int32_t *launches, float *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOMA_H */

@@ -25,15 +25,16 @@
 /* Shape of one layer call.  N = H*W tokens on a row-major H x W grid; regions are tile_h x tile_w
  * windows (a stripe region is tile_h rows by W columns).  merge_regions is 1 (merge weights over
  * all tokens: the variant the paper calls ToMA) or P (weights inside each region: ToMA_tile,
- * Alg. 3).  sim_fp32 != 0 rounds every similarity S_ij to IEEE single before the greedy
- * decisions are taken: it names the precision in which the argmax is decided. */
+ * Alg. 3).  sim_bits > 0 rounds every similarity S_ij to the nearest multiple of 2^-sim_bits
+ * before the greedy decisions are taken: it names the precision in which the argmax is decided
+ * (sums of such values are exact in double, so ties are exact ties). */
 typedef struct {
   int32_t B, H, W, C;
   int32_t tile_h, tile_w;
   int32_t d_loc;
   int32_t merge_regions;
   double scale; /* logit multiplier of the merge weights, 1/tau in Sec. 4.2.1's display formula */
-  int32_t sim_fp32;
+  int32_t sim_bits;
 } oracle_desc;
 
 static int n_regions(const oracle_desc *d) { return (d->H / d->tile_h) * (d->W / d->tile_w); }
@@ -59,7 +60,7 @@ ORACLE_API void toma_oracle_region_map(int H, int W, int tile_h, int tile_w, int
 /* Sec. 4.1: S_ij = cos(x_i, x_j) for the n tokens whose rows are listed in rows[] (row stride C).
  * A zero vector gets norm eps = 1e-12 so that its similarities are 0 rather than NaN. */
 ORACLE_API void toma_oracle_cosine(const double *X, const int32_t *rows, int n, int C,
-                                   int round_f32, double *S) {
+                                   int round_bits, double *S) {
   double *nrm = (double *)malloc(sizeof(double) * (size_t)n);
   for (int i = 0; i < n; i++) {
     const double *xi = X + (size_t)rows[i] * C;
@@ -75,7 +76,7 @@ ORACLE_API void toma_oracle_cosine(const double *X, const int32_t *rows, int n, 
       double s = 0.0;
       for (int c = 0; c < C; c++) s += xi[c] * xj[c];
       s = s / (nrm[i] * nrm[j]);
-      S[(size_t)i * n + j] = round_f32 ? (double)(float)s : s;
+      S[(size_t)i * n + j] = round_bits > 0 ? ldexp(nearbyint(ldexp(s, round_bits)), -round_bits) : s;
     }
   }
   free(nrm);
@@ -225,7 +226,7 @@ ORACLE_API void toma_oracle_select(const oracle_desc *d, const double *X, int32_
     int b = bp / P, p = bp % P;
     double *S = (double *)malloc(sizeof(double) * (size_t)nl * nl);
     int32_t *t = (int32_t *)malloc(sizeof(int32_t) * (size_t)k);
-    toma_oracle_cosine(X + (size_t)b * N * d->C, token_of + (size_t)p * nl, nl, d->C, d->sim_fp32, S);
+    toma_oracle_cosine(X + (size_t)b * N * d->C, token_of + (size_t)p * nl, nl, d->C, d->sim_bits, S);
     toma_oracle_greedy_fl(S, nl, k, t, gain ? gain + (size_t)bp * k : NULL,
                           gap ? gap + (size_t)bp * k : NULL);
     for (int q = 0; q < k; q++) idx[(size_t)bp * k + q] = token_of[(size_t)p * nl + t[q]];

@@ -19,7 +19,7 @@ class OracleDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
                 ("C", ctypes.c_int32), ("tile_h", ctypes.c_int32), ("tile_w", ctypes.c_int32),
                 ("d_loc", ctypes.c_int32), ("merge_regions", ctypes.c_int32),
-                ("scale", ctypes.c_double), ("sim_fp32", ctypes.c_int32)]
+                ("scale", ctypes.c_double), ("sim_bits", ctypes.c_int32)]
 
 
 def lib():
@@ -47,7 +47,10 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
-def make_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, sim_fp32=True, scale=None):
+SIM_BITS = 25  # similarities are decided on a 2^-25 grid (see toma_oracle.c)
+
+
+def make_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, sim_bits=SIM_BITS, scale=None):
     if H % tile_h or W % tile_w:
         raise ValueError("tiles must divide the grid")
     P = (H // tile_h) * (W // tile_w)
@@ -56,7 +59,7 @@ def make_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, sim_fp32=Tr
     if not 1 <= d_loc <= tile_h * tile_w:
         raise ValueError("d_loc out of range")
     return OracleDesc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions,
-                      float(scale if scale is not None else 1.0 / tau), 1 if sim_fp32 else 0)
+                      float(scale if scale is not None else 1.0 / tau), int(sim_bits))
 
 
 def n_regions(d):
@@ -73,12 +76,12 @@ def region_map(H, W, tile_h, tile_w):
     return region, local, token_of.reshape(P, tile_h * tile_w)
 
 
-def cosine(X, round_f32=False):
+def cosine(X, round_bits=0):
     X = _f64(X)
     n, C = X.shape
     rows = np.arange(n, dtype=np.int32)
     S = np.empty((n, n), np.float64)
-    lib().toma_oracle_cosine(_d(X), _i(rows), n, C, 1 if round_f32 else 0, _d(S))
+    lib().toma_oracle_cosine(_d(X), _i(rows), n, C, int(round_bits), _d(S))
     return S
 
 

@@ -1,0 +1,203 @@
+// C-ABI entry points of libtoma: argument checks on the host, workspace layout, stage launches.
+#include <math.h>
+
+#include "toma_internal.h"
+
+namespace toma {
+
+static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s) {
+  if (!d) return TOMA_ERR_NULL;
+  if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->tile_h <= 0 || d->tile_w <= 0 || d->d_loc <= 0)
+    return TOMA_ERR_SHAPE;
+  if (d->H % d->tile_h || d->W % d->tile_w) return TOMA_ERR_SHAPE;
+  if (!(d->tau > 0.0f) || !isfinite(d->tau) || !isfinite(d->logit_scale) || d->logit_scale < 0.0f)
+    return TOMA_ERR_SHAPE;
+  if (d->dtype != TOMA_F32 && d->dtype != TOMA_BF16) return TOMA_ERR_UNSUPPORTED;
+  s->B = d->B; s->H = d->H; s->W = d->W; s->C = d->C;
+  s->tile_h = d->tile_h; s->tile_w = d->tile_w; s->d_loc = d->d_loc;
+  s->N = d->H * d->W;
+  s->P = (d->H / d->tile_h) * (d->W / d->tile_w);
+  s->n_loc = d->tile_h * d->tile_w;
+  if (d->d_loc > s->n_loc) return TOMA_ERR_SHAPE;
+  if (d->merge_regions != 1 && d->merge_regions != s->P) return TOMA_ERR_SHAPE;
+  if (d->C % 32) return TOMA_ERR_UNSUPPORTED;
+  if (s->n_loc % 16 || s->n_loc > 256) return TOMA_ERR_UNSUPPORTED;
+  if ((long long)d->B * s->N * d->C >= (1ll << 40)) return TOMA_ERR_UNSUPPORTED;
+  s->R = d->merge_regions;
+  s->D = s->P * d->d_loc;
+  s->Nr = s->N / s->R;
+  s->Dr = s->D / s->R;
+  s->scale = d->logit_scale > 0.0f ? d->logit_scale : 1.0f / d->tau;
+  s->dtype = d->dtype;
+  s->heads = s->head_dim = s->T = s->L = 0;
+  if (a) {
+    if (a->heads <= 0 || a->head_dim <= 0 || a->t_extra < 0) return TOMA_ERR_SHAPE;
+    if ((long long)a->heads * a->head_dim != d->C) return TOMA_ERR_SHAPE;
+    if (a->head_dim != 32 && a->head_dim != 64 && a->head_dim != 128) return TOMA_ERR_UNSUPPORTED;
+    s->heads = a->heads; s->head_dim = a->head_dim; s->T = a->t_extra; s->L = s->D + a->t_extra;
+  }
+  return TOMA_OK;
+}
+
+void plan_workspace(const Shape &s, Workspace *w) {
+  size_t es = s.dtype == TOMA_BF16 ? 2 : 4;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+  w->stat_parts = 2 * ((s.Dr + kGemmTile - 1) / kGemmTile);
+  w->z_parts = 2 * ((s.Nr + kGemmTile - 1) / kGemmTile);
+  w->nrm = take((size_t)s.B * s.N * sizeof(double));
+  w->sim = take((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(float));
+  w->stats = take((size_t)s.B * s.N * w->stat_parts * 2 * sizeof(float));
+  w->lse = take((size_t)s.B * s.N * sizeof(float));
+  w->zpart = take((size_t)s.B * s.D * w->z_parts * sizeof(float));
+  w->os = take((size_t)s.B * s.D * s.C * es);
+  size_t qkv = (size_t)s.B * s.L * s.C * es;
+  w->q = take(qkv); w->k = take(qkv); w->v = take(qkv); w->oh = take(qkv);
+  w->xm = take((size_t)s.B * s.D * s.C * es);  // merged tokens and attention output of toma_layer
+  w->o = take(qkv);
+  w->total = off;
+}
+
+static bool misaligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+// Shared prologue of every call: shape, workspace size and alignment.
+static int prepare(const toma_desc *d, const toma_attn_desc *a, void *ws, size_t ws_bytes, Shape *s, Workspace *w) {
+  int rc = make_shape(d, a, s);
+  if (rc != TOMA_OK) return rc;
+  plan_workspace(*s, w);
+  if (!ws) return TOMA_ERR_NULL;
+  if (misaligned(ws, 256)) return TOMA_ERR_ALIGN;
+  if (ws_bytes < w->total) return TOMA_ERR_WORKSPACE;
+  return TOMA_OK;
+}
+
+}  // namespace toma
+
+using namespace toma;
+
+#define TOMA_API extern "C" __attribute__((visibility("default")))
+
+TOMA_API size_t toma_workspace_bytes(const toma_desc *desc, const toma_attn_desc *attn) {
+  Shape s;
+  Workspace w;
+  if (make_shape(desc, attn, &s) != TOMA_OK) return 0;
+  plan_workspace(s, &w);
+  return w.total;
+}
+
+TOMA_API const char *toma_status_string(int status) {
+  switch (status) {
+    case TOMA_OK: return "ok";
+    case TOMA_ERR_NULL: return "null pointer";
+    case TOMA_ERR_SHAPE: return "invalid shape";
+    case TOMA_ERR_ALIGN: return "misaligned pointer";
+    case TOMA_ERR_WORKSPACE: return "workspace too small";
+    case TOMA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case TOMA_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+TOMA_API int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt, void *ws,
+                         size_t ws_bytes, void *stream) {
+  Shape s; Workspace w;
+  int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!X || !idx) return TOMA_ERR_NULL;
+  if (misaligned(X, 16) || misaligned(idx, 4) || (gain_opt && misaligned(gain_opt, 4))) return TOMA_ERR_ALIGN;
+  return launch_select(s, X, idx, gain_opt, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+}
+
+TOMA_API int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx, void *A, float *Z, void *Xm,
+                        void *ws, size_t ws_bytes, void *stream) {
+  Shape s; Workspace w;
+  int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!X || !idx || !A || !Z || !Xm) return TOMA_ERR_NULL;
+  if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Xm, 16) || misaligned(Z, 4) || misaligned(idx, 4))
+    return TOMA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  rc = launch_weights(s, X, idx, A, Z, static_cast<char *>(ws), w, st);
+  if (rc != TOMA_OK) return rc;
+  return launch_merge(s, X, A, Z, Xm, st);
+}
+
+TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void *A, const float *Z, void *Xm,
+                               void *ws, size_t ws_bytes, void *stream) {
+  Shape s; Workspace w;
+  int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!X || !A || !Z || !Xm) return TOMA_ERR_NULL;
+  if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Xm, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
+  return launch_merge(s, X, A, Z, Xm, static_cast<hipStream_t>(stream));
+}
+
+TOMA_API int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *Xm,
+                         const void *X_extra_opt, const void *Wq, const void *Wk, const void *Wv,
+                         const void *Wo_opt, void *O, void *ws, size_t ws_bytes, void *stream) {
+  if (!attn) return TOMA_ERR_NULL;
+  Shape s; Workspace w;
+  int rc = prepare(desc, attn, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!Xm || !Wq || !Wk || !Wv || !O) return TOMA_ERR_NULL;
+  if ((s.T > 0) != (X_extra_opt != nullptr)) return TOMA_ERR_NULL;
+  if (misaligned(Xm, 16) || misaligned(Wq, 16) || misaligned(Wk, 16) || misaligned(Wv, 16) || misaligned(O, 16) ||
+      (X_extra_opt && misaligned(X_extra_opt, 16)) || (Wo_opt && misaligned(Wo_opt, 16)))
+    return TOMA_ERR_ALIGN;
+  return launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, static_cast<char *>(ws), w,
+                       static_cast<hipStream_t>(stream));
+}
+
+TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *O, int32_t o_rows,
+                          void *Y, void *ws, size_t ws_bytes, void *stream) {
+  Shape s; Workspace w;
+  int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!A || !Z || !O || !Y) return TOMA_ERR_NULL;
+  if (o_rows < s.D) return TOMA_ERR_SHAPE;
+  if (misaligned(A, 16) || misaligned(O, 16) || misaligned(Y, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
+  return launch_unmerge(s, A, Z, O, o_rows, Y, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+}
+
+TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse_flags, const void *X,
+                        const void *X_extra_opt, int32_t *idx, void *A, float *Z, const void *Wq,
+                        const void *Wk, const void *Wv, const void *Wo_opt, void *Y, void *Y_extra_opt,
+                        void *ws, size_t ws_bytes, void *stream) {
+  if (!attn) return TOMA_ERR_NULL;
+  Shape s; Workspace w;
+  int rc = prepare(desc, attn, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (reuse_flags & ~(uint32_t)(TOMA_REUSE_IDX | TOMA_REUSE_A)) return TOMA_ERR_UNSUPPORTED;
+  const bool reuse_a = (reuse_flags & TOMA_REUSE_A) != 0;
+  const bool reuse_idx = reuse_a || (reuse_flags & TOMA_REUSE_IDX) != 0;
+  if (!X || !A || !Z || !Wq || !Wk || !Wv || !Y) return TOMA_ERR_NULL;
+  if (!reuse_a && !idx) return TOMA_ERR_NULL;
+  if ((s.T > 0) != (X_extra_opt != nullptr) || (s.T > 0) != (Y_extra_opt != nullptr)) return TOMA_ERR_NULL;
+  if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Y, 16) || misaligned(Z, 4) || misaligned(Wq, 16) ||
+      misaligned(Wk, 16) || misaligned(Wv, 16) || (idx && misaligned(idx, 4)) ||
+      (X_extra_opt && misaligned(X_extra_opt, 16)) || (Y_extra_opt && misaligned(Y_extra_opt, 16)) ||
+      (Wo_opt && misaligned(Wo_opt, 16)))
+    return TOMA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char *wsb = static_cast<char *>(ws);
+  // Xm and O are internal to the layer and live in their own workspace sections.
+  void *Xm = wsb + w.xm, *O = wsb + w.o;
+  if (!reuse_idx) {
+    rc = launch_select(s, X, idx, nullptr, wsb, w, st);
+    if (rc != TOMA_OK) return rc;
+  }
+  if (!reuse_a) {
+    rc = launch_weights(s, X, idx, A, Z, wsb, w, st);
+    if (rc != TOMA_OK) return rc;
+  }
+  rc = launch_merge(s, X, A, Z, Xm, st);
+  if (rc != TOMA_OK) return rc;
+  rc = launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, wsb, w, st);
+  if (rc != TOMA_OK) return rc;
+  rc = launch_unmerge(s, A, Z, O, s.L, Y, wsb, w, st);
+  if (rc != TOMA_OK) return rc;
+  if (s.T > 0) rc = launch_copy_extra(s, O, Y_extra_opt, st);
+  return rc;
+}

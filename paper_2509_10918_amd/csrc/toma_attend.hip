@@ -1,0 +1,275 @@
+// The core module on the merged tokens: multi-head scaled dot-product attention (paper Eq. 1 with
+// tau = 1; Alg. 3 "computational layer"), on U = [X_merged ; X_extra].
+//
+//   k_gemm<QkvPol>   Q, K, V = U W  (one launch, blockIdx.z picks the weight), written head-major
+//                    [B][heads][L][head_dim] so that every head is a dense matrix.
+//   k_attn           flash-style attention: 128 queries per workgroup (32 per wave), 64 keys per
+//                    step through LDS, online softmax, nothing of size L x L ever stored.
+//                    The score tile is computed TRANSPOSED (keys x queries): its accumulator
+//                    layout (lane = query, registers = 4 consecutive keys) is then already the
+//                    B-operand layout of the second product O^T += V^T P^T, so probabilities go
+//                    from accumulators straight back into the matrix cores without touching LDS.
+//                    V^T fragments come from the row-major V tile through the LDS transpose read.
+//   k_gemm<ProjPol>  optional output projection.
+#include "toma_gemm.h"
+#include "toma_internal.h"
+
+namespace toma {
+
+template <typename T> struct QkvPol {
+  static constexpr bool A_KS = false, B_KS = true;
+  const T *Xm, *Xe;
+  const T *W[3];
+  T *out[3];
+  int B, D, Tx, L, C, H, dh;
+  __device__ __forceinline__ GemmCtx setup(int bz) const { return GemmCtx{B * L, C, C, 0, 0, bz}; }
+  __device__ __forceinline__ const T *a_ptr(const GemmCtx &, int m, int k) const {
+    int b = m / L, l = m % L;
+    return l < D ? Xm + ((size_t)b * D + l) * C + k : Xe + ((size_t)b * Tx + (l - D)) * C + k;
+  }
+  __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
+    return W[x.z] + (size_t)k * C + n;
+  }
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAcc &acc, int m_w, int n_w, int lane) const {
+    T *o = out[x.z];
+    const int L_ = L, H_ = H, dh_ = dh;
+    store_rows<T>(acc, m_w, n_w, lane, x.M, x.N,
+                  [=](int m, int n) {
+                    int b = m / L_, l = m % L_, h = n / dh_, dd = n % dh_;
+                    return o + (((size_t)b * H_ + h) * L_ + l) * dh_ + dd;
+                  },
+                  [](int) { return 1.0f; });
+  }
+};
+
+template <typename T> struct ProjPol {
+  static constexpr bool A_KS = false, B_KS = true;
+  const T *In, *Wt;
+  T *Out;
+  int rows, C;
+  __device__ __forceinline__ GemmCtx setup(int) const { return GemmCtx{rows, C, C, 0, 0, 0}; }
+  __device__ __forceinline__ const T *a_ptr(const GemmCtx &, int m, int k) const { return In + (size_t)m * C + k; }
+  __device__ __forceinline__ const T *b_ptr(const GemmCtx &, int n, int k) const { return Wt + (size_t)k * C + n; }
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAcc &acc, int m_w, int n_w, int lane) const {
+    T *o = Out;
+    const int C_ = C;
+    store_rows<T>(acc, m_w, n_w, lane, x.M, x.N, [=](int m, int n) { return o + (size_t)m * C_ + n; },
+                  [](int) { return 1.0f; });
+  }
+};
+
+// Probabilities (fp32 accumulator registers) -> B-operand fragment slots.
+__device__ __forceinline__ void pack_probs(Frag<bf16_t> &f, const f32x4 &lo, const f32x4 &hi) {
+#pragma unroll
+  for (int r = 0; r < 4; r++) { f.v[r] = (bf16_t)lo[r]; f.v[4 + r] = (bf16_t)hi[r]; }
+}
+__device__ __forceinline__ void pack_probs(Frag<float> &f, const f32x4 &lo, const f32x4 &hi) {
+#pragma unroll
+  for (int r = 0; r < 4; r++) { f.v[r] = lo[r]; f.v[4 + r] = hi[r]; }
+}
+
+template <typename T, int DH>
+__global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *__restrict__ Kx,
+                                             const T *__restrict__ V, T *__restrict__ O, int L, int H,
+                                             float scale_log2) {
+  constexpr int EPP = 16 / (int)sizeof(T);
+  constexpr int LD = DH + EPP;        // LDS row stride (elements) of the K and V tiles [64][DH]
+  constexpr int KK = DH / 32;         // fragments along head_dim
+  constexpr int DT = DH / 16;         // output tiles along head_dim
+  constexpr int QT = 2;               // query tiles (of 16) per wave
+  constexpr int NP = 64 * DH / EPP / 256;
+  __shared__ __align__(16) T Ks[64 * LD];
+  __shared__ __align__(16) T Vs[64 * LD];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const size_t head = ((size_t)b * H + h) * L * DH;
+  const T *Qh = Q + head, *Kh = Kx + head, *Vh = V + head;
+  const int q_w = blockIdx.x * 128 + w * 32;
+
+  // queries as B-operand fragments: lane = query column, slots = head_dim 32 kk + 8 g + i
+  Frag<T> fq[QT][KK];
+#pragma unroll
+  for (int qt = 0; qt < QT; qt++) {
+    int q = q_w + 16 * qt + c;
+    q = q < L ? q : L - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) {
+      const T *src = Qh + (size_t)q * DH + 32 * kk + 8 * g;
+      if constexpr (sizeof(T) == 2) {
+        Pkt pk = pkt_load(src);
+        fq[qt][kk] = __builtin_bit_cast(Frag<T>, pk);
+      } else {
+        Pkt p0 = pkt_load(src), p1 = pkt_load(src + 4);
+        struct { Pkt a, b; } two = {p0, p1};
+        fq[qt][kk] = __builtin_bit_cast(Frag<T>, two);
+      }
+    }
+  }
+
+  f32x4 oacc[DT][QT];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) oacc[dt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; qt++) { m_run[qt] = -__builtin_inff(); l_run[qt] = 0.f; }
+
+  int lds_off[NP], g_row[NP], g_col[NP];
+#pragma unroll
+  for (int i = 0; i < NP; i++) {
+    int q = tid + 256 * i;
+    constexpr int PPR = DH / EPP;
+    g_row[i] = q / PPR; g_col[i] = (q % PPR) * EPP;
+    lds_off[i] = g_row[i] * LD + g_col[i];
+  }
+
+  Pkt rk[NP], rv[NP];
+  auto fetch = [&](int key0) {
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+      int key = key0 + g_row[i];
+      key = key < L ? key : L - 1;  // rows past the end are masked below
+      rk[i] = pkt_load(Kh + (size_t)key * DH + g_col[i]);
+      rv[i] = pkt_load(Vh + (size_t)key * DH + g_col[i]);
+    }
+  };
+
+  fetch(0);
+  for (int key0 = 0; key0 < L; key0 += 64) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NP; i++) { pkt_store(Ks + lds_off[i], rk[i]); pkt_store(Vs + lds_off[i], rv[i]); }
+    __syncthreads();
+    if (key0 + 64 < L) fetch(key0 + 64);
+
+    // transposed scores: st[kt][qt] holds keys 16 kt + 4 g + r (rows) of query c (column)
+    f32x4 st[4][QT];
+#pragma unroll
+    for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+      for (int qt = 0; qt < QT; qt++) st[kt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++)
+#pragma unroll
+      for (int kt = 0; kt < 4; kt++) {
+        Frag<T> fk;
+        frag_load_kc(fk, Ks + (16 * kt + c) * LD + 32 * kk + 8 * g);
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) mma16(st[kt][qt], fk, fq[qt][kk]);
+      }
+
+    const bool tail = key0 + 64 > L;
+    Frag<T> fp[QT][2];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+      float mx = -__builtin_inff();
+#pragma unroll
+      for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          float sv = st[kt][qt][r] * scale_log2;
+          if (tail && key0 + 16 * kt + 4 * g + r >= L) sv = -__builtin_inff();
+          st[kt][qt][r] = sv;
+          mx = fmaxf(mx, sv);
+        }
+      mx = fmaxf(mx, wave_xor_f32(mx, 16));
+      mx = fmaxf(mx, wave_xor_f32(mx, 32));
+      float m_new = fmaxf(m_run[qt], mx);
+      float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+      m_run[qt] = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          float pv = __builtin_amdgcn_exp2f(st[kt][qt][r] - m_new);
+          st[kt][qt][r] = pv;
+          psum += pv;
+        }
+      l_run[qt] = l_run[qt] * alpha + psum;
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) oacc[dt][qt][r] *= alpha;
+      pack_probs(fp[qt][0], st[0][qt], st[1][qt]);
+      pack_probs(fp[qt][1], st[2][qt], st[3][qt]);
+    }
+
+    // O^T[dh][q] += sum_keys V[key][dh] P^T[key][q]; slot s of k-group g is key 32 u + 4 g + s
+    // (s < 4) or 32 u + 16 + 4 g + s - 4, matching how the probabilities were packed.
+#pragma unroll
+    for (int u = 0; u < 2; u++)
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++) {
+        Frag<T> fv;
+        frag_load_ks(fv, Vs, LD, 32 * u + 4 * g, 32 * u + 16 + 4 * g, 16 * dt, lane);
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) mma16(oacc[dt][qt], fv, fp[qt][u]);
+      }
+  }
+
+  // O[b][q][h * DH + dh]: lane holds query c and head_dim rows 16 dt + 4 g + r
+  const int Cw = H * DH;
+#pragma unroll
+  for (int qt = 0; qt < QT; qt++) {
+    float l = l_run[qt];
+    l += wave_xor_f32(l, 16);
+    l += wave_xor_f32(l, 32);
+    float inv = 1.0f / l;
+    int q = q_w + 16 * qt + c;
+    if (q >= L) continue;
+    T *dst = O + ((size_t)b * L + q) * Cw + h * DH + 4 * g;
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) {
+      alignas(16) T o[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++) o[r] = from_f32<T>(oacc[dt][qt][r] * inv);
+      if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst + 16 * dt) = *reinterpret_cast<u32x2 *>(o);
+      else *reinterpret_cast<u32x4 *>(dst + 16 * dt) = *reinterpret_cast<u32x4 *>(o);
+    }
+  }
+}
+
+template <typename T, int DH>
+static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, hipStream_t st) {
+  float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  dim3 grid((s.L + 127) / 128, s.heads, s.B);
+  KernelTimer kt(K_ATTN, st);
+  hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2);
+}
+
+template <typename T>
+static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
+                        const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w, hipStream_t st) {
+  T *Q = reinterpret_cast<T *>(ws + w.q), *K = reinterpret_cast<T *>(ws + w.k), *V = reinterpret_cast<T *>(ws + w.v);
+  QkvPol<T> p{};
+  p.Xm = static_cast<const T *>(Xm); p.Xe = static_cast<const T *>(Xe);
+  p.W[0] = static_cast<const T *>(Wq); p.W[1] = static_cast<const T *>(Wk); p.W[2] = static_cast<const T *>(Wv);
+  p.out[0] = Q; p.out[1] = K; p.out[2] = V;
+  p.B = s.B; p.D = s.D; p.Tx = s.T; p.L = s.L; p.C = s.C; p.H = s.heads; p.dh = s.head_dim;
+  launch_gemm<T>(K_QKV, p, s.B * s.L, s.C, 3, st);
+  T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
+  switch (s.head_dim) {
+    case 32: launch_attn<T, 32>(s, Q, K, V, Oh, st); break;
+    case 64: launch_attn<T, 64>(s, Q, K, V, Oh, st); break;
+    case 128: launch_attn<T, 128>(s, Q, K, V, Oh, st); break;
+    default: return TOMA_ERR_UNSUPPORTED;
+  }
+  if (Wo) {
+    ProjPol<T> pp{};
+    pp.In = Oh; pp.Wt = static_cast<const T *>(Wo); pp.Out = static_cast<T *>(O);
+    pp.rows = s.B * s.L; pp.C = s.C;
+    launch_gemm<T>(K_PROJ, pp, s.B * s.L, s.C, 1, st);
+  }
+  return launch_status();
+}
+
+int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
+                  const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w, hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? attend_typed<bf16_t>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, ws, w, st)
+                              : attend_typed<float>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, ws, w, st);
+}
+
+}  // namespace toma

@@ -1,0 +1,85 @@
+// Profiling aid: per-kernel HIP-event timing of the library's own launches (see toma.h).
+#include <mutex>
+#include <string.h>
+#include <vector>
+
+#include "toma_internal.h"
+
+namespace toma {
+
+static const char *const kNames[K_COUNT] = {"norms", "gram", "greedy", "weights_stats", "lse", "weights_write",
+                                            "zsum", "merge", "qkv", "attention", "proj", "scale_rows",
+                                            "unmerge", "copy_extra"};
+struct Rec { int id; hipEvent_t a, b; };
+static std::mutex g_mu;
+static bool g_on = false;
+static std::vector<Rec> g_recs;
+static std::vector<hipEvent_t> g_pool;
+static int g_launches[K_COUNT];
+static double g_ms[K_COUNT];
+
+static hipEvent_t take_event() {
+  if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+KernelTimer::KernelTimer(int id, hipStream_t s) : slot(-1), st(s) {
+  if (!g_on) return;
+  std::lock_guard<std::mutex> lk(g_mu);
+  Rec r{id, take_event(), take_event()};
+  if (!r.a || !r.b) return;
+  (void)hipEventRecord(r.a, st);
+  g_recs.push_back(r);
+  slot = (int)g_recs.size() - 1;
+}
+
+KernelTimer::~KernelTimer() {
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (slot < (int)g_recs.size()) (void)hipEventRecord(g_recs[slot].b, st);
+}
+
+static void collect() {
+  for (const Rec &r : g_recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+      g_launches[r.id]++;
+      g_ms[r.id] += ms;
+    }
+    g_pool.push_back(r.a);
+    g_pool.push_back(r.b);
+  }
+  g_recs.clear();
+}
+
+}  // namespace toma
+
+using namespace toma;
+#define TOMA_API extern "C" __attribute__((visibility("default")))
+
+TOMA_API int toma_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  collect();
+  g_on = on != 0;
+  for (int i = 0; i < K_COUNT; i++) { g_launches[i] = 0; g_ms[i] = 0.0; }
+  return TOMA_OK;
+}
+
+TOMA_API const char *toma_profile_kernel_name(int i) { return (i >= 0 && i < K_COUNT) ? kNames[i] : nullptr; }
+
+TOMA_API int toma_profile_read(const char *kernel, int32_t *launches, float *total_ms) {
+  if (!kernel || !launches || !total_ms) return TOMA_ERR_NULL;
+  std::lock_guard<std::mutex> lk(g_mu);
+  collect();
+  for (int i = 0; i < K_COUNT; i++)
+    if (strcmp(kernel, kNames[i]) == 0) {
+      *launches = g_launches[i];
+      *total_ms = (float)g_ms[i];
+      g_launches[i] = 0;
+      g_ms[i] = 0.0;
+      return TOMA_OK;
+    }
+  return TOMA_ERR_UNSUPPORTED;
+}

@@ -1,0 +1,85 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, and turns bad arguments into status codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_10918_amd import binding as tb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "toma.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(toma_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = _declared()
+    assert sorted(names) == sorted(tb.EXPORTS)
+    L = tb.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    assert tb.status_string(0) == "ok"
+    assert len({tb.status_string(i) for i in range(7)}) == 7
+
+
+def _d(**kw):
+    base = dict(B=2, H=64, W=64, C=640, tile_h=16, tile_w=16, d_loc=128, merge_regions=1, tau=0.1, dtype="bf16")
+    base.update(kw)
+    return tb.make_desc(**base)
+
+
+def test_workspace_bytes_and_shape_errors():
+    a = tb.toma_attn_desc(10, 64, 0)
+    n = tb.toma_workspace_bytes(_d(), a)
+    assert n > 0 and n % 256 == 0
+    assert tb.toma_workspace_bytes(_d(), None) > 0
+    assert tb.toma_workspace_bytes(_d(tile_h=15), a) == 0          # does not divide the grid
+    assert tb.toma_workspace_bytes(_d(d_loc=257), a) == 0           # more destinations than tokens
+    assert tb.toma_workspace_bytes(_d(merge_regions=4), a) == 0     # neither 1 nor P
+    assert tb.toma_workspace_bytes(_d(C=650), a) == 0               # width not a multiple of 32
+    assert tb.toma_workspace_bytes(_d(tile_h=32, tile_w=32), a) == 0  # region larger than 256 tokens
+    assert tb.toma_workspace_bytes(_d(tau=0.0), a) == 0
+    assert tb.toma_workspace_bytes(_d(), tb.toma_attn_desc(10, 32, 0)) == 0   # heads * head_dim != C
+    assert tb.toma_workspace_bytes(None, None) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = tb.lib()
+    d = _d()
+    a = tb.toma_attn_desc(10, 64, 0)
+    dp, ap = ctypes.addressof(d), ctypes.addressof(a)
+    need = tb.toma_workspace_bytes(d, a)
+    ws = 256 * 1024          # fake but aligned addresses: nothing is dereferenced on these paths
+    x = 1 << 20
+    assert L.toma_select(None, x, x, None, ws, need, None) == 1
+    assert L.toma_select(dp, None, x, None, ws, need, None) == 1
+    assert L.toma_select(dp, x, x, None, None, need, None) == 1
+    assert L.toma_select(dp, x, x, None, ws + 16, need, None) == 3
+    assert L.toma_select(dp, x + 8, x, None, ws, need, None) == 3
+    assert L.toma_select(dp, x, x, None, ws, tb.toma_workspace_bytes(d, None) - 1, None) == 4
+    assert L.toma_layer(dp, ap, 0, x, None, x, x, x, x, x, x, None, x, None, ws, need - 1, None) == 4
+    bad = _d(tile_w=48)
+    assert L.toma_select(ctypes.addressof(bad), x, x, None, ws, need, None) == 2
+    big = _d(tile_h=32, tile_w=32, d_loc=512)
+    assert L.toma_select(ctypes.addressof(big), x, x, None, ws, need, None) == 5
+    assert L.toma_merge(dp, x, x, None, x, x, ws, need, None) == 1
+    assert L.toma_merge_cached(dp, x, x, x, None, ws, need, None) == 1
+    assert L.toma_attend(dp, None, x, None, x, x, x, None, x, ws, need, None) == 1
+    assert L.toma_attend(dp, ap, x, x, x, x, x, None, x, ws, need, None) == 1   # extra tokens given, t_extra == 0
+    assert L.toma_unmerge(dp, x, x, x, 100, x, ws, need, None) == 2             # fewer rows than D
+    assert L.toma_layer(dp, ap, 4, x, None, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
+    assert L.toma_layer(dp, ap, 0, x, None, None, x, x, x, x, x, None, x, None, ws, need, None) == 1
+
+
+def test_binding_raises_with_status():
+    with pytest.raises(tb.TomaError) as e:
+        tb._check(4, "toma_select")
+    assert e.value.status == 4 and "workspace" in str(e.value)

@@ -48,15 +48,16 @@ def test_cosine_matches_numpy(oracle):
     assert np.array_equal(S, S.T)
 
 
-def test_cosine_zero_vector_and_fp32_rounding(oracle):
+def test_cosine_zero_vector_and_grid_rounding(oracle):
     rng = np.random.default_rng(2)
     X = rng.standard_normal((6, 5))
     X[3] = 0.0
     S = oracle.cosine(X)
     assert np.all(S[3] == 0.0) and np.all(S[:, 3] == 0.0) and np.all(np.isfinite(S))
-    S32 = oracle.cosine(X, round_f32=True)
-    assert np.array_equal(S32, S32.astype(np.float32).astype(np.float64))
-    assert np.array_equal(S32, S.astype(np.float32).astype(np.float64))
+    Sq = oracle.cosine(X, round_bits=25)
+    assert np.array_equal(Sq * 2.0 ** 25, np.rint(Sq * 2.0 ** 25))
+    assert np.array_equal(Sq, np.rint(S * 2.0 ** 25) / 2.0 ** 25)
+    assert np.abs(Sq - S).max() <= 2.0 ** -26
 
 
 def test_fl_value_matches_numpy_and_bounds(oracle):
@@ -107,14 +108,14 @@ def test_cached_gain_equals_direct_marginal(oracle):
             assert g1[q] == pytest.approx(_np_fl(S, p1[:q + 1]) - _np_fl(S, p1[:q]), abs=1e-10)
 
 
-def test_structural_ties_resolve_to_lowest_index_in_fp32_decision_precision(oracle):
-    # With similarities rounded to single and values accumulated in double, the sums of a tie's
+def test_structural_ties_resolve_to_lowest_index_in_decision_precision(oracle):
+    # With similarities on a 2^-25 grid and values accumulated in double, the sums of a tie's
     # two sides are exact, so a mathematical tie is an exact tie and the lowest index wins.
     rng = np.random.default_rng(55)
     hits = 0
     for _ in range(20):
         X = rng.standard_normal((40, 6))
-        S = oracle.cosine(X, round_f32=True)
+        S = oracle.cosine(X, round_bits=25)
         picks, gains, gaps = oracle.greedy_fl(S, 30)
         for q in np.nonzero(gaps[:29] == 0.0)[0]:
             _, deficit, first = oracle.check_picks(S, picks[:q + 1])
@@ -214,7 +215,7 @@ def test_select_per_region_matches_single_region_runs(oracle):
     rng = np.random.default_rng(12)
     B, H, W, C, th, tw, k = 2, 8, 12, 5, 4, 6, 7
     X = rng.standard_normal((B, H * W, C))
-    d = oracle.make_desc(B, H, W, C, th, tw, k, 1, 0.1, sim_fp32=False)
+    d = oracle.make_desc(B, H, W, C, th, tw, k, 1, 0.1, sim_bits=0)
     idx, gain, gap = oracle.select(d, X)
     _, _, token_of = oracle.region_map(H, W, th, tw)
     for b in range(B):
@@ -223,8 +224,8 @@ def test_select_per_region_matches_single_region_runs(oracle):
             picks, g, _ = oracle.greedy_fl(S, k)
             assert np.array_equal(idx[b, p], token_of[p][picks])
             assert np.allclose(gain[b, p], g)
-    # decision precision: with sim_fp32 the similarities are rounded to single first
-    d32 = oracle.make_desc(B, H, W, C, th, tw, k, 1, 0.1, sim_fp32=True)
-    idx32, _, _ = oracle.select(d32, X)
-    S32 = oracle.cosine(X[1, token_of[2]], round_f32=True)
-    assert np.array_equal(idx32[1, 2], token_of[2][oracle.greedy_fl(S32, k)[0]])
+    # decision precision: with sim_bits the similarities are rounded to the grid first
+    dq = oracle.make_desc(B, H, W, C, th, tw, k, 1, 0.1, sim_bits=25)
+    idxq, _, _ = oracle.select(dq, X)
+    Sq = oracle.cosine(X[1, token_of[2]], round_bits=25)
+    assert np.array_equal(idxq[1, 2], token_of[2][oracle.greedy_fl(Sq, k)[0]])

@@ -1,0 +1,128 @@
+"""Helpers of the GPU parity tests: move seeded inputs to the device, call libtoma through the
+binding, fetch results as float64 numpy, and compare with the oracle in the benchmark spec's metric."""
+import numpy as np
+import torch
+
+from paper_2509_10918_amd import binding as tb
+from paper_2509_10918_amd import synth
+
+NEAR_TIE = 1e-6     # relative runner-up gap below which a step counts as a near tie
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def dev(a, dtype):
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(tdt).contiguous()
+
+
+def host(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def max_rel(got, ref):
+    """max |got - ref| / max |ref| over the tensor."""
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+def descs(w, merge_regions):
+    d = tb.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, merge_regions, w.tau, w.dtype)
+    a = tb.toma_attn_desc(w.heads, w.head_dim, w.T_extra)
+    return d, a
+
+
+def oracle_desc(oracle, w, merge_regions):
+    return oracle.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, merge_regions, w.tau)
+
+
+class Device:
+    """Device copies of one workload's tensors plus output buffers and workspace."""
+
+    def __init__(self, w, inputs, merge_regions):
+        self.w, self.R = w, merge_regions
+        self.desc, self.attn = descs(w, merge_regions)
+        dt = w.dtype
+        self.X = dev(inputs["X"], dt)
+        self.Xe = dev(inputs["X_extra"], dt) if inputs.get("X_extra") is not None else None
+        self.Wq, self.Wk, self.Wv = (dev(inputs[k], dt) for k in ("Wq", "Wk", "Wv"))
+        self.ws = tb.alloc_workspace(self.desc, self.attn)
+        self.idx, self.A, self.Z = tb.alloc_cache(self.desc)
+        tdt = tb.torch_dtype(self.desc)
+        self.gain = torch.empty((w.B, w.P, w.d_loc), dtype=torch.float32, device="cuda")
+        self.Xm = torch.empty((w.B, w.D, w.C), dtype=tdt, device="cuda")
+        self.O = torch.empty((w.B, w.D + w.T_extra, w.C), dtype=tdt, device="cuda")
+        self.Y = torch.empty((w.B, w.N, w.C), dtype=tdt, device="cuda")
+        self.Ye = torch.empty((w.B, w.T_extra, w.C), dtype=tdt, device="cuda") if w.T_extra else None
+
+    def select(self):
+        tb.toma_select(self.desc, self.X, self.idx, self.gain, self.ws)
+        torch.cuda.synchronize()
+        return self.idx.cpu().numpy()
+
+    def merge(self, idx=None):
+        if idx is not None:
+            self.idx.copy_(torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)))
+        tb.toma_merge(self.desc, self.X, self.idx, self.A, self.Z, self.Xm, self.ws)
+        torch.cuda.synchronize()
+        return host(self.A), host(self.Z), host(self.Xm)
+
+    def merge_cached(self):
+        tb.toma_merge_cached(self.desc, self.X, self.A, self.Z, self.Xm, self.ws)
+        torch.cuda.synchronize()
+        return host(self.Xm)
+
+    def attend(self, Xm=None, Wo=None):
+        if Xm is not None:
+            self.Xm.copy_(dev(Xm, self.w.dtype))
+        tb.toma_attend(self.desc, self.attn, self.Xm, self.Xe, self.Wq, self.Wk, self.Wv, Wo, self.O, self.ws)
+        torch.cuda.synchronize()
+        return host(self.O)
+
+    def unmerge(self, O=None):
+        if O is not None:
+            self.O.copy_(dev(O, self.w.dtype))
+        tb.toma_unmerge(self.desc, self.A, self.Z, self.O, self.Y, self.ws)
+        torch.cuda.synchronize()
+        return host(self.Y)
+
+    def layer(self, flags=0, X=None):
+        if X is not None:
+            self.X.copy_(dev(X, self.w.dtype))
+        tb.toma_layer(self.desc, self.attn, flags, self.X, self.Xe, self.idx, self.A, self.Z, self.Wq, self.Wk,
+                      self.Wv, None, self.Y, self.Ye, self.ws)
+        torch.cuda.synchronize()
+        return host(self.Y), (host(self.Ye) if self.Ye is not None else None)
+
+
+def compare_picks(oracle, w, X, idx_gpu):
+    """Exact index parity, region by region.  A region whose picks differ from the oracle's is
+    excused only if the first difference is at a step the oracle flags as a near tie, and every
+    later pick is then verified teacher-forced (it must be a maximiser, to the same tolerance,
+    given the GPU's own prefix).  Returns (mismatching regions, near-tie steps, checked regions)."""
+    d = oracle_desc(oracle, w, 1)
+    idx_ref, gain, gap = oracle.select(d, X)
+    rel_gap = gap / np.maximum(gain, 1e-30)
+    near = int((rel_gap[..., :-1] < NEAR_TIE).sum()) if w.d_loc > 1 else 0
+    _, _, token_of = oracle.region_map(w.H, w.W, w.tile_h, w.tile_w)
+    local_of = {}
+    bad_regions, forced = [], 0
+    for b in range(w.B):
+        for p in range(w.P):
+            if np.array_equal(idx_gpu[b, p], idx_ref[b, p]):
+                continue
+            first = int(np.nonzero(idx_gpu[b, p] != idx_ref[b, p])[0][0])
+            ok = rel_gap[b, p, first] < NEAR_TIE
+            if ok:
+                if p not in local_of:
+                    local_of[p] = {int(t): l for l, t in enumerate(token_of[p])}
+                try:
+                    picks = np.array([local_of[p][int(t)] for t in idx_gpu[b, p]], np.int32)
+                except KeyError:
+                    ok = False
+                else:
+                    S = oracle.cosine(X[b, token_of[p]], round_bits=oracle.SIM_BITS)
+                    bad, deficit, _ = oracle.check_picks(S, picks)
+                    ok = bad == -1 and bool(np.all(deficit < NEAR_TIE))
+                    forced += 1
+            if not ok:
+                bad_regions.append((b, p, first))
+    return bad_regions, near, forced
