@@ -24,7 +24,7 @@
  *     (tile-shaped regions, Sec. 4.3.1; tile_w == W gives stripe-shaped regions).
  *     P = regions per sample, N_loc = tile_h * tile_w, D = P * d_loc destinations per sample.
  *   - Limits: C % 32 == 0; N_loc % 16 == 0 and N_loc <= 256; 1 <= d_loc <= N_loc;
- *     merge_regions is 1 or P; head_dim is 64 or 128 (or C when heads == 1 and C <= 128).
+ *     merge_regions is 1 or P; head_dim is 32, 64 or 128.
  *     Anything else returns TOMA_ERR_UNSUPPORTED or TOMA_ERR_SHAPE.
  */
 #ifndef TOMA_H
@@ -79,8 +79,9 @@ const char *toma_status_string(int status);
  * For every (sample, region): S_ij = cos(x_i, x_j) over the region's tokens; first pick = largest
  * row sum; every later pick maximises sum_j max(0, S_ij - m_j) over tokens not yet picked, with
  * m_j the largest similarity of token j to the picks so far.  Ties go to the lowest index.
- * Similarities are evaluated in double precision from the stored token values, rounded once to
- * single precision, and the sums over them are accumulated in double precision.
+ * Similarities are evaluated in double precision from the stored token values and rounded once
+ * to the nearest multiple of 2^-25; the sums and comparisons over them are exact, so the picks
+ * do not depend on any summation order and exact ties are decided by index alone.
  *   X        in   [B, N, C]         tokens (dtype)
  *   idx      out  [B, P, d_loc]     int32 grid index of each pick, in pick order
  *   gain_opt out  [B, P, d_loc]     float value of each winning candidate, or NULL
