@@ -80,7 +80,7 @@ const char *toma_status_string(int status);
  * row sum; every later pick maximises sum_j max(0, S_ij - m_j) over tokens not yet picked, with
  * m_j the largest similarity of token j to the picks so far.  Ties go to the lowest index.
  * Similarities are evaluated in double precision from the stored token values and rounded once
- * to the nearest multiple of 2^-25; the sums and comparisons over them are exact, so the picks
+ * to the nearest multiple of 2^-22; the sums and comparisons over them are exact, so the picks
  * do not depend on any summation order and exact ties are decided by index alone.
  *   X        in   [B, N, C]         tokens (dtype)
  *   idx      out  [B, P, d_loc]     int32 grid index of each pick, in pick order

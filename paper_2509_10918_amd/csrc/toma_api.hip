@@ -45,8 +45,10 @@ void plan_workspace(const Shape &s, Workspace *w) {
   size_t es = s.dtype == TOMA_BF16 ? 2 : 4;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
-  w->stat_parts = 2 * ((s.Dr + kGemmTile - 1) / kGemmTile);
-  w->z_parts = 2 * ((s.Nr + kGemmTile - 1) / kGemmTile);
+  // row strides of the partial-result arrays: enough for the smallest GEMM tile (two wave slices of
+  // 32 per 64-wide tile)
+  w->stat_parts = 2 * ((s.Dr + kGemmMinTile - 1) / kGemmMinTile);
+  w->z_parts = 2 * ((s.Nr + kGemmMinTile - 1) / kGemmMinTile);
   w->nrm = take((size_t)s.B * s.N * sizeof(double));
   w->sim = take((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(float));
   w->stats = take((size_t)s.B * s.N * w->stat_parts * 2 * sizeof(float));

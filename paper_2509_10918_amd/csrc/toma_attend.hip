@@ -23,6 +23,8 @@ template <typename T> struct QkvPol {
   T *out[3];
   int B, D, Tx, L, C, H, dh;
   __device__ __forceinline__ GemmCtx setup(int bz) const { return GemmCtx{B * L, C, C, 0, 0, bz}; }
+  __device__ __forceinline__ bool a_linear(int) const { return true; }
+  __device__ __forceinline__ bool b_linear(int) const { return true; }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &, int m, int k) const {
     int b = m / L, l = m % L;
     return l < D ? Xm + ((size_t)b * D + l) * C + k : Xe + ((size_t)b * Tx + (l - D)) * C + k;
@@ -30,10 +32,12 @@ template <typename T> struct QkvPol {
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
     return W[x.z] + (size_t)k * C + n;
   }
-  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAcc &acc, int m_w, int n_w, int lane) const {
+  template <int TM, int TN>
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
+                                           int lane) const {
     T *o = out[x.z];
     const int L_ = L, H_ = H, dh_ = dh;
-    store_rows<T>(acc, m_w, n_w, lane, x.M, x.N,
+    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
                   [=](int m, int n) {
                     int b = m / L_, l = m % L_, h = n / dh_, dd = n % dh_;
                     return o + (((size_t)b * H_ + h) * L_ + l) * dh_ + dd;
@@ -48,12 +52,16 @@ template <typename T> struct ProjPol {
   T *Out;
   int rows, C;
   __device__ __forceinline__ GemmCtx setup(int) const { return GemmCtx{rows, C, C, 0, 0, 0}; }
+  __device__ __forceinline__ bool a_linear(int) const { return true; }
+  __device__ __forceinline__ bool b_linear(int) const { return true; }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &, int m, int k) const { return In + (size_t)m * C + k; }
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &, int n, int k) const { return Wt + (size_t)k * C + n; }
-  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAcc &acc, int m_w, int n_w, int lane) const {
+  template <int TM, int TN>
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
+                                           int lane) const {
     T *o = Out;
     const int C_ = C;
-    store_rows<T>(acc, m_w, n_w, lane, x.M, x.N, [=](int m, int n) { return o + (size_t)m * C_ + n; },
+    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N, [=](int m, int n) { return o + (size_t)m * C_ + n; },
                   [](int) { return 1.0f; });
   }
 };
@@ -249,7 +257,7 @@ static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const vo
   p.W[0] = static_cast<const T *>(Wq); p.W[1] = static_cast<const T *>(Wk); p.W[2] = static_cast<const T *>(Wv);
   p.out[0] = Q; p.out[1] = K; p.out[2] = V;
   p.B = s.B; p.D = s.D; p.Tx = s.T; p.L = s.L; p.C = s.C; p.H = s.heads; p.dh = s.head_dim;
-  launch_gemm<T>(K_QKV, p, s.B * s.L, s.C, 3, st);
+  launch_gemm<T>(K_QKV, p, s.B * s.L, s.C, s.C, 3, st);
   T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
   switch (s.head_dim) {
     case 32: launch_attn<T, 32>(s, Q, K, V, Oh, st); break;
@@ -261,7 +269,7 @@ static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const vo
     ProjPol<T> pp{};
     pp.In = Oh; pp.Wt = static_cast<const T *>(Wo); pp.Out = static_cast<T *>(O);
     pp.rows = s.B * s.L; pp.C = s.C;
-    launch_gemm<T>(K_PROJ, pp, s.B * s.L, s.C, 1, st);
+    launch_gemm<T>(K_PROJ, pp, s.B * s.L, s.C, s.C, 1, st);
   }
   return launch_status();
 }

@@ -1,20 +1,26 @@
 // Block GEMM on the matrix cores with LDS-staged tiles, shared by the merge-weight, merge, QKV /
-// output projection and unmerge stages.  One workgroup (4 waves, 2 x 2) computes a 128 x 128
-// output tile; each wave owns 64 x 64 as 4 x 4 MFMA tiles; K advances 32 per step with the next
-// step's global loads issued before the current step's products.
+// output projection and unmerge stages.
 //
-// An operand is either k-contiguous in memory (a row of the matrix is a run of k: tokens, weight
-// rows of A) or k-major (consecutive k are separate rows and the other index is contiguous: X as
-// the right operand of the merge, W[k][n], A as the left operand of the unmerge).  k-contiguous
-// tiles are read back as 16-byte fragments; k-major tiles keep their memory order in LDS and are
-// read with the LDS transpose read (bf16) so that no operand is ever transposed by a copy.
+// One workgroup (4 waves, 2 x 2) computes a BM x BN output tile (128 x 128, 128 x 64 or 64 x 64,
+// chosen per launch so that the grid fills the chip); each wave owns (BM/2) x (BN/2) as 16 x 16
+// MFMA tiles.  K advances 128 bytes per step (64 bf16 / 32 fp32) through two LDS stages: the next
+// step's global loads are issued before the current step's products and stored to the other stage
+// after them, so there is one barrier per step.  Workgroup ids are remapped so that the tiles an
+// XCD works on are neighbours (they share operand rows through that XCD's L2).
+//
+// An operand is either k-contiguous in memory (a row of the matrix is a run of k: tokens, rows of
+// A) or k-major (consecutive k are separate rows and the other index is contiguous: X as the right
+// operand of the merge, W[k][n], A as the left operand of the unmerge).  k-contiguous tiles are
+// read back as 16-byte fragments; k-major tiles keep their memory order in LDS and are read with
+// the LDS transpose read (bf16), so that no operand is ever transposed by a copy.
 //
 // A policy type describes one product:
 //   static constexpr bool A_KS, B_KS      operand is k-major
-//   GemmCtx setup(int z) const            decode the batch index blockIdx.z into extents M, N, K
+//   GemmCtx setup(int z) const            decode the batch index into extents M, N, K
 //   const T* a_ptr(ctx, int m, int k)     address of element (m, k); the 16-byte packet starting
 //   const T* b_ptr(ctx, int n, int k)     there runs along k (k-contiguous) or along m / n (k-major)
-//   void epilogue(ctx, acc, m_w, n_w, lane)  consume the wave's 64 x 64 accumulators
+//   bool a_linear(int step), b_linear(int step)   address is affine in k over multiples of `step`
+//   void epilogue<TM, TN>(ctx, acc, m_w, n_w, lane)  consume the wave's accumulators
 // The policy itself is never written to, so it stays in the kernel-argument segment.
 // Extents along a packet's direction must be multiples of the packet length (8 bf16 / 4 fp32).
 #pragma once
@@ -23,127 +29,418 @@
 
 namespace toma {
 
-template <typename T> struct GemmTile {
-  static constexpr int BM = 128, BN = 128, BK = 32;
-  static constexpr int EPP = 16 / (int)sizeof(T);  // elements per 16-byte packet
-  static constexpr int LDK = BK + EPP;             // row stride of a k-contiguous tile [128][BK]
-  static constexpr int LDN = 128 + EPP;            // row stride of a k-major tile [BK][128]
-  static constexpr int KC_ELEMS = 128 * LDK;
-  static constexpr int KS_ELEMS = BK * LDN;
-  static constexpr int NP = 128 * BK / EPP / 256;  // packets per thread per operand tile
-};
-
-typedef f32x4 WaveAcc[4][4];
-
 struct GemmCtx { int M, N, K, b, rho, z; };
 
-template <typename T, typename Pol>
-__global__ __launch_bounds__(256) void k_gemm(const Pol pol) {
-  typedef GemmTile<T> G;
-  constexpr int A_ELEMS = Pol::A_KS ? G::KS_ELEMS : G::KC_ELEMS;
-  constexpr int B_ELEMS = Pol::B_KS ? G::KS_ELEMS : G::KC_ELEMS;
-  __shared__ __align__(16) T As[A_ELEMS];
-  __shared__ __align__(16) T Bs[B_ELEMS];
+template <typename T, int BM, int BN> struct GemmTile {
+  static constexpr int ES = (int)sizeof(T);
+  static constexpr int BK = 128 / ES;               // k per step
+  static constexpr int KSUB = BK / 32;              // 32-wide MFMA groups per step
+  static constexpr int EPP = 16 / ES;               // elements per 16-byte packet
+  static constexpr int LDK = BK + EPP;              // k-contiguous tile [rows][BK], padded row
+  static constexpr int PADN = 32 / ES;
+  static constexpr int TM = BM / 32, TN = BN / 32;  // 16 x 16 MFMA tiles per wave
+  static constexpr int NPA = BM / 32, NPB = BN / 32;  // 16-byte packets per thread per operand tile
+  static constexpr int a_elems(bool ks) { return ks ? BK * (BM + PADN) : BM * LDK; }
+  static constexpr int b_elems(bool ks) { return ks ? BK * (BN + PADN) : BN * LDK; }
+};
 
-  const GemmCtx ctx = pol.setup(blockIdx.z);
-  const int m0 = blockIdx.y * G::BM, n0 = blockIdx.x * G::BN;
-  if (m0 >= ctx.M || n0 >= ctx.N) return;
+template <int TM, int TN> struct WaveAccT { f32x4 t[TM][TN]; };
+
+// Linear workgroup id -> tile id such that the ids an XCD receives (id mod 8) form a contiguous
+// run of tiles.
+__device__ __forceinline__ int xcd_remap(int id, int total) {
+  const int per = total >> 3, body = per << 3;
+  return id < body ? (id & 7) * per + (id >> 3) : id;
+}
+
+template <typename T, typename Pol, int BM, int BN>
+__global__ __launch_bounds__(256) void k_gemm(const Pol pol, int tiles_m, int tiles_n) {
+  typedef GemmTile<T, BM, BN> G;
+  constexpr int A_ELEMS = G::a_elems(Pol::A_KS), B_ELEMS = G::b_elems(Pol::B_KS);
+  constexpr int LDA = Pol::A_KS ? BM + G::PADN : G::LDK;
+  constexpr int LDB = Pol::B_KS ? BN + G::PADN : G::LDK;
+  __shared__ __align__(16) T As[2][A_ELEMS];
+  __shared__ __align__(16) T Bs[2][B_ELEMS];
+
+  int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int per_batch = tiles_m * tiles_n;
+  const int z = tile / per_batch;
+  tile -= z * per_batch;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const GemmCtx ctx = pol.setup(z);
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
   const int g = lane >> 4, c = lane & 15;
   const int K = ctx.K;
 
   // where this thread's packets sit inside a tile
-  int a_lds[G::NP], a_i[G::NP], a_k[G::NP], b_lds[G::NP], b_i[G::NP], b_k[G::NP];
+  int a_lds[G::NPA], a_i[G::NPA], a_k[G::NPA], b_lds[G::NPB], b_i[G::NPB], b_k[G::NPB];
 #pragma unroll
-  for (int i = 0; i < G::NP; i++) {
+  for (int i = 0; i < G::NPA; i++) {
     int q = tid + 256 * i;
     if (Pol::A_KS) {
-      constexpr int PPN = 128 / G::EPP;
-      a_k[i] = q / PPN; a_i[i] = (q % PPN) * G::EPP; a_lds[i] = a_k[i] * G::LDN + a_i[i];
+      constexpr int PPN = BM / G::EPP;
+      a_k[i] = q / PPN; a_i[i] = (q % PPN) * G::EPP; a_lds[i] = a_k[i] * LDA + a_i[i];
     } else {
       constexpr int PPR = G::BK / G::EPP;
-      a_i[i] = q / PPR; a_k[i] = (q % PPR) * G::EPP; a_lds[i] = a_i[i] * G::LDK + a_k[i];
+      a_i[i] = q / PPR; a_k[i] = (q % PPR) * G::EPP; a_lds[i] = a_i[i] * LDA + a_k[i];
     }
+  }
+#pragma unroll
+  for (int i = 0; i < G::NPB; i++) {
+    int q = tid + 256 * i;
     if (Pol::B_KS) {
-      constexpr int PPN = 128 / G::EPP;
-      b_k[i] = q / PPN; b_i[i] = (q % PPN) * G::EPP; b_lds[i] = b_k[i] * G::LDN + b_i[i];
+      constexpr int PPN = BN / G::EPP;
+      b_k[i] = q / PPN; b_i[i] = (q % PPN) * G::EPP; b_lds[i] = b_k[i] * LDB + b_i[i];
     } else {
       constexpr int PPR = G::BK / G::EPP;
-      b_i[i] = q / PPR; b_k[i] = (q % PPR) * G::EPP; b_lds[i] = b_i[i] * G::LDK + b_k[i];
+      b_i[i] = q / PPR; b_k[i] = (q % PPR) * G::EPP; b_lds[i] = b_i[i] * LDB + b_k[i];
     }
   }
 
-  WaveAcc acc;
+  WaveAccT<G::TM, G::TN> acc;
 #pragma unroll
-  for (int i = 0; i < 4; i++)
+  for (int i = 0; i < G::TM; i++)
 #pragma unroll
-    for (int j = 0; j < 4; j++) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < G::TN; j++) acc.t[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  Pkt ra[G::NP], rb[G::NP];
+  Pkt ra[G::NPA], rb[G::NPB];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < G::NP; i++) {
+    for (int i = 0; i < G::NPA; i++) {
       int m = m0 + a_i[i], ka = k0 + a_k[i];
       ra[i] = (m < ctx.M && ka < K) ? pkt_load(pol.a_ptr(ctx, m, ka)) : pkt_zero();
+    }
+#pragma unroll
+    for (int i = 0; i < G::NPB; i++) {
       int n = n0 + b_i[i], kb = k0 + b_k[i];
       rb[i] = (n < ctx.N && kb < K) ? pkt_load(pol.b_ptr(ctx, n, kb)) : pkt_zero();
     }
   };
+  auto stash = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < G::NPA; i++) pkt_store(As[stage] + a_lds[i], ra[i]);
+#pragma unroll
+    for (int i = 0; i < G::NPB; i++) pkt_store(Bs[stage] + b_lds[i], rb[i]);
+  };
 
   fetch(0);
+  stash(0);
+  __syncthreads();
+  int stage = 0;
   for (int k0 = 0; k0 < K; k0 += G::BK) {
-    __syncthreads();
+    const bool more = k0 + G::BK < K;
+    if (more) fetch(k0 + G::BK);
+    const T *at = As[stage], *bt = Bs[stage];
 #pragma unroll
-    for (int i = 0; i < G::NP; i++) {
-      pkt_store(As + a_lds[i], ra[i]);
-      pkt_store(Bs + b_lds[i], rb[i]);
+    for (int kk = 0; kk < G::KSUB; kk++) {
+      Frag<T> fa[G::TM], fb[G::TN];
+      const int kf = 32 * kk + 8 * g;
+#pragma unroll
+      for (int i = 0; i < G::TM; i++) {
+        const int row = wm * (BM / 2) + 16 * i;
+        if (Pol::A_KS) frag_load_ks(fa[i], at, LDA, kf, kf + 4, row, lane);
+        else frag_load_kc(fa[i], at + (row + c) * LDA + kf);
+      }
+#pragma unroll
+      for (int j = 0; j < G::TN; j++) {
+        const int col = wn * (BN / 2) + 16 * j;
+        if (Pol::B_KS) frag_load_ks(fb[j], bt, LDB, kf, kf + 4, col, lane);
+        else frag_load_kc(fb[j], bt + (col + c) * LDB + kf);
+      }
+#pragma unroll
+      for (int i = 0; i < G::TM; i++)
+#pragma unroll
+        for (int j = 0; j < G::TN; j++) mma16(acc.t[i][j], fa[i], fb[j]);
     }
+    if (more) stash(stage ^ 1);
     __syncthreads();
-    if (k0 + G::BK < K) fetch(k0 + G::BK);
-
-    Frag<T> fa[4], fb[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      if (Pol::A_KS) frag_load_ks(fa[i], As, G::LDN, 8 * g, 8 * g + 4, wm * 64 + 16 * i, lane);
-      else frag_load_kc(fa[i], As + (wm * 64 + 16 * i + c) * G::LDK + 8 * g);
-      if (Pol::B_KS) frag_load_ks(fb[i], Bs, G::LDN, 8 * g, 8 * g + 4, wn * 64 + 16 * i, lane);
-      else frag_load_kc(fb[i], Bs + (wn * 64 + 16 * i + c) * G::LDK + 8 * g);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; i++)
-#pragma unroll
-      for (int j = 0; j < 4; j++) mma16(acc[i][j], fa[i], fb[j]);
+    stage ^= 1;
   }
 
-  pol.epilogue(ctx, acc, m0 + wm * 64, n0 + wn * 64, lane);
+  pol.template epilogue<G::TM, G::TN>(ctx, acc, m0 + wm * (BM / 2), n0 + wn * (BN / 2), lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same product with the operand tiles copied global -> LDS by the load-to-LDS path
+// (global_load_lds, 16 bytes per lane, no register staging) through a ring of STAGES tiles, so that
+// several K steps of loads are in flight while the matrix cores work on the oldest one.
+// A load-to-LDS instruction writes lane l's 16 bytes at (LDS base + 16 l): LDS tiles are therefore
+// dense 1 KiB chunks, and bank conflicts are avoided by permuting WHICH global packet a lane
+// fetches (an XOR swizzle of the packet index by the row), undone by the fragment reads.
+// Needs K to be a multiple of the K step; rows past the end are clamped (their results are never
+// stored).  Other shapes use k_gemm above.
+// ------------------------------------------------------------------------------------------------
+template <typename T> struct SwzTile {
+  static constexpr int ES = (int)sizeof(T);
+  static constexpr int EPP = 16 / ES;
+  // k-contiguous tile: 128-byte rows of 8 packets; packet kp of row r sits at slot kp ^ (r & 7)
+  __device__ static __forceinline__ int kc(int row, int kp) { return row * (128 / ES) + ((kp ^ (row & 7)) * EPP); }
+  // k-major tile: rows of PPR packets; packet pi of row k sits at slot pi ^ ((k & 3) << 1)
+  template <int PPR> __device__ static __forceinline__ int ks(int k, int pi) {
+    return (k * PPR + (pi ^ ((k & 3) << 1))) * EPP;
+  }
+};
+
+template <int PPR>
+__device__ __forceinline__ void frag_load_ks_sw(Frag<bf16_t> &f, const bf16_t *tile, int ka, int kb, int nb, int lane) {
+  typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const int j = lane & 15, col = nb + 4 * (j & 3);
+  const int ra = ka + (j >> 2), rb = kb + (j >> 2);
+  const bf16_t *pa = tile + SwzTile<bf16_t>::ks<PPR>(ra, col >> 3) + (col & 7);
+  const bf16_t *pb = tile + SwzTile<bf16_t>::ks<PPR>(rb, col >> 3) + (col & 7);
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pa));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pb));
+  s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  f.v = __builtin_bit_cast(bf16x8, both);
+}
+template <int PPR>
+__device__ __forceinline__ void frag_load_ks_sw(Frag<float> &f, const float *tile, int ka, int kb, int nb, int lane) {
+  const int col = nb + (lane & 15);
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    f.v[i] = tile[SwzTile<float>::ks<PPR>(ka + i, col >> 2) + (col & 3)];
+    f.v[4 + i] = tile[SwzTile<float>::ks<PPR>(kb + i, col >> 2) + (col & 3)];
+  }
+}
+// eight consecutive k starting at element kf of row `row` of a swizzled k-contiguous tile
+__device__ __forceinline__ void frag_load_kc_sw(Frag<bf16_t> &f, const bf16_t *tile, int row, int kf) {
+  f.v = *reinterpret_cast<const bf16x8 *>(tile + SwzTile<bf16_t>::kc(row, kf >> 3));
+}
+__device__ __forceinline__ void frag_load_kc_sw(Frag<float> &f, const float *tile, int row, int kf) {
+  f32x4 a = *reinterpret_cast<const f32x4 *>(tile + SwzTile<float>::kc(row, kf >> 2));
+  f32x4 b = *reinterpret_cast<const f32x4 *>(tile + SwzTile<float>::kc(row, (kf >> 2) + 1));
+#pragma unroll
+  for (int i = 0; i < 4; i++) { f.v[i] = a[i]; f.v[4 + i] = b[i]; }
+}
+
+// One load-to-LDS instruction: lane l's 16 bytes at gptr land at lds_chunk + 16 l.  Issued as
+// assembly so that the pipeline's own s_waitcnt vmcnt(n) (below) decides when a tile is complete;
+// the compiler's model would otherwise drain every outstanding load before each LDS read.
+template <typename T>
+__device__ __forceinline__ void load_to_lds16(const T *gptr, T *lds_chunk) {
+  uint32_t lds_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds_chunk;
+  lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr)
+               : "memory", "m0");
+}
+// wait until at most n of this wave's vector-memory loads are outstanding (n < 64)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | (((N >> 4) & 3) << 14));
+}
+
+template <typename T, typename Pol, int BM, int BN, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_async(const Pol pol, int tiles_m, int tiles_n) {
+  typedef GemmTile<T, BM, BN> G;
+  constexpr int NWAVES = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;               // wave tile
+  constexpr int TM = WTM / 16, TN = WTN / 16;                 // 16 x 16 MFMA tiles per wave
+  constexpr int A_ELEMS = BM * G::BK, B_ELEMS = BN * G::BK;   // dense: 128 bytes per row / k-row
+  constexpr int NIA = BM / 8 / NWAVES, NIB = BN / 8 / NWAVES; // load instructions per wave per tile
+  constexpr int PPR_A = BM / G::EPP, PPR_B = BN / G::EPP;     // packets per k-row of a k-major tile
+  __shared__ __align__(1024) T As[STAGES][A_ELEMS];
+  __shared__ __align__(1024) T Bs[STAGES][B_ELEMS];
+
+  int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int per_batch = tiles_m * tiles_n;
+  const int z = tile / per_batch;
+  tile -= z * per_batch;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const GemmCtx ctx = pol.setup(z);
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w / WGN, wn = w % WGN;
+  const int g = lane >> 4, c = lane & 15;
+  const int K = ctx.K, nk = K / G::BK;
+
+  // what this lane fetches for chunk `ch` (1 KiB = 64 packets) of a tile: tile coordinates
+  int a_i[NIA], a_k[NIA], b_i[NIB], b_k[NIB];
+#pragma unroll
+  for (int t = 0; t < NIA; t++) {
+    const int ch = w * NIA + t;
+    if (Pol::A_KS) {
+      const int k = ch * (64 / PPR_A) + lane / PPR_A, pos = lane % PPR_A;
+      a_k[t] = k; a_i[t] = (pos ^ ((k & 3) << 1)) * G::EPP;
+    } else {
+      const int row = ch * 8 + (lane >> 3);
+      a_i[t] = row; a_k[t] = ((lane & 7) ^ (row & 7)) * G::EPP;
+    }
+    // rows past the end repeat the last valid row / packet
+    const int lim = Pol::A_KS ? ctx.M - G::EPP : ctx.M - 1;
+    if (m0 + a_i[t] > lim) a_i[t] = lim - m0;
+  }
+#pragma unroll
+  for (int t = 0; t < NIB; t++) {
+    const int ch = w * NIB + t;
+    if (Pol::B_KS) {
+      const int k = ch * (64 / PPR_B) + lane / PPR_B, pos = lane % PPR_B;
+      b_k[t] = k; b_i[t] = (pos ^ ((k & 3) << 1)) * G::EPP;
+    } else {
+      const int row = ch * 8 + (lane >> 3);
+      b_i[t] = row; b_k[t] = ((lane & 7) ^ (row & 7)) * G::EPP;
+    }
+    const int lim = Pol::B_KS ? ctx.N - G::EPP : ctx.N - 1;
+    if (n0 + b_i[t] > lim) b_i[t] = lim - n0;
+  }
+
+  // Operand addresses advance by a fixed amount per K step when the operand is linear in k (all
+  // operands except a k-major walk over a region whose width does not divide the step): keep the
+  // step-0 address and the per-step delta instead of recomputing maps and gathers every step.
+  const bool lin_a = pol.a_linear(G::BK), lin_b = pol.b_linear(G::BK);
+  const T *pa[NIA], *pb[NIB];
+  int da[NIA], db[NIB];
+#pragma unroll
+  for (int t = 0; t < NIA; t++) {
+    pa[t] = pol.a_ptr(ctx, m0 + a_i[t], a_k[t]);
+    da[t] = lin_a ? (int)(pol.a_ptr(ctx, m0 + a_i[t], a_k[t] + G::BK) - pa[t]) : 0;
+  }
+#pragma unroll
+  for (int t = 0; t < NIB; t++) {
+    pb[t] = pol.b_ptr(ctx, n0 + b_i[t], b_k[t]);
+    db[t] = lin_b ? (int)(pol.b_ptr(ctx, n0 + b_i[t], b_k[t] + G::BK) - pb[t]) : 0;
+  }
+  auto issue = [&](int kt) {
+    const int st = kt % STAGES, k0 = kt * G::BK;
+#pragma unroll
+    for (int t = 0; t < NIA; t++) {
+      const T *src = lin_a ? pa[t] + (ptrdiff_t)kt * da[t] : pol.a_ptr(ctx, m0 + a_i[t], k0 + a_k[t]);
+      load_to_lds16(src, As[st] + (w * NIA + t) * (1024 / G::ES));
+    }
+#pragma unroll
+    for (int t = 0; t < NIB; t++) {
+      const T *src = lin_b ? pb[t] + (ptrdiff_t)kt * db[t] : pol.b_ptr(ctx, n0 + b_i[t], k0 + b_k[t]);
+      load_to_lds16(src, Bs[st] + (w * NIB + t) * (1024 / G::ES));
+    }
+  };
+
+  WaveAccT<TM, TN> acc;
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++) acc.t[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; s++)
+    if (s < nk) issue(s);
+
+  for (int kt = 0; kt < nk; kt++) {
+    // this wave's loads of step kt are the oldest outstanding ones: wait until at most the
+    // younger steps' loads remain, then meet the other waves
+    const int younger = min(nk - 1 - kt, STAGES - 2);
+    if (younger >= 2) wait_vmcnt<2 * (NIA + NIB)>();
+    else if (younger == 1) wait_vmcnt<NIA + NIB>();
+    else wait_vmcnt<0>();
+    // every wave's part of tile kt has landed, and every wave is done reading tile kt - 1
+    __builtin_amdgcn_s_barrier();
+    if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
+    const T *at = As[kt % STAGES], *bt = Bs[kt % STAGES];
+#pragma unroll
+    for (int kk = 0; kk < G::KSUB; kk++) {
+      Frag<T> fa[TM], fb[TN];
+      const int kf = 32 * kk + 8 * g;
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        const int row = wm * WTM + 16 * i;
+        if (Pol::A_KS) frag_load_ks_sw<PPR_A>(fa[i], at, kf, kf + 4, row, lane);
+        else frag_load_kc_sw(fa[i], at, row + c, kf);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const int col = wn * WTN + 16 * j;
+        if (Pol::B_KS) frag_load_ks_sw<PPR_B>(fb[j], bt, kf, kf + 4, col, lane);
+        else frag_load_kc_sw(fb[j], bt, col + c, kf);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) mma16(acc.t[i][j], fa[i], fb[j]);
+    }
+  }
+
+  pol.template epilogue<TM, TN>(ctx, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
 }
 
 // Row-major store of a wave's accumulators: element (m, n) goes to ptr(m, n), scaled per row.
 // ptr must be contiguous in n inside an aligned run of 16 columns.
-template <typename T, typename PtrFn, typename RowScaleFn>
-__device__ __forceinline__ void store_rows(const WaveAcc &acc, int m_w, int n_w, int lane, int M, int N,
+template <typename T, int TM, int TN, typename PtrFn, typename RowScaleFn>
+__device__ __forceinline__ void store_rows(const WaveAccT<TM, TN> &acc, int m_w, int n_w, int lane, int M, int N,
                                            PtrFn ptr, RowScaleFn row_scale) {
   const int g = lane >> 4, c = lane & 15;
 #pragma unroll
-  for (int i = 0; i < 4; i++)
+  for (int i = 0; i < TM; i++)
 #pragma unroll
     for (int r = 0; r < 4; r++) {
       int m = m_w + 16 * i + 4 * g + r;
       if (m >= M) continue;
       float sc = row_scale(m);
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
+      for (int j = 0; j < TN; j++) {
         int n = n_w + 16 * j + c;
-        if (n < N) *ptr(m, n) = from_f32<T>(acc[i][j][r] * sc);
+        if (n < N) *ptr(m, n) = from_f32<T>(acc.t[i][j][r] * sc);
       }
     }
 }
 
+struct GemmShape { int bm, bn, wgm, wgn, tiles_m, tiles_n; };
+
+inline GemmShape make_gemm_shape(int M, int N, int bm, int bn, int wgm, int wgn) {
+  return GemmShape{bm, bn, wgm, wgn, (M + bm - 1) / bm, (N + bn - 1) / bn};
+}
+
+// Tile shape for the load-to-LDS kernel.  The kernel is fed from L2 at a few tens of bytes per
+// clock and CU, so a workgroup's time per K step grows with the tile perimeter (BM + BN) while
+// its work grows with the area: take the shape with the least perimeter * (rounds of workgroups
+// over the 256 CUs; every shape keeps one workgroup per CU resident).
+inline GemmShape choose_async_shape(int M, int N, int batch) {
+  const GemmShape cands[4] = {make_gemm_shape(M, N, 256, 128, 4, 2), make_gemm_shape(M, N, 128, 128, 2, 2),
+                              make_gemm_shape(M, N, 128, 64, 2, 2), make_gemm_shape(M, N, 64, 64, 2, 2)};
+  int best = 0;
+  long long best_cost = -1;
+  for (int i = 0; i < 4; i++) {
+    long long blocks = (long long)cands[i].tiles_m * cands[i].tiles_n * batch;
+    long long rounds = (blocks + 255) / 256;
+    long long cost = rounds * (cands[i].bm + cands[i].bn);
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = i; }
+  }
+  return cands[best];
+}
+
+// Tile shape for the register-staged kernel: the largest that still gives about two workgroups per CU.
+inline GemmShape choose_gemm_shape(int M, int N, int batch) {
+  auto blocks = [&](const GemmShape &g) { return (long long)g.tiles_m * g.tiles_n * batch; };
+  GemmShape g = make_gemm_shape(M, N, 128, 128, 2, 2);
+  if (blocks(g) >= 512) return g;
+  g = make_gemm_shape(M, N, 128, 64, 2, 2);
+  if (blocks(g) >= 512) return g;
+  return make_gemm_shape(M, N, 64, 64, 2, 2);
+}
+
 template <typename T, typename Pol>
-inline void launch_gemm(int kernel_id, const Pol &pol, int M, int N, int batch, hipStream_t st) {
-  dim3 grid((N + 127) / 128, (M + 127) / 128, batch);
+inline GemmShape launch_gemm(int kernel_id, const Pol &pol, int M, int N, int K, int batch, hipStream_t st) {
+  constexpr int BK = 128 / (int)sizeof(T), EPP = 16 / (int)sizeof(T);
+  const bool fits = K % BK == 0 && M >= EPP && N >= EPP;
   KernelTimer kt(kernel_id, st);
-  hipLaunchKernelGGL((k_gemm<T, Pol>), grid, dim3(256), 0, st, pol);
+  if (fits) {
+    // load-to-LDS pipeline
+    const GemmShape g = choose_async_shape(M, N, batch);
+    const dim3 grid(g.tiles_m * g.tiles_n * batch);
+    if (g.bm == 256)
+      hipLaunchKernelGGL((k_gemm_async<T, Pol, 256, 128, 4, 2, 3>), grid, dim3(512), 0, st, pol, g.tiles_m, g.tiles_n);
+    else if (g.bm == 128 && g.bn == 128)
+      hipLaunchKernelGGL((k_gemm_async<T, Pol, 128, 128, 2, 2, 4>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
+    else if (g.bm == 128)
+      hipLaunchKernelGGL((k_gemm_async<T, Pol, 128, 64, 2, 2, 4>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
+    else
+      hipLaunchKernelGGL((k_gemm_async<T, Pol, 64, 64, 2, 2, 4>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
+    return g;
+  }
+  const GemmShape g = choose_gemm_shape(M, N, batch);
+  const dim3 grid(g.tiles_m * g.tiles_n * batch);
+  if (g.bm == 128 && g.bn == 128)
+    hipLaunchKernelGGL((k_gemm<T, Pol, 128, 128>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
+  else if (g.bm == 128)
+    hipLaunchKernelGGL((k_gemm<T, Pol, 128, 64>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
+  else
+    hipLaunchKernelGGL((k_gemm<T, Pol, 64, 64>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
+  return g;
 }
 
 }  // namespace toma

@@ -23,7 +23,7 @@ struct Workspace {
   int stat_parts, z_parts;
 };
 
-constexpr int kGemmTile = 128;  // block tile edge of the MFMA GEMM kernels
+constexpr int kGemmMinTile = 64;  // smallest block tile edge of the MFMA GEMM kernels
 
 int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s);
 void plan_workspace(const Shape &s, Workspace *w);

@@ -23,6 +23,8 @@ template <typename T> struct RegionView {
   RegionMap map;
   int N, C, D, R, Nr, Dr;
   __device__ __forceinline__ int token(int rho, int s) const { return R == 1 ? s : map.token(rho, s); }
+  // token(rho, s + step) - token(rho, s) does not depend on s
+  __device__ __forceinline__ bool token_linear(int step) const { return R == 1 || step % map.tile_w == 0; }
 };
 
 // ---- pass 1 and pass 2 of the weights ----------------------------------------------------------
@@ -40,6 +42,8 @@ template <typename T, bool WRITE> struct WeightsPol {
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Nr, v.Dr, v.C, bz / v.R, bz % v.R, bz};
   }
+  __device__ __forceinline__ bool a_linear(int) const { return true; }
+  __device__ __forceinline__ bool b_linear(int) const { return true; }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &x, int m, int k) const {
     return v.X + ((size_t)x.b * v.N + v.token(x.rho, m)) * v.C + k;
   }
@@ -48,29 +52,31 @@ template <typename T, bool WRITE> struct WeightsPol {
     t = t < 0 ? 0 : (t >= v.N ? v.N - 1 : t);
     return v.X + ((size_t)x.b * v.N + t) * v.C + k;
   }
-  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAcc &acc, int m_w, int n_w, int lane) const {
+  template <int TM, int TN>
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
+                                           int lane) const {
     const int g = lane >> 4, c = lane & 15;
     const int M = x.M, N = x.N, z = x.z;
     if (!WRITE) {
-      // per source row: (max, sum exp) over this wave's 64 destination columns
-      const int part = (n_w / 64);
+      // per source row: (max, sum exp) over this wave's slice of destination columns
+      const int part = n_w / (16 * TN);
 #pragma unroll
-      for (int i = 0; i < 4; i++)
+      for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int r = 0; r < 4; r++) {
           float mx = -__builtin_inff();
 #pragma unroll
-          for (int j = 0; j < 4; j++) {
+          for (int j = 0; j < TN; j++) {
             int n = n_w + 16 * j + c;
-            if (n < N) mx = fmaxf(mx, acc[i][j][r] * scale);
+            if (n < N) mx = fmaxf(mx, acc.t[i][j][r] * scale);
           }
 #pragma unroll
           for (int x = 1; x < 16; x <<= 1) mx = fmaxf(mx, wave_xor_f32(mx, x));
           float sum = 0.f;
 #pragma unroll
-          for (int j = 0; j < 4; j++) {
+          for (int j = 0; j < TN; j++) {
             int n = n_w + 16 * j + c;
-            if (n < N) sum += __expf(acc[i][j][r] * scale - mx);
+            if (n < N) sum += __expf(acc.t[i][j][r] * scale - mx);
           }
 #pragma unroll
           for (int x = 1; x < 16; x <<= 1) sum += wave_xor_f32(sum, x);
@@ -78,22 +84,24 @@ template <typename T, bool WRITE> struct WeightsPol {
           if (c == 0 && m < M) stats[((size_t)z * M + m) * parts + part] = make_float2(mx, sum);
         }
     } else {
-      float colsum[4] = {0.f, 0.f, 0.f, 0.f};
+      float colsum[TN];
 #pragma unroll
-      for (int i = 0; i < 4; i++) {
+      for (int j = 0; j < TN; j++) colsum[j] = 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
         int mb = m_w + 16 * i + 4 * g;  // four consecutive sources mb .. mb+3 (M is a multiple of 16)
         if (mb >= M) continue;
         float l4[4];
 #pragma unroll
         for (int r = 0; r < 4; r++) l4[r] = lse[(size_t)z * M + mb + r];
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
+        for (int j = 0; j < TN; j++) {
           int n = n_w + 16 * j + c;
           if (n >= N) continue;
           alignas(16) T o[4];
 #pragma unroll
           for (int r = 0; r < 4; r++) {
-            o[r] = from_f32<T>(__expf(acc[i][j][r] * scale - l4[r]));
+            o[r] = from_f32<T>(__expf(acc.t[i][j][r] * scale - l4[r]));
             colsum[j] += to_f32(o[r]);
           }
           T *dst = A + ((size_t)z * N + n) * M + mb;
@@ -104,9 +112,9 @@ template <typename T, bool WRITE> struct WeightsPol {
           }
         }
       }
-      const int part = m_w / 64;
+      const int part = m_w / (16 * TM);
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
+      for (int j = 0; j < TN; j++) {
         float v4 = colsum[j];
         v4 += wave_xor_f32(v4, 16);
         v4 += wave_xor_f32(v4, 32);
@@ -118,10 +126,10 @@ template <typename T, bool WRITE> struct WeightsPol {
 };
 
 // lse[row] = M + log(sum_i s_i exp(m_i - M)) over the row's partial (max, sum) pairs.
-__global__ void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse, int rows, int parts) {
+__global__ void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse, int rows, int stride, int parts) {
   int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= rows) return;
-  const float2 *s = stats + (size_t)row * parts;
+  const float2 *s = stats + (size_t)row * stride;
   float mx = -__builtin_inff();
   for (int i = 0; i < parts; i++) mx = fmaxf(mx, s[i].x);
   float sum = 0.f;
@@ -130,10 +138,10 @@ __global__ void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse,
 }
 
 // Z[j] = sum of the partial row sums, in index order (fixed order: reruns are bit-identical).
-__global__ void k_zsum(const float *__restrict__ zpart, float *__restrict__ Z, int rows, int parts) {
+__global__ void k_zsum(const float *__restrict__ zpart, float *__restrict__ Z, int rows, int stride, int parts) {
   int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= rows) return;
-  const float *s = zpart + (size_t)row * parts;
+  const float *s = zpart + (size_t)row * stride;
   float sum = 0.f;
   for (int i = 0; i < parts; i++) sum += s[i];
   Z[row] = sum;
@@ -149,17 +157,21 @@ template <typename T> struct MergePol {
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Dr, v.C, v.Nr, bz / v.R, bz % v.R, bz};
   }
+  __device__ __forceinline__ bool a_linear(int) const { return true; }
+  __device__ __forceinline__ bool b_linear(int step) const { return v.token_linear(step); }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &x, int m, int k) const {
     return A + ((size_t)x.z * x.M + m) * x.K + k;
   }
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
     return v.X + ((size_t)x.b * v.N + v.token(x.rho, k)) * v.C + n;
   }
-  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAcc &acc, int m_w, int n_w, int lane) const {
+  template <int TM, int TN>
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
+                                           int lane) const {
     const float *Zr = Z + (size_t)x.b * v.D + x.rho * v.Dr;
     T *out = Xm + ((size_t)x.b * v.D + x.rho * v.Dr) * v.C;
     const int Cc = v.C;
-    store_rows<T>(acc, m_w, n_w, lane, x.M, x.N,
+    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
                   [=](int m, int n) { return out + (size_t)m * Cc + n; },
                   [=](int m) { return 1.0f / fmaxf(Zr[m], 1e-20f); });
   }
@@ -175,17 +187,21 @@ template <typename T> struct UnmergePol {
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Nr, v.C, v.Dr, bz / v.R, bz % v.R, bz};
   }
+  __device__ __forceinline__ bool a_linear(int) const { return true; }
+  __device__ __forceinline__ bool b_linear(int) const { return true; }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &x, int m, int k) const {
     return A + ((size_t)x.z * x.K + k) * x.M + m;
   }
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
     return Os + ((size_t)x.b * v.D + x.rho * v.Dr + k) * v.C + n;
   }
-  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAcc &acc, int m_w, int n_w, int lane) const {
+  template <int TM, int TN>
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
+                                           int lane) const {
     T *out = Y + (size_t)x.b * v.N * v.C;
     const RegionView<T> vv = v;
     const int rr = x.rho;
-    store_rows<T>(acc, m_w, n_w, lane, x.M, x.N,
+    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
                   [=](int m, int n) { return out + (size_t)vv.token(rr, m) * vv.C + n; },
                   [](int) { return 1.0f; });
   }
@@ -229,19 +245,19 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   p1.v = make_view<T>(s, X);
   p1.idx = idx; p1.scale = s.scale;
   p1.stats = reinterpret_cast<float2 *>(ws + w.stats); p1.parts = w.stat_parts;
-  launch_gemm<T>(K_WSTATS, p1, s.Nr, s.Dr, batch, st);
+  const GemmShape gs = launch_gemm<T>(K_WSTATS, p1, s.Nr, s.Dr, s.C, batch, st);
   float *lse = reinterpret_cast<float *>(ws + w.lse);
   int rows = batch * s.Nr;
   { KernelTimer kt(K_LSE, st);
-    hipLaunchKernelGGL(k_lse, dim3((rows + 255) / 256), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts); }
+    hipLaunchKernelGGL(k_lse, dim3((rows + 255) / 256), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n); }
   WeightsPol<T, true> p2{};
   p2.v = p1.v; p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
   p2.A = static_cast<T *>(A);
   p2.zpart = reinterpret_cast<float *>(ws + w.zpart); p2.zparts = w.z_parts;
-  launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, batch, st);
+  const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
   int zr = s.B * s.D;
   { KernelTimer kt(K_ZSUM, st);
-    hipLaunchKernelGGL(k_zsum, dim3((zr + 255) / 256), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts); }
+    hipLaunchKernelGGL(k_zsum, dim3((zr + 255) / 256), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
   return launch_status();
 }
 
@@ -256,7 +272,7 @@ static int merge_typed(const Shape &s, const void *X, const void *A, const float
   MergePol<T> p{};
   p.v = make_view<T>(s, X);
   p.A = static_cast<const T *>(A); p.Z = Z; p.Xm = static_cast<T *>(Xm);
-  launch_gemm<T>(K_MERGE, p, s.Dr, s.C, s.B * s.R, st);
+  launch_gemm<T>(K_MERGE, p, s.Dr, s.C, s.Nr, s.B * s.R, st);
   return launch_status();
 }
 
@@ -275,7 +291,7 @@ static int unmerge_typed(const Shape &s, const void *A, const float *Z, const vo
   UnmergePol<T> p{};
   p.v = make_view<T>(s, nullptr);
   p.A = static_cast<const T *>(A); p.Os = Os; p.Y = static_cast<T *>(Y);
-  launch_gemm<T>(K_UNMERGE, p, s.Nr, s.C, s.B * s.R, st);
+  launch_gemm<T>(K_UNMERGE, p, s.Nr, s.C, s.Dr, s.B * s.R, st);
   return launch_status();
 }
 

@@ -5,25 +5,21 @@
 //   k_norms   ||x_n||_2 of every token, accumulated in double.
 //   k_gram    S = cos(x_i, x_j) per region with the fp64 matrix cores (v_mfma_f64_16x16x4_f64):
 //             products of stored bf16 / fp32 values are exact in double, so S is the similarity
-//             to ~1e-16 before it is rounded once to the nearest multiple of 2^-25 and stored as
+//             to ~1e-16 before it is rounded once to the nearest multiple of 2^-22 and stored as
 //             a 32-bit integer.  From there on every sum and comparison of the greedy loop is
 //             exact integer arithmetic: the picks do not depend on any summation order, and
 //             mathematically tied candidates (common: two tokens that only improve each other's
 //             coverage) are exact ties that go to the lowest index.
-//   k_greedy  one workgroup per (sample, region).  The region's whole S (up to 256 x 256 words)
-//             lives in the workgroup's vector registers: wave w owns rows 16w .. 16w+15, lane
-//             (g, c) = (lane / 16, lane % 16) holds rows 16w + 4g + r and columns c + 16t.  A
-//             round is: per-lane partial sums of max(0, S_ij - m_j), a 16-lane reduction, an
-//             in-wave argmax, one LDS exchange between the waves (each wave also posts its
-//             candidate's row, so the winner's row is already there for m <- max(m, S_t)).
+//   k_greedy  one workgroup per (sample, region); the region's whole S (up to 256 x 256 words)
+//             lives in the workgroup's vector registers (see the comment at the kernel).
 #include "toma_common.h"
 #include "toma_internal.h"
 
 namespace toma {
 
-// Similarities are decided on a grid of 2^-25: |S| <= 1 + rounding, so a lane's 16-term partial
-// sum of differences stays below 2^31 and a full 256-term sum below 2^35 (exact in a double).
-constexpr double kSimScale = 33554432.0;
+// Similarities are decided on a grid of 2^-22: |S| <= 1, so a 256-term sum of differences
+// max(0, S_ij - m_j) <= 2^23 stays below 2^31 and is exact in a 32-bit integer.
+constexpr double kSimScale = 4194304.0;
 
 // ------------------------------------------------------------------------------------------------
 template <typename T>
@@ -134,94 +130,224 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, const dou
 }
 
 // ------------------------------------------------------------------------------------------------
+// Greedy facility location, one workgroup per (sample, region), exact and lazy.
+//
+// Arithmetic.  S is on a grid of 2^-22 (kSimScale): a term max(0, S_ij - m_j) is at most 2^23 and a
+// 256-term sum fits an unsigned 32-bit register, so values, sums and comparisons are plain 32-bit
+// integer instructions and every cross-lane step is a single DPP-modified add or max.
+// Layout.  Wave w owns rows 32w .. 32w+31 of the region's S; lane l holds, of each of those rows,
+// the columns l + 64u.  Evaluating one row's value is a few integer operations per lane plus one
+// 64-lane reduction, and WHICH rows are evaluated is a wave-uniform (scalar) decision.
+// Keys.  Lane r < 32 of wave w keeps key = value + 1 of row 32w + r (0 = chosen or absent).
+// Across waves a candidate travels as (key << 8) | (255 - row): the largest packed word is the
+// largest value and, among equals, the lowest index, so the workgroup's argmax is one LDS
+// atomic max per wave.
+// Laziness.  Values only shrink as m grows (diminishing returns, paper Sec. 3.2), so a key from an
+// earlier round is an upper bound.  In a round every wave re-evaluates its row with the largest
+// stale key and posts that fresh candidate together with the best of its remaining stale keys.
+// If no stale key in the workgroup beats the best fresh candidate B0, B0 is the pick (one barrier
+// per round, the common case).  Otherwise every wave re-evaluates exactly its rows whose stale key
+// still beats B0 and the waves vote again.  Rows that are skipped cannot win, so the pick is the
+// one a full rescan (Alg. 2) makes.
+// ------------------------------------------------------------------------------------------------
+template <int CTRL, int ROW_MASK = 0xf> __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppRor4 = 0x124, kDppRor8 = 0x128;
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;
+
+// sum over the 64 lanes (mod 2^32); the result is uniform
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  v += dpp_u32<kDppXor1>(v);
+  v += dpp_u32<kDppXor2>(v);
+  v += dpp_u32<kDppRor4>(v);
+  v += dpp_u32<kDppRor8>(v);               // every lane: total of its row of 16
+  v += dpp_u32<kDppBcast15, 0xa>(v);       // rows 1, 3 += rows 0, 2
+  v += dpp_u32<kDppBcast31, 0xc>(v);       // rows 2, 3 += rows 0 + 1
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+// max over lanes 0..31; the result is uniform
+__device__ __forceinline__ uint32_t wave_max32_u32(uint32_t v) {
+  v = max(v, dpp_u32<kDppXor1>(v));
+  v = max(v, dpp_u32<kDppXor2>(v));
+  v = max(v, dpp_u32<kDppRor4>(v));
+  v = max(v, dpp_u32<kDppRor8>(v));
+  return max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16));
+}
+
+#define TOMA_ROWS32(X) \
+  X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) \
+  X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30) X(31)
+
 template <int NT>
-__global__ __launch_bounds__(64 * NT) void k_greedy(const int32_t *__restrict__ S, int32_t *__restrict__ idx,
-                                                   float *__restrict__ gain_out, RegionMap map, int P, int d_loc) {
-  constexpr int NL = 16 * NT;
-  __shared__ int32_t rowbuf[2][NT][NL];
-  __shared__ double cand_gain[2][NT];
-  __shared__ int cand_idx[2][NT];
+__global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *__restrict__ S,
+                                                             int32_t *__restrict__ idx,
+                                                             float *__restrict__ gain_out, RegionMap map,
+                                                             int P, int d_loc) {
+  constexpr int NL = 16 * NT;          // tokens in the region
+  constexpr int NW = (NT + 1) / 2;     // waves, 32 rows each
+  constexpr int CPL = (NT + 3) / 4;    // columns per lane
+  constexpr int32_t kPad = 1 << 23;    // m of a padding column: above every S, so it never contributes
+  constexpr uint32_t kBias0 = 1u << 30;  // first step: row sums are signed, |sum| <= 2^30
+  constexpr int kBulk = 6;             // refresh all rows at once when at least this many are due
+  __shared__ int32_t rowbuf[2][NW][64 * CPL];   // [round parity]: each wave's candidate row
+  // packed best candidates, rotated over three rounds so that a slot is cleared two rounds
+  // before it is written again: [round % 3][0 fresh, 1 best stale runner-up, 2 after phase 2]
+  __shared__ unsigned long long slot[3][4];
 
   const int bp = blockIdx.x, p = bp % P;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int32_t *Sr = S + (size_t)bp * NL * NL;
-  const int row0 = 16 * w + 4 * g;
 
-  int32_t s[4][NT];
+  int32_t s[32][CPL];
+  int32_t m[CPL];
+  bool col_ok[CPL];
 #pragma unroll
-  for (int r = 0; r < 4; r++)
+  for (int u = 0; u < CPL; u++) {
+    col_ok[u] = lane + 64 * u < NL;
+    m[u] = kPad;
+  }
 #pragma unroll
-    for (int t = 0; t < NT; t++) s[r][t] = Sr[(size_t)(row0 + r) * NL + c + 16 * t];
+  for (int r = 0; r < 32; r++)
+#pragma unroll
+    for (int u = 0; u < CPL; u++) {
+      int row = 32 * w + r;
+      s[r][u] = (row < NL && col_ok[u]) ? Sr[(size_t)row * NL + lane + 64 * u] : 0;
+    }
+  int32_t msum = 0;  // sum of this lane's m: sum_u max(0, s - m) = sum_u max(s, m) - msum
 
-  int32_t m[NT];
-#pragma unroll
-  for (int t = 0; t < NT; t++) m[t] = 0;
-  unsigned chosen = 0;  // bit r: row row0 + r is already a destination
-  const double kNone = -__builtin_inf();
+  const int my_row = 32 * w + lane;
+  const bool my_live0 = lane < 32 && my_row < NL;
+  uint32_t key = 0;  // lane r < 32: value + 1 of row 32w + r, an upper bound between refreshes
 
+  // value of row r of this wave (r is wave-uniform): first step = row sum, later = sum max(0, S - m)
+  auto eval = [&](int r, bool first) -> uint32_t {
+    int32_t part = 0;
+    switch (r) {
+#define TOMA_EVAL_CASE(R)                                                                            \
+  case R:                                                                                            \
+    _Pragma("unroll") for (int u = 0; u < CPL; u++) part += first ? s[R][u] : max(s[R][u], m[u]);     \
+    break;
+      TOMA_ROWS32(TOMA_EVAL_CASE)
+#undef TOMA_EVAL_CASE
+    }
+    if (!first) part -= msum;
+    return wave_sum_u32((uint32_t)part);
+  };
+  // refresh the keys of all live rows of this wave at once (straight-line code, independent chains)
+  auto eval_all = [&](bool first) {
+#pragma unroll
+    for (int r = 0; r < 32; r++) {
+      int32_t part = first ? 0 : -msum;
+#pragma unroll
+      for (int u = 0; u < CPL; u++) part += first ? s[r][u] : max(s[r][u], m[u]);
+      uint32_t g = wave_sum_u32((uint32_t)part);
+      if (lane == r && (first ? my_live0 : key != 0)) key = g + 1u + (first ? kBias0 : 0u);
+    }
+  };
+  auto post_row = [&](int buf, int r) {
+    switch (r) {
+#define TOMA_POST_CASE(R)                                                                      \
+  case R:                                                                                      \
+    _Pragma("unroll") for (int u = 0; u < CPL; u++) rowbuf[buf][w][lane + 64 * u] = s[R][u];   \
+    break;
+      TOMA_ROWS32(TOMA_POST_CASE)
+#undef TOMA_POST_CASE
+    }
+  };
+  auto read_slot = [&](const unsigned long long *ptr) -> unsigned long long {
+    unsigned long long v = *ptr;
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+  };
+  auto pack = [&](uint32_t k, int r) -> unsigned long long {
+    return ((unsigned long long)k << 8) | (unsigned)(255 - (32 * w + r));
+  };
+
+  if (threadIdx.x < 12) slot[threadIdx.x / 4][threadIdx.x % 4] = 0;
+  __syncthreads();
+
+  int q3 = 0;  // step % 3
   for (int step = 0; step < d_loc; step++) {
-    int32_t part[4] = {0, 0, 0, 0};
-    if (step == 0) {
-#pragma unroll
-      for (int t = 0; t < NT; t++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) part[r] += s[r][t];
-    } else {
-#pragma unroll
-      for (int t = 0; t < NT; t++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) part[r] += max(s[r][t] - m[t], 0);
-    }
-    double acc[4];
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      acc[r] = (double)part[r];
-#pragma unroll
-      for (int x = 1; x < 16; x <<= 1) acc[r] += wave_xor_f64(acc[r], x);
-    }
-    // best row of this lane group, then of the wave; equal values keep the lower row index
-    double bg = kNone;
-    int bi = NL;
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      bool free_row = !((chosen >> r) & 1u);
-      if (free_row && acc[r] > bg) { bg = acc[r]; bi = row0 + r; }
-    }
-#pragma unroll
-    for (int x = 16; x < 64; x <<= 1) {
-      double og = wave_xor_f64(bg, x);
-      int oi = __shfl_xor(bi, x, 64);
-      if (og > bg || (og == bg && oi < bi)) { bg = og; bi = oi; }
-    }
+    const bool first = step == 0;
     const int buf = step & 1;
-    if (bi < NL && g == ((bi & 15) >> 2)) {
-      const int rr = bi & 3;
-#pragma unroll
-      for (int t = 0; t < NT; t++) {
-        int32_t v = rr == 0 ? s[0][t] : rr == 1 ? s[1][t] : rr == 2 ? s[2][t] : s[3][t];
-        rowbuf[buf][w][c + 16 * t] = v;
+    unsigned long long *sl = slot[q3];
+    bool fresh = false;
+    // ---- phase 1: refresh the row with the largest stale key; post it, and the best of the rest ----
+    if (first) {
+      eval_all(true);
+      fresh = true;
+    }
+    {
+      uint32_t top = wave_max32_u32(key);
+      if (top != 0) {
+        int r = __builtin_ctzll(__ballot(key == top && lane < 32));
+        uint32_t g = top;
+        if (!first) {
+          g = eval(r, false) + 1u;
+          if (lane == r) { key = g; fresh = true; }
+        }
+        post_row(buf, r);
+        uint32_t rest = first ? 0u : wave_max32_u32(lane == r ? 0u : key);
+        unsigned long long rest_lanes = __ballot(key == rest && lane < 32 && lane != r);
+        if (lane == 0) {
+          atomicMax(&sl[0], pack(g, r));
+          if (rest != 0) atomicMax(&sl[1], pack(rest, __builtin_ctzll(rest_lanes)));
+        }
       }
     }
-    if (lane == 0) { cand_gain[buf][w] = bg; cand_idx[buf][w] = bi; }
     __syncthreads();
-    double G = kNone;
-    int I = NL, ww = 0;
-#pragma unroll
-    for (int v = 0; v < NT; v++) {
-      double og = cand_gain[buf][v];
-      int oi = cand_idx[buf][v];
-      if (og > G || (og == G && oi < I)) { G = og; I = oi; ww = v; }
+    if (threadIdx.x < 4) slot[q3 == 0 ? 2 : q3 - 1][threadIdx.x] = 0;  // the slots of round step + 2
+    unsigned long long best = read_slot(&sl[0]);
+    if (!first) {
+      const unsigned long long stale = read_slot(&sl[1]);
+      if (stale > best) {
+        // ---- phase 2: some stale key still beats the best fresh candidate: refresh those rows ----
+        uint32_t g0 = (uint32_t)(best >> 8);
+        int i0 = 255 - (int)(best & 255u);
+        bool beats = key > g0 || (key == g0 && my_row < i0);
+        unsigned long long need = __ballot(key != 0 && !fresh && beats && lane < 32);
+        if (__builtin_popcountll(need) >= kBulk) {
+          eval_all(false);
+        } else {
+          while (need) {
+            int r = __builtin_ctzll(need);
+            need &= need - 1;
+            uint32_t g = eval(r, false) + 1u;
+            if (lane == r) key = g;
+          }
+        }
+        uint32_t top = wave_max32_u32(key);
+        if (top != 0) {
+          int r = __builtin_ctzll(__ballot(key == top && lane < 32));
+          post_row(buf, r);
+          if (lane == 0) atomicMax(&sl[2], pack(top, r));
+        }
+        __syncthreads();
+        best = read_slot(&sl[2]);
+      }
     }
+    const uint32_t G = (uint32_t)(best >> 8);
+    const int I = 255 - (int)(best & 255u);
+    const int ww = I >> 5;
+    msum = 0;
 #pragma unroll
-    for (int t = 0; t < NT; t++) {
-      int32_t mv = rowbuf[buf][ww][c + 16 * t];
-      m[t] = step == 0 ? mv : max(m[t], mv);
+    for (int u = 0; u < CPL; u++) {
+      int32_t mv = rowbuf[buf][ww][lane + 64 * u];
+      m[u] = !col_ok[u] ? kPad : (first ? mv : max(m[u], mv));
+      msum += m[u];
     }
-    if (w == (I >> 4) && g == ((I & 15) >> 2)) chosen |= 1u << (I & 3);
+    if (first && my_live0) key = 0xffffffffu;  // row sums are no bounds on later values: force a refresh
+    if (w == ww && lane == (I & 31)) key = 0;
     if (threadIdx.x == 0) {
       idx[(size_t)bp * d_loc + step] = map.token(p, I);
-      if (gain_out) gain_out[(size_t)bp * d_loc + step] = (float)(G / kSimScale);
+      if (gain_out) {
+        double v = first ? (double)G - 1.0 - (double)kBias0 : (double)G - 1.0;
+        gain_out[(size_t)bp * d_loc + step] = (float)(v / kSimScale);
+      }
     }
+    q3 = q3 == 2 ? 0 : q3 + 1;
   }
 }
 
@@ -243,7 +369,8 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, c
   switch (s.n_loc / 16) {
 #define TOMA_GREEDY_CASE(NT)                                                                              \
   case NT:                                                                                                \
-    hipLaunchKernelGGL(k_greedy<NT>, dim3(regions), dim3(64 * NT), 0, st, S, idx, gain, map, s.P, s.d_loc); \
+    hipLaunchKernelGGL(k_greedy<NT>, dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, map, s.P, \
+                       s.d_loc);                                                                           \
     break;
     TOMA_GREEDY_CASE(1)
     TOMA_GREEDY_CASE(2)
