@@ -49,7 +49,6 @@ void plan_workspace(const Shape &s, Workspace *w) {
   // 32 per 64-wide tile)
   w->stat_parts = 2 * ((s.Dr + kGemmMinTile - 1) / kGemmMinTile);
   w->z_parts = 2 * ((s.Nr + kGemmMinTile - 1) / kGemmMinTile);
-  w->nrm = take((size_t)s.B * s.N * sizeof(double));
   w->sim = take((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(float));
   w->stats = take((size_t)s.B * s.N * w->stat_parts * 2 * sizeof(float));
   w->lse = take((size_t)s.B * s.N * sizeof(float));
@@ -148,7 +147,7 @@ TOMA_API int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, cons
   if (misaligned(Xm, 16) || misaligned(Wq, 16) || misaligned(Wk, 16) || misaligned(Wv, 16) || misaligned(O, 16) ||
       (X_extra_opt && misaligned(X_extra_opt, 16)) || (Wo_opt && misaligned(Wo_opt, 16)))
     return TOMA_ERR_ALIGN;
-  return launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, static_cast<char *>(ws), w,
+  return launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, nullptr, static_cast<char *>(ws), w,
                        static_cast<hipStream_t>(stream));
 }
 
@@ -160,7 +159,8 @@ TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, 
   if (!A || !Z || !O || !Y) return TOMA_ERR_NULL;
   if (o_rows < s.D) return TOMA_ERR_SHAPE;
   if (misaligned(A, 16) || misaligned(O, 16) || misaligned(Y, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
-  return launch_unmerge(s, A, Z, O, o_rows, Y, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+  return launch_unmerge(s, A, Z, O, o_rows, false, Y, static_cast<char *>(ws), w,
+                        static_cast<hipStream_t>(stream));
 }
 
 TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse_flags, const void *X,
@@ -196,9 +196,11 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
   }
   rc = launch_merge(s, X, A, Z, Xm, st);
   if (rc != TOMA_OK) return rc;
-  rc = launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, wsb, w, st);
+  // inside the layer the attention writes its merged rows already divided by Z (the unmerge's
+  // input), so no separate scaling pass runs; the extra-token rows stay as they are
+  rc = launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, Z, wsb, w, st);
   if (rc != TOMA_OK) return rc;
-  rc = launch_unmerge(s, A, Z, O, s.L, Y, wsb, w, st);
+  rc = launch_unmerge(s, A, Z, O, s.L, true, Y, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   if (s.T > 0) rc = launch_copy_extra(s, O, Y_extra_opt, st);
   return rc;

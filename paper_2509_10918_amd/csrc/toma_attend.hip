@@ -50,7 +50,8 @@ template <typename T> struct ProjPol {
   static constexpr bool A_KS = false, B_KS = true;
   const T *In, *Wt;
   T *Out;
-  int rows, C;
+  const float *Zs;  // when set: rows l < D of every sample are divided by max(Z, 1e-20)
+  int rows, C, L, D;
   __device__ __forceinline__ GemmCtx setup(int) const { return GemmCtx{rows, C, C, 0, 0, 0}; }
   __device__ __forceinline__ bool a_linear(int) const { return true; }
   __device__ __forceinline__ bool b_linear(int) const { return true; }
@@ -60,9 +61,13 @@ template <typename T> struct ProjPol {
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
                                            int lane) const {
     T *o = Out;
-    const int C_ = C;
+    const int C_ = C, L_ = L, D_ = D;
+    const float *zs = Zs;
     store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N, [=](int m, int n) { return o + (size_t)m * C_ + n; },
-                  [](int) { return 1.0f; });
+                          [=](int m) {
+                            int b = m / L_, l = m % L_;
+                            return (zs && l < D_) ? 1.0f / fmaxf(zs[(size_t)b * D_ + l], 1e-20f) : 1.0f;
+                          });
   }
 };
 
@@ -79,7 +84,7 @@ __device__ __forceinline__ void pack_probs(Frag<float> &f, const f32x4 &lo, cons
 template <typename T, int DH>
 __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *__restrict__ Kx,
                                              const T *__restrict__ V, T *__restrict__ O, int L, int H,
-                                             float scale_log2) {
+                                             float scale_log2, const float *__restrict__ Zs, int D) {
   constexpr int EPP = 16 / (int)sizeof(T);
   constexpr int LD = DH + EPP;        // LDS row stride (elements) of the K and V tiles [64][DH]
   constexpr int KK = DH / 32;         // fragments along head_dim
@@ -228,6 +233,7 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
     float inv = 1.0f / l;
     int q = q_w + 16 * qt + c;
     if (q >= L) continue;
+    if (Zs && q < D) inv /= fmaxf(Zs[(size_t)b * D + q], 1e-20f);  // unmerge input: O / Z
     T *dst = O + ((size_t)b * L + q) * Cw + h * DH + 4 * g;
 #pragma unroll
     for (int dt = 0; dt < DT; dt++) {
@@ -241,16 +247,17 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
 }
 
 template <typename T, int DH>
-static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, hipStream_t st) {
+static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, const float *Zs, hipStream_t st) {
   float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   dim3 grid((s.L + 127) / 128, s.heads, s.B);
   KernelTimer kt(K_ATTN, st);
-  hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2);
+  hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
 }
 
 template <typename T>
 static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
-                        const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w, hipStream_t st) {
+                        const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
+                        hipStream_t st) {
   T *Q = reinterpret_cast<T *>(ws + w.q), *K = reinterpret_cast<T *>(ws + w.k), *V = reinterpret_cast<T *>(ws + w.v);
   QkvPol<T> p{};
   p.Xm = static_cast<const T *>(Xm); p.Xe = static_cast<const T *>(Xe);
@@ -260,24 +267,25 @@ static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const vo
   launch_gemm<T>(K_QKV, p, s.B * s.L, s.C, s.C, 3, st);
   T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
   switch (s.head_dim) {
-    case 32: launch_attn<T, 32>(s, Q, K, V, Oh, st); break;
-    case 64: launch_attn<T, 64>(s, Q, K, V, Oh, st); break;
-    case 128: launch_attn<T, 128>(s, Q, K, V, Oh, st); break;
+    case 32: launch_attn<T, 32>(s, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
+    case 64: launch_attn<T, 64>(s, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
+    case 128: launch_attn<T, 128>(s, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
     default: return TOMA_ERR_UNSUPPORTED;
   }
   if (Wo) {
     ProjPol<T> pp{};
     pp.In = Oh; pp.Wt = static_cast<const T *>(Wo); pp.Out = static_cast<T *>(O);
-    pp.rows = s.B * s.L; pp.C = s.C;
+    pp.rows = s.B * s.L; pp.C = s.C; pp.L = s.L; pp.D = s.D; pp.Zs = Zs;
     launch_gemm<T>(K_PROJ, pp, s.B * s.L, s.C, s.C, 1, st);
   }
   return launch_status();
 }
 
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
-                  const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w, hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? attend_typed<bf16_t>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, ws, w, st)
-                              : attend_typed<float>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, ws, w, st);
+                  const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
+                  hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? attend_typed<bf16_t>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st)
+                              : attend_typed<float>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st);
 }
 
 }  // namespace toma

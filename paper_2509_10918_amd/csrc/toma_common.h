@@ -107,6 +107,26 @@ __device__ __forceinline__ Pkt pkt_load(const void *p) {
 __device__ __forceinline__ Pkt pkt_zero() { Pkt r; r.v = (u32x4){0u, 0u, 0u, 0u}; return r; }
 __device__ __forceinline__ void pkt_store(void *p, const Pkt &r) { *reinterpret_cast<u32x4 *>(p) = r.v; }
 
+// Reductions inside each row of 16 lanes with DPP-modified instructions (no LDS traffic): after
+// the call every lane of a 16-lane row holds the row's result.
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_max_f32(float v) {
+  v = fmaxf(v, dpp_f32<0xB1>(v));   // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp_f32<0x4E>(v));   // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp_f32<0x124>(v));  // row_ror 4
+  v = fmaxf(v, dpp_f32<0x128>(v));  // row_ror 8
+  return v;
+}
+__device__ __forceinline__ float row16_sum_f32(float v) {
+  v += dpp_f32<0xB1>(v);
+  v += dpp_f32<0x4E>(v);
+  v += dpp_f32<0x124>(v);
+  v += dpp_f32<0x128>(v);
+  return v;
+}
+
 // Wave-level helpers (64 lanes).
 __device__ __forceinline__ float wave_xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 __device__ __forceinline__ double wave_xor_f64(double v, int mask) { return __shfl_xor(v, mask, 64); }

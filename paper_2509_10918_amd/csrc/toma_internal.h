@@ -19,7 +19,7 @@ struct Shape {
 
 // Offsets (bytes) of the scratch sections inside the caller's workspace.
 struct Workspace {
-  size_t nrm, sim, stats, lse, zpart, os, q, k, v, oh, xm, o, total;
+  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, total;
   int stat_parts, z_parts;
 };
 
@@ -34,14 +34,17 @@ int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, char
 int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, char *ws,
                    const Workspace &w, hipStream_t st);
 int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, hipStream_t st);
+// Zs (optional): divide the merged rows of O by max(Z, 1e-20) on the way out (the unmerge input)
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
-                  const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w, hipStream_t st);
-int launch_unmerge(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, void *Y,
-                   char *ws, const Workspace &w, hipStream_t st);
+                  const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
+                  hipStream_t st);
+// prescaled: the merged rows of O were already divided by Z (see launch_attend)
+int launch_unmerge(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, bool prescaled,
+                   void *Y, char *ws, const Workspace &w, hipStream_t st);
 int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t st);
 
 // Kernel identifiers of the profiling aid (toma_profile_*): one per kernel of the path.
-enum KernelId { K_NORMS = 0, K_GRAM, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
+enum KernelId { K_GRAM = 0, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
                 K_SCALE, K_UNMERGE, K_COPY, K_COUNT };
 
 // Brackets one launch with HIP events on its stream while profiling is enabled; free otherwise.

@@ -70,16 +70,14 @@ template <typename T, bool WRITE> struct WeightsPol {
             int n = n_w + 16 * j + c;
             if (n < N) mx = fmaxf(mx, acc.t[i][j][r] * scale);
           }
-#pragma unroll
-          for (int x = 1; x < 16; x <<= 1) mx = fmaxf(mx, wave_xor_f32(mx, x));
+          mx = row16_max_f32(mx);
           float sum = 0.f;
 #pragma unroll
           for (int j = 0; j < TN; j++) {
             int n = n_w + 16 * j + c;
             if (n < N) sum += __expf(acc.t[i][j][r] * scale - mx);
           }
-#pragma unroll
-          for (int x = 1; x < 16; x <<= 1) sum += wave_xor_f32(sum, x);
+          sum = row16_sum_f32(sum);
           int m = m_w + 16 * i + 4 * g + r;
           if (c == 0 && m < M) stats[((size_t)z * M + m) * parts + part] = make_float2(mx, sum);
         }
@@ -125,26 +123,32 @@ template <typename T, bool WRITE> struct WeightsPol {
   }
 };
 
-// lse[row] = M + log(sum_i s_i exp(m_i - M)) over the row's partial (max, sum) pairs.
-__global__ void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse, int rows, int stride, int parts) {
-  int row = blockIdx.x * blockDim.x + threadIdx.x;
+// lse[row] = M + log(sum_i s_i exp(m_i - M)) over the row's partial (max, sum) pairs.  One 16-lane
+// group per row, partials strided over its lanes; the combination order is fixed.
+__global__ __launch_bounds__(256) void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse, int rows,
+                                            int stride, int parts) {
+  int row = (blockIdx.x * 256 + threadIdx.x) >> 4, c = threadIdx.x & 15;
   if (row >= rows) return;
   const float2 *s = stats + (size_t)row * stride;
   float mx = -__builtin_inff();
-  for (int i = 0; i < parts; i++) mx = fmaxf(mx, s[i].x);
+  for (int i = c; i < parts; i += 16) mx = fmaxf(mx, s[i].x);
+  mx = row16_max_f32(mx);
   float sum = 0.f;
-  for (int i = 0; i < parts; i++) sum += s[i].y * __expf(s[i].x - mx);
-  lse[row] = mx + __logf(sum);
+  for (int i = c; i < parts; i += 16) sum += s[i].y * __expf(s[i].x - mx);
+  sum = row16_sum_f32(sum);
+  if (c == 0) lse[row] = mx + __logf(sum);
 }
 
-// Z[j] = sum of the partial row sums, in index order (fixed order: reruns are bit-identical).
-__global__ void k_zsum(const float *__restrict__ zpart, float *__restrict__ Z, int rows, int stride, int parts) {
-  int row = blockIdx.x * blockDim.x + threadIdx.x;
+// Z[j] = sum of the partial row sums (fixed order: reruns are bit-identical).
+__global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, float *__restrict__ Z, int rows,
+                                             int stride, int parts) {
+  int row = (blockIdx.x * 256 + threadIdx.x) >> 4, c = threadIdx.x & 15;
   if (row >= rows) return;
   const float *s = zpart + (size_t)row * stride;
   float sum = 0.f;
-  for (int i = 0; i < parts; i++) sum += s[i];
-  Z[row] = sum;
+  for (int i = c; i < parts; i += 16) sum += s[i];
+  sum = row16_sum_f32(sum);
+  if (c == 0) Z[row] = sum;
 }
 
 // ---- merge -------------------------------------------------------------------------------------
@@ -182,7 +186,8 @@ template <typename T> struct UnmergePol {
   static constexpr bool A_KS = true, B_KS = true;
   RegionView<T> v;
   const T *A;
-  const T *Os;  // [B][D][C], already divided by Z
+  const T *Os;  // [B][os_rows][C], rows [0, D) already divided by Z
+  int os_rows;
   T *Y;
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Nr, v.C, v.Dr, bz / v.R, bz % v.R, bz};
@@ -193,7 +198,7 @@ template <typename T> struct UnmergePol {
     return A + ((size_t)x.z * x.K + k) * x.M + m;
   }
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
-    return Os + ((size_t)x.b * v.D + x.rho * v.Dr + k) * v.C + n;
+    return Os + ((size_t)x.b * os_rows + x.rho * v.Dr + k) * v.C + n;
   }
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
@@ -249,7 +254,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   float *lse = reinterpret_cast<float *>(ws + w.lse);
   int rows = batch * s.Nr;
   { KernelTimer kt(K_LSE, st);
-    hipLaunchKernelGGL(k_lse, dim3((rows + 255) / 256), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n); }
+    hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n); }
   WeightsPol<T, true> p2{};
   p2.v = p1.v; p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
   p2.A = static_cast<T *>(A);
@@ -257,7 +262,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
   int zr = s.B * s.D;
   { KernelTimer kt(K_ZSUM, st);
-    hipLaunchKernelGGL(k_zsum, dim3((zr + 255) / 256), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
+    hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
   return launch_status();
 }
 
@@ -281,24 +286,29 @@ int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, v
 }
 
 template <typename T>
-static int unmerge_typed(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, void *Y,
-                         char *ws, const Workspace &w, hipStream_t st) {
-  T *Os = reinterpret_cast<T *>(ws + w.os);
-  size_t total = (size_t)s.B * s.D * s.C;
-  { KernelTimer kt(K_SCALE, st);
-  hipLaunchKernelGGL(k_scale_rows<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                     static_cast<const T *>(O), Z, Os, s.D, o_rows, s.C, total); }
+static int unmerge_typed(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, bool prescaled,
+                         void *Y, char *ws, const Workspace &w, hipStream_t st) {
   UnmergePol<T> p{};
+  if (prescaled) {
+    p.Os = static_cast<const T *>(O); p.os_rows = o_rows;
+  } else {
+    T *Os = reinterpret_cast<T *>(ws + w.os);
+    size_t total = (size_t)s.B * s.D * s.C;
+    KernelTimer kt(K_SCALE, st);
+    hipLaunchKernelGGL(k_scale_rows<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const T *>(O), Z, Os, s.D, o_rows, s.C, total);
+    p.Os = Os; p.os_rows = s.D;
+  }
   p.v = make_view<T>(s, nullptr);
-  p.A = static_cast<const T *>(A); p.Os = Os; p.Y = static_cast<T *>(Y);
+  p.A = static_cast<const T *>(A); p.Y = static_cast<T *>(Y);
   launch_gemm<T>(K_UNMERGE, p, s.Nr, s.C, s.Dr, s.B * s.R, st);
   return launch_status();
 }
 
-int launch_unmerge(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, void *Y, char *ws,
-                   const Workspace &w, hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? unmerge_typed<bf16_t>(s, A, Z, O, o_rows, Y, ws, w, st)
-                              : unmerge_typed<float>(s, A, Z, O, o_rows, Y, ws, w, st);
+int launch_unmerge(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, bool prescaled,
+                   void *Y, char *ws, const Workspace &w, hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? unmerge_typed<bf16_t>(s, A, Z, O, o_rows, prescaled, Y, ws, w, st)
+                              : unmerge_typed<float>(s, A, Z, O, o_rows, prescaled, Y, ws, w, st);
 }
 
 int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t st) {

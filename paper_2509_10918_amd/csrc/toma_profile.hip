@@ -7,7 +7,7 @@
 
 namespace toma {
 
-static const char *const kNames[K_COUNT] = {"norms", "gram", "greedy", "weights_stats", "lse", "weights_write",
+static const char *const kNames[K_COUNT] = {"gram", "greedy", "weights_stats", "lse", "weights_write",
                                             "zsum", "merge", "qkv", "attention", "proj", "scale_rows",
                                             "unmerge", "copy_extra"};
 struct Rec { int id; hipEvent_t a, b; };

@@ -1,8 +1,7 @@
 // Destination selection: cosine similarity inside each region and the greedy facility-location
 // pick sequence (paper Sec. 4.1, Eq. 2, Alg. 2; regions as in Alg. 3 step 1).
 //
-// Three kernels:
-//   k_norms   ||x_n||_2 of every token, accumulated in double.
+// Two kernels:
 //   k_gram    S = cos(x_i, x_j) per region with the fp64 matrix cores (v_mfma_f64_16x16x4_f64):
 //             products of stored bf16 / fp32 values are exact in double, so S is the similarity
 //             to ~1e-16 before it is rounded once to the nearest multiple of 2^-22 and stored as
@@ -22,31 +21,13 @@ namespace toma {
 constexpr double kSimScale = 4194304.0;
 
 // ------------------------------------------------------------------------------------------------
+// 64 x 64 block of one region's similarity matrix per workgroup, 2 x 2 waves of 32 x 32.  S is
+// symmetric: only blocks on or above the diagonal are computed and each value is stored twice.
+// The token norms come out of the same pass: while a K slice sits in LDS, the first 128 threads add
+// the squares of one row each (64 rows of the left operand, 64 of the right) in double.
 template <typename T>
-__global__ __launch_bounds__(256) void k_norms(const T *__restrict__ X, double *__restrict__ nrm, int rows, int C) {
-  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  int lane = threadIdx.x & 63;
-  if (row >= rows) return;
-  const T *x = X + (size_t)row * C;
-  double acc = 0.0;
-  for (int c = lane; c < C; c += kWave) {
-    double v = (double)to_f32(x[c]);
-    acc += v * v;
-  }
-#pragma unroll
-  for (int m = 1; m < kWave; m <<= 1) acc += wave_xor_f64(acc, m);
-  if (lane == 0) {
-    double n = sqrt(acc);
-    nrm[row] = n > 1e-12 ? n : 1e-12;
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// 64 x 64 block of one region's similarity matrix per workgroup, 2 x 2 waves of 32 x 32.
-template <typename T>
-__global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, const double *__restrict__ nrm,
-                                             int32_t *__restrict__ S, RegionMap map, int N, int C, int P,
-                                             int n_loc) {
+__global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *__restrict__ S, RegionMap map,
+                                             int N, int C, int P, int n_loc, int tiles) {
   constexpr int BK = 32;
   constexpr int EPP = 16 / (int)sizeof(T);
   constexpr int LDK = BK + EPP;
@@ -54,9 +35,14 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, const dou
   constexpr int NP = 64 * PPR / 256;
   __shared__ __align__(16) T As[64 * LDK];
   __shared__ __align__(16) T Bs[64 * LDK];
+  __shared__ double nrm[128];
 
-  const int bp = blockIdx.z, b = bp / P, p = bp % P;
-  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  // blockIdx.x enumerates the pairs (tm <= tn) row by row
+  int tm = 0, rest = blockIdx.x;
+  while (rest >= tiles - tm) { rest -= tiles - tm; tm++; }
+  const int tn = tm + rest;
+  const int bp = blockIdx.y, b = bp / P, p = bp % P;
+  const int m0 = tm * 64, n0 = tn * 64;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
   const int g = lane >> 4, c = lane & 15;
   const T *Xb = X + (size_t)b * N * C;
@@ -77,14 +63,16 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, const dou
   for (int i = 0; i < 2; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++) acc[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
+  double sq = 0.0;
+  const T *my_row = tid < 64 ? As + tid * LDK : Bs + (tid - 64) * LDK;
 
-  for (int k0 = 0; k0 < C; k0 += BK) {
-    Pkt ra[NP], rb[NP];
+  Pkt ra[NP], rb[NP];
 #pragma unroll
-    for (int i = 0; i < NP; i++) {
-      ra[i] = pa[i] ? pkt_load(pa[i] + k0) : pkt_zero();
-      rb[i] = pb[i] ? pkt_load(pb[i] + k0) : pkt_zero();
-    }
+  for (int i = 0; i < NP; i++) {
+    ra[i] = pa[i] ? pkt_load(pa[i]) : pkt_zero();
+    rb[i] = pb[i] ? pkt_load(pb[i]) : pkt_zero();
+  }
+  for (int k0 = 0; k0 < C; k0 += BK) {
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < NP; i++) {
@@ -92,6 +80,20 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, const dou
       pkt_store(Bs + lo[i], rb[i]);
     }
     __syncthreads();
+    if (k0 + BK < C) {
+#pragma unroll
+      for (int i = 0; i < NP; i++) {
+        ra[i] = pa[i] ? pkt_load(pa[i] + k0 + BK) : pkt_zero();
+        rb[i] = pb[i] ? pkt_load(pb[i] + k0 + BK) : pkt_zero();
+      }
+    }
+    if (tid < 128) {
+#pragma unroll
+      for (int k = 0; k < BK; k++) {
+        double v = (double)to_f32(my_row[k]);
+        sq += v * v;
+      }
+    }
     Frag<T> fa[2], fb[2];
 #pragma unroll
     for (int i = 0; i < 2; i++) {
@@ -99,31 +101,36 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, const dou
       frag_load_kc(fb[i], Bs + (wn * 32 + 16 * i + c) * LDK + 8 * g);
     }
 #pragma unroll
-    for (int s = 0; s < 8; s++)
+    for (int s8 = 0; s8 < 8; s8++)
 #pragma unroll
       for (int i = 0; i < 2; i++)
 #pragma unroll
         for (int j = 0; j < 2; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)to_f32(fa[i].v[s]), (double)to_f32(fb[j].v[s]),
+          acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)to_f32(fa[i].v[s8]), (double)to_f32(fb[j].v[s8]),
                                                            acc[i][j], 0, 0, 0);
   }
+  if (tid < 128) {
+    double n = sqrt(sq);
+    nrm[tid] = n > 1e-12 ? n : 1e-12;
+  }
+  __syncthreads();
 
   // fp64 accumulator tile: lane holds column lane % 16 and rows (lane / 16) + 4 r.
-  const double *nb = nrm + (size_t)b * N;
   int32_t *Sr = S + (size_t)bp * n_loc * n_loc;
 #pragma unroll
   for (int j = 0; j < 2; j++) {
-    int col = n0 + wn * 32 + 16 * j + c;
+    int cl = wn * 32 + 16 * j + c, col = n0 + cl;
     if (col >= n_loc) continue;
-    double ncol = nb[map.token(p, col)];
+    double ncol = nrm[64 + cl];
 #pragma unroll
     for (int i = 0; i < 2; i++)
 #pragma unroll
       for (int r = 0; r < 4; r++) {
-        int row = m0 + wm * 32 + 16 * i + g + 4 * r;
+        int rl = wm * 32 + 16 * i + g + 4 * r, row = m0 + rl;
         if (row < n_loc) {
-          double den = nb[map.token(p, row)] * ncol;
-          Sr[(size_t)row * n_loc + col] = (int32_t)rint(acc[i][j][r] / den * kSimScale);
+          int32_t v = (int32_t)rint(acc[i][j][r] / (nrm[rl] * ncol) * kSimScale);
+          Sr[(size_t)row * n_loc + col] = v;
+          if (tm != tn) Sr[(size_t)col * n_loc + row] = v;
         }
       }
   }
@@ -234,6 +241,23 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
     if (!first) part -= msum;
     return wave_sum_u32((uint32_t)part);
   };
+  // the same, and the row is also posted to rowbuf[buf][w] (one dispatch for both)
+  auto eval_post = [&](int buf, int r) -> uint32_t {
+    int32_t part = 0;
+    switch (r) {
+#define TOMA_EVALP_CASE(R)                                                       \
+  case R:                                                                        \
+    _Pragma("unroll") for (int u = 0; u < CPL; u++) {                            \
+      part += max(s[R][u], m[u]);                                                \
+      rowbuf[buf][w][lane + 64 * u] = s[R][u];                                   \
+    }                                                                            \
+    break;
+      TOMA_ROWS32(TOMA_EVALP_CASE)
+#undef TOMA_EVALP_CASE
+    }
+    part -= msum;
+    return wave_sum_u32((uint32_t)part);
+  };
   // refresh the keys of all live rows of this wave at once (straight-line code, independent chains)
   auto eval_all = [&](bool first) {
 #pragma unroll
@@ -265,8 +289,20 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
     return ((unsigned long long)k << 8) | (unsigned)(255 - (32 * w + r));
   };
 
+  // LDS traffic is the only thing the waves exchange inside the loop: wait for it, then meet
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  };
+  // picks and their values are kept in registers of wave 0 (pick k in lane k % 64) and written
+  // once at the end, so that no global store sits on the loop's critical path
+  int32_t pick_row[CPL];
+  uint32_t pick_key[CPL];
+#pragma unroll
+  for (int u = 0; u < CPL; u++) { pick_row[u] = 0; pick_key[u] = 0; }
+
   if (threadIdx.x < 12) slot[threadIdx.x / 4][threadIdx.x % 4] = 0;
-  __syncthreads();
+  lds_barrier();
 
   int q3 = 0;  // step % 3
   for (int step = 0; step < d_loc; step++) {
@@ -285,10 +321,13 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
         int r = __builtin_ctzll(__ballot(key == top && lane < 32));
         uint32_t g = top;
         if (!first) {
-          g = eval(r, false) + 1u;
-          if (lane == r) { key = g; fresh = true; }
+          g = eval_post(buf, r) + 1u;
+          const bool mine = lane == r;
+          key = mine ? g : key;
+          fresh = mine;
+        } else {
+          post_row(buf, r);
         }
-        post_row(buf, r);
         uint32_t rest = first ? 0u : wave_max32_u32(lane == r ? 0u : key);
         unsigned long long rest_lanes = __ballot(key == rest && lane < 32 && lane != r);
         if (lane == 0) {
@@ -297,7 +336,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
     if (threadIdx.x < 4) slot[q3 == 0 ? 2 : q3 - 1][threadIdx.x] = 0;  // the slots of round step + 2
     unsigned long long best = read_slot(&sl[0]);
     if (!first) {
@@ -315,7 +354,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
             int r = __builtin_ctzll(need);
             need &= need - 1;
             uint32_t g = eval(r, false) + 1u;
-            if (lane == r) key = g;
+            key = lane == r ? g : key;
           }
         }
         uint32_t top = wave_max32_u32(key);
@@ -324,7 +363,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
           post_row(buf, r);
           if (lane == 0) atomicMax(&sl[2], pack(top, r));
         }
-        __syncthreads();
+        lds_barrier();
         best = read_slot(&sl[2]);
       }
     }
@@ -339,31 +378,37 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
       msum += m[u];
     }
     if (first && my_live0) key = 0xffffffffu;  // row sums are no bounds on later values: force a refresh
-    if (w == ww && lane == (I & 31)) key = 0;
-    if (threadIdx.x == 0) {
-      idx[(size_t)bp * d_loc + step] = map.token(p, I);
-      if (gain_out) {
-        double v = first ? (double)G - 1.0 - (double)kBias0 : (double)G - 1.0;
-        gain_out[(size_t)bp * d_loc + step] = (float)(v / kSimScale);
-      }
+    key = (w == ww && lane == (I & 31)) ? 0u : key;
+#pragma unroll
+    for (int u = 0; u < CPL; u++) {
+      const bool here = step == lane + 64 * u;
+      pick_row[u] = here ? I : pick_row[u];
+      pick_key[u] = here ? G : pick_key[u];
     }
     q3 = q3 == 2 ? 0 : q3 + 1;
+  }
+  if (w == 0) {
+#pragma unroll
+    for (int u = 0; u < CPL; u++) {
+      const int k = lane + 64 * u;
+      if (k < d_loc) {
+        idx[(size_t)bp * d_loc + k] = map.token(p, pick_row[u]);
+        const double v = (double)pick_key[u] - 1.0 - (k == 0 ? (double)kBias0 : 0.0);
+        if (gain_out) gain_out[(size_t)bp * d_loc + k] = (float)(v / kSimScale);
+      }
+    }
   }
 }
 
 template <typename T>
 static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, char *ws, const Workspace &w,
                         hipStream_t st) {
-  double *nrm = reinterpret_cast<double *>(ws + w.nrm);
   int32_t *S = reinterpret_cast<int32_t *>(ws + w.sim);
   RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
-  int rows = s.B * s.N;
-  { KernelTimer kt(K_NORMS, st);
-  hipLaunchKernelGGL(k_norms<T>, dim3((rows + 3) / 4), dim3(256), 0, st, X, nrm, rows, s.C); }
   int tiles = (s.n_loc + 63) / 64;
   { KernelTimer kt(K_GRAM, st);
-  hipLaunchKernelGGL(k_gram<T>, dim3(tiles, tiles, s.B * s.P), dim3(256), 0, st, X, nrm, S, map, s.N, s.C, s.P,
-                     s.n_loc); }
+  hipLaunchKernelGGL(k_gram<T>, dim3(tiles * (tiles + 1) / 2, s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C,
+                     s.P, s.n_loc, tiles); }
   int regions = s.B * s.P;
   KernelTimer kt(K_GREEDY, st);
   switch (s.n_loc / 16) {
