@@ -11,6 +11,8 @@
 //                    from accumulators straight back into the matrix cores without touching LDS.
 //                    V^T fragments come from the row-major V tile through the LDS transpose read.
 //   k_gemm<ProjPol>  optional output projection.
+#include <type_traits>
+
 #include "toma_gemm.h"
 #include "toma_internal.h"
 
@@ -73,8 +75,9 @@ template <typename T> struct ProjPol {
 
 // Probabilities (fp32 accumulator registers) -> B-operand fragment slots.
 __device__ __forceinline__ void pack_probs(Frag<bf16_t> &f, const f32x4 &lo, const f32x4 &hi) {
-#pragma unroll
-  for (int r = 0; r < 4; r++) { f.v[r] = (bf16_t)lo[r]; f.v[4 + r] = (bf16_t)hi[r]; }
+  typedef float f32x8 __attribute__((ext_vector_type(8)));
+  f32x8 all = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  f.v = __builtin_convertvector(all, bf16x8);  // four packed conversions
 }
 __device__ __forceinline__ void pack_probs(Frag<float> &f, const f32x4 &lo, const f32x4 &hi) {
 #pragma unroll
@@ -246,11 +249,201 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
   }
 }
 
+// The same attention with K and V tiles copied global -> LDS by the load-to-LDS path through a ring
+// of three tiles (one barrier per 64 keys, two tiles of loads in flight behind the matrix cores)
+// and bank-conflict-free swizzled tiles; the softmax scale is folded into the exponent's FMA.
+template <typename T, int DH>
+__global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, const T *__restrict__ Kx,
+                                                   const T *__restrict__ V, T *__restrict__ O, int L, int H,
+                                                   float scale_log2, const float *__restrict__ Zs, int D) {
+  constexpr int ES = (int)sizeof(T), EPP = 16 / ES;
+  constexpr int PPR = DH / EPP;       // 16-byte packets per K / V row
+  constexpr int KK = DH / 32, DT = DH / 16, QT = 2, STAGES = 3;
+  constexpr int CH = PPR;             // 1 KiB chunks per 64-row tile
+  constexpr int NI = CH / 4;          // load instructions per wave per tile, for K and for V
+  constexpr int TILE = 64 * DH;
+  __shared__ __align__(1024) T Ks[STAGES][TILE];
+  __shared__ __align__(1024) T Vs[STAGES][TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const size_t head = ((size_t)b * H + h) * L * DH;
+  const T *Qh = Q + head, *Kh = Kx + head, *Vh = V + head;
+  const int q_w = blockIdx.x * 128 + w * 32;
+  const int nt = (L + 63) / 64;
+
+  Frag<T> fq[QT][KK];
+#pragma unroll
+  for (int qt = 0; qt < QT; qt++) {
+    int q = q_w + 16 * qt + c;
+    q = q < L ? q : L - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) {
+      const T *src = Qh + (size_t)q * DH + 32 * kk + 8 * g;
+      if constexpr (sizeof(T) == 2) {
+        Pkt pk = pkt_load(src);
+        fq[qt][kk] = __builtin_bit_cast(Frag<T>, pk);
+      } else {
+        Pkt p0 = pkt_load(src), p1 = pkt_load(src + 4);
+        struct { Pkt a, b; } two = {p0, p1};
+        fq[qt][kk] = __builtin_bit_cast(Frag<T>, two);
+      }
+    }
+  }
+
+  // what this lane fetches for its chunks: tile row and element offset inside the row
+  int k_row[NI];
+  const T *kp[NI], *vp[NI];
+#pragma unroll
+  for (int t = 0; t < NI; t++) {
+    const int ch = w * NI + t, row = ch * (64 / PPR) + lane / PPR, pos = lane % PPR;
+    k_row[t] = row;
+    kp[t] = Kh + (size_t)row * DH + ((pos & ~7) | ((pos ^ row) & 7)) * EPP;
+    vp[t] = Vh + (size_t)row * DH + (pos ^ ((row & 3) << 1)) * EPP;
+  }
+  auto issue = [&](int st, int it) {
+    const ptrdiff_t adv = (ptrdiff_t)it * 64 * DH;
+    const bool last = (it + 1) * 64 > L;  // rows past the end repeat row L - 1 and are masked below
+#pragma unroll
+    for (int t = 0; t < NI; t++) {
+      ptrdiff_t a = adv;
+      if (last && it * 64 + k_row[t] >= L) a = (ptrdiff_t)(L - 1 - k_row[t]) * DH;
+      load_to_lds16(kp[t] + a, Ks[st] + (w * NI + t) * (1024 / ES));
+      load_to_lds16(vp[t] + a, Vs[st] + (w * NI + t) * (1024 / ES));
+    }
+  };
+
+  f32x4 oacc[DT][QT];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) oacc[dt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m_run[QT], l_run[QT];  // running maximum (of the raw scores) and sum per query
+#pragma unroll
+  for (int qt = 0; qt < QT; qt++) { m_run[qt] = -__builtin_inff(); l_run[qt] = 0.f; }
+
+  // the query loads must have landed before the ring starts: from here on only the ring's own
+  // loads are outstanding, and only the waits below order them
+  wait_vmcnt<0>();
+  issue(0, 0);
+  if (nt > 1) issue(1, 1);
+  // one step per 64 keys; the ring position is a compile-time constant of each of the three
+  // unrolled copies, so LDS addresses of the fragment reads are loop-invariant plus an immediate
+  auto tile_step = [&](auto stage_c, int it) {
+    constexpr int ST = decltype(stage_c)::value;
+    if (it + 1 < nt) wait_vmcnt<2 * NI>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (it + 2 < nt) issue((ST + 2) % STAGES, it + 2);
+    const T *kt_ = Ks[ST], *vt_ = Vs[ST];
+    const int key0 = it * 64;
+
+    f32x4 st[4][QT];
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++)
+#pragma unroll
+      for (int kt = 0; kt < 4; kt++) {
+        Frag<T> fk;
+        frag_load_kcw_sw<PPR>(fk, kt_, 16 * kt + c, 32 * kk + 8 * g);
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+          if (kk == 0) st[kt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          mma16(st[kt][qt], fk, fq[qt][kk]);
+        }
+      }
+
+    if (key0 + 64 > L) {  // only the last tile can reach past the end (uniform branch)
+#pragma unroll
+      for (int qt = 0; qt < QT; qt++)
+#pragma unroll
+        for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+          for (int r = 0; r < 4; r++)
+            if (key0 + 16 * kt + 4 * g + r >= L) st[kt][qt][r] = -__builtin_inff();
+    }
+    Frag<T> fp[QT][2];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+      float mx = st[0][qt][0];
+#pragma unroll
+      for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) mx = fmaxf(mx, st[kt][qt][r]);
+      mx = fmaxf(mx, wave_xor_f32(mx, 16));
+      mx = fmaxf(mx, wave_xor_f32(mx, 32));
+      const float m_new = fmaxf(m_run[qt], mx);
+      const bool grew = __any(m_new != m_run[qt]);  // the output is rescaled only when some maximum moved
+      const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * scale_log2);
+      const float mc = m_new * scale_log2;
+      m_run[qt] = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][qt][r], scale_log2, -mc));
+          st[kt][qt][r] = pv;
+          psum += pv;
+        }
+      l_run[qt] = l_run[qt] * alpha + psum;
+      if (grew) {
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int r = 0; r < 4; r++) oacc[dt][qt][r] *= alpha;
+      }
+      pack_probs(fp[qt][0], st[0][qt], st[1][qt]);
+      pack_probs(fp[qt][1], st[2][qt], st[3][qt]);
+    }
+
+#pragma unroll
+    for (int u = 0; u < 2; u++)
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++) {
+        Frag<T> fv;
+        frag_load_ks_sw<PPR>(fv, vt_, 32 * u + 4 * g, 32 * u + 16 + 4 * g, 16 * dt, lane);
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) mma16(oacc[dt][qt], fv, fp[qt][u]);
+      }
+  };
+  for (int it = 0; it < nt; it += 3) {
+    tile_step(std::integral_constant<int, 0>{}, it);
+    if (it + 1 < nt) tile_step(std::integral_constant<int, 1>{}, it + 1);
+    if (it + 2 < nt) tile_step(std::integral_constant<int, 2>{}, it + 2);
+  }
+
+  const int Cw = H * DH;
+#pragma unroll
+  for (int qt = 0; qt < QT; qt++) {
+    float l = l_run[qt];
+    l += wave_xor_f32(l, 16);
+    l += wave_xor_f32(l, 32);
+    float inv = 1.0f / l;
+    int q = q_w + 16 * qt + c;
+    if (q >= L) continue;
+    if (Zs && q < D) inv /= fmaxf(Zs[(size_t)b * D + q], 1e-20f);  // unmerge input: O / Z
+    T *dst = O + ((size_t)b * L + q) * Cw + h * DH + 4 * g;
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) {
+      alignas(16) T o[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++) o[r] = from_f32<T>(oacc[dt][qt][r] * inv);
+      if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst + 16 * dt) = *reinterpret_cast<u32x2 *>(o);
+      else *reinterpret_cast<u32x4 *>(dst + 16 * dt) = *reinterpret_cast<u32x4 *>(o);
+    }
+  }
+}
+
 template <typename T, int DH>
 static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, const float *Zs, hipStream_t st) {
   float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   dim3 grid((s.L + 127) / 128, s.heads, s.B);
   KernelTimer kt(K_ATTN, st);
+  // load-to-LDS pipeline when a row is at least eight packets and three tiles fit the LDS
+  constexpr int kRowPackets = DH * (int)sizeof(T) / 16;
+  if constexpr (kRowPackets >= 8 && 3 * 2 * 64 * DH * (int)sizeof(T) <= 160 * 1024 - 4096) {
+    hipLaunchKernelGGL((k_attn_async<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+    return;
+  }
   hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
 }
 

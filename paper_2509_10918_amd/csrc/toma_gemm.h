@@ -175,6 +175,10 @@ template <typename T> struct SwzTile {
   static constexpr int EPP = 16 / ES;
   // k-contiguous tile: 128-byte rows of 8 packets; packet kp of row r sits at slot kp ^ (r & 7)
   __device__ static __forceinline__ int kc(int row, int kp) { return row * (128 / ES) + ((kp ^ (row & 7)) * EPP); }
+  // k-contiguous tile with rows of PPR >= 8 packets: the same swizzle inside each group of 8
+  template <int PPR> __device__ static __forceinline__ int kcw(int row, int kp) {
+    return (row * PPR + ((kp & ~7) | ((kp ^ row) & 7))) * EPP;
+  }
   // k-major tile: rows of PPR packets; packet pi of row k sits at slot pi ^ ((k & 3) << 1)
   template <int PPR> __device__ static __forceinline__ int ks(int k, int pi) {
     return (k * PPR + (pi ^ ((k & 3) << 1))) * EPP;
@@ -217,6 +221,17 @@ __device__ __forceinline__ void frag_load_kc_sw(Frag<float> &f, const float *til
 // One load-to-LDS instruction: lane l's 16 bytes at gptr land at lds_chunk + 16 l.  Issued as
 // assembly so that the pipeline's own s_waitcnt vmcnt(n) (below) decides when a tile is complete;
 // the compiler's model would otherwise drain every outstanding load before each LDS read.
+// eight consecutive k starting at element kf of a row of PPR packets
+template <int PPR> __device__ __forceinline__ void frag_load_kcw_sw(Frag<bf16_t> &f, const bf16_t *tile, int row, int kf) {
+  f.v = *reinterpret_cast<const bf16x8 *>(tile + SwzTile<bf16_t>::kcw<PPR>(row, kf >> 3));
+}
+template <int PPR> __device__ __forceinline__ void frag_load_kcw_sw(Frag<float> &f, const float *tile, int row, int kf) {
+  f32x4 a = *reinterpret_cast<const f32x4 *>(tile + SwzTile<float>::kcw<PPR>(row, kf >> 2));
+  f32x4 b = *reinterpret_cast<const f32x4 *>(tile + SwzTile<float>::kcw<PPR>(row, (kf >> 2) + 1));
+#pragma unroll
+  for (int i = 0; i < 4; i++) { f.v[i] = a[i]; f.v[4 + i] = b[i]; }
+}
+
 template <typename T>
 __device__ __forceinline__ void load_to_lds16(const T *gptr, T *lds_chunk) {
   uint32_t lds_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds_chunk;
