@@ -405,6 +405,70 @@ ORACLE_API void toma_oracle_attend(int B, int D, int T, int C, int heads, const 
   free(U); free(Q); free(K); free(V); free(Oh);
 }
 
+/* The same attention (Eq. 1) evaluated only for the query rows listed in rows[] (indices into
+ * the B*L rows of U); keys and values are still formed from every token.  out is [nrows][C].
+ * Lets a test check sampled rows of a workload whose full attention is too slow in fp64. */
+ORACLE_API void toma_oracle_attend_rows(int B, int D, int T, int C, int heads, const double *Xm,
+                                        const double *Xe, const double *Wq, const double *Wk,
+                                        const double *Wv, const int32_t *rows, int nrows, double *out) {
+  int L = D + T, dh = C / heads;
+  size_t per = (size_t)L * C;
+  double *U = (double *)malloc(sizeof(double) * per * B);
+  double *K = (double *)malloc(sizeof(double) * per * B);
+  double *V = (double *)malloc(sizeof(double) * per * B);
+  for (int b = 0; b < B; b++) {
+    memcpy(U + b * per, Xm + (size_t)b * D * C, sizeof(double) * (size_t)D * C);
+    if (T > 0) memcpy(U + b * per + (size_t)D * C, Xe + (size_t)b * T * C, sizeof(double) * (size_t)T * C);
+  }
+#pragma omp parallel for schedule(dynamic)
+  for (int r = 0; r < B * L; r++) {
+    const double *u = U + (size_t)r * C;
+    double *k = K + (size_t)r * C, *v = V + (size_t)r * C;
+    for (int n = 0; n < C; n++) { k[n] = 0.0; v[n] = 0.0; }
+    for (int c = 0; c < C; c++) {
+      double uc = u[c];
+      const double *wk = Wk + (size_t)c * C, *wv = Wv + (size_t)c * C;
+      for (int n = 0; n < C; n++) { k[n] += uc * wk[n]; v[n] += uc * wv[n]; }
+    }
+  }
+  double inv = 1.0 / sqrt((double)dh);
+#pragma omp parallel for schedule(dynamic)
+  for (int i = 0; i < nrows; i++) {
+    int r = rows[i], b = r / L;
+    const double *u = U + (size_t)r * C;
+    double *q = (double *)malloc(sizeof(double) * (size_t)C);
+    double *p = (double *)malloc(sizeof(double) * (size_t)L);
+    for (int n = 0; n < C; n++) q[n] = 0.0;
+    for (int c = 0; c < C; c++) {
+      double uc = u[c];
+      const double *wq = Wq + (size_t)c * C;
+      for (int n = 0; n < C; n++) q[n] += uc * wq[n];
+    }
+    for (int h = 0; h < heads; h++) {
+      const double *qh = q + (size_t)h * dh;
+      double mx = -INFINITY, den = 0.0;
+      for (int j = 0; j < L; j++) {
+        const double *k = K + ((size_t)b * L + j) * C + (size_t)h * dh;
+        double sc = 0.0;
+        for (int c = 0; c < dh; c++) sc += qh[c] * k[c];
+        p[j] = sc * inv;
+        if (p[j] > mx) mx = p[j];
+      }
+      for (int j = 0; j < L; j++) { p[j] = exp(p[j] - mx); den += p[j]; }
+      double *o = out + (size_t)i * C + (size_t)h * dh;
+      for (int c = 0; c < dh; c++) o[c] = 0.0;
+      for (int j = 0; j < L; j++) {
+        double wgt = p[j] / den;
+        const double *v = V + ((size_t)b * L + j) * C + (size_t)h * dh;
+        for (int c = 0; c < dh; c++) o[c] += wgt * v[c];
+      }
+    }
+    free(q);
+    free(p);
+  }
+  free(U); free(K); free(V);
+}
+
 /* Sec. 4.2.2 (transpose unmerge): X'_unmerged = A~^T X', i.e. for source s of merge region rho
  * Y[token(rho, s)] = sum_{j in rho} A~_js O[j].  O is [B][o_rows][C] and only its first D rows
  * (the merged image tokens) are read; Y is [B][N][C] in grid order. */

@@ -162,6 +162,20 @@ def attend(Xm, Xe, Wq, Wk, Wv, heads, Wo=None):
     return O
 
 
+def attend_rows(Xm, Xe, Wq, Wk, Wv, heads, rows):
+    """Attention output for the listed rows only (rows index the B*(D+T) token rows)."""
+    Xm = _f64(Xm)
+    B, D, C = Xm.shape
+    T = 0 if Xe is None else Xe.shape[1]
+    Xe_p = None if Xe is None else _f64(Xe)
+    Wq, Wk, Wv = _f64(Wq), _f64(Wk), _f64(Wv)
+    rows = _i32(rows)
+    out = np.empty((len(rows), C), np.float64)
+    lib().toma_oracle_attend_rows(B, D, T, C, heads, _d(Xm), None if Xe_p is None else _d(Xe_p),
+                                  _d(Wq), _d(Wk), _d(Wv), _i(rows), len(rows), _d(out))
+    return out
+
+
 def unmerge(d, A, Z, O):
     A, Z, O = _f64(A), _f64(Z), _f64(O)
     N = d.H * d.W

@@ -1,0 +1,119 @@
+"""GPU parity at the full sizes of the benchmark workloads, in the launch configuration bench.py
+times (toma_layer through the C ABI).  SDXL stage 1 / stage 2 and the Flux-shaped block are checked
+against the complete fp64 oracle; the 128 x 128 high-resolution sequence is checked completely once
+(global merge, step 0) and on sampled regions along its reuse schedule (region-local merge)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_10918_amd import binding as tb
+from paper_2509_10918_amd import synth
+
+import toma_gpu as tg
+
+pytestmark = pytest.mark.gpu
+W = synth.WORKLOADS
+
+
+def _f64(a):
+    return None if a is None else np.asarray(a, dtype=np.float64)
+
+
+def _report(name, got, ref, tol):
+    err = tg.max_rel(got, ref)
+    print(f"  {name}: max|err|/max|ref| = {err:.3e} (tol {tol:g})", flush=True)
+    assert np.all(np.isfinite(got)) and err <= tol, name
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("tile_local", [False, True])
+@pytest.mark.parametrize("name", ["sdxl1", "sdxl2", "flux"])
+def test_full_workload_layer(oracle, name, tile_local):
+    w = W[name]
+    R = w.P if tile_local else 1
+    tol = tg.TOL[w.dtype]
+    print(f"[full] {name} merge_regions={R}: B={w.B} N={w.N} C={w.C} D={w.D} heads={w.heads} T={w.T_extra}",
+          flush=True)
+    inp = synth.make_inputs(w)
+    X, Xe = _f64(inp["X"]), _f64(inp["X_extra"])
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    d = tg.oracle_desc(oracle, w, R)
+    ref = oracle.layer(d, X, *Wts, heads=w.heads, Xe=Xe)
+    print(f"  oracle done; destinations with Z < 1e-20: {ref['clamps']}", flush=True)
+    dv = tg.Device(w, inp, R)
+    Y, Ye = dv.layer(0)
+    bad, near, forced = tg.compare_picks(oracle, w, X, dv.idx.cpu().numpy())
+    print(f"  near-tie steps {near}, regions verified teacher-forced {forced}, mismatching {bad}", flush=True)
+    assert not bad
+    _report("Z", tg.host(dv.Z), ref["Z"], tol)
+    _report("Y", Y, ref["Y"], tol)
+    if Ye is not None:
+        _report("Y_extra", Ye, ref["Y_extra"], tol)
+    # stage-isolated merge at full size (fed the oracle's picks)
+    _, Z, Xm = dv.merge(idx=ref["idx"])
+    _report("Xm", Xm, ref["Xm"], tol)
+    # cached variants reproduce the full call bit for bit on unchanged tokens
+    Yi, _ = dv.layer(tb.TOMA_REUSE_IDX)
+    Ya, _ = dv.layer(tb.TOMA_REUSE_A)
+    assert np.array_equal(Yi, Y) and np.array_equal(Ya, Y)
+
+
+@pytest.mark.timeout(1200)
+def test_hires_global_first_step(oracle):
+    w = W["hires"]
+    tol = tg.TOL[w.dtype]
+    print(f"[full] hires step 0, global merge: N={w.N} D={w.D} (A is {w.B * w.D * w.N * 2 / 1e6:.0f} MB)", flush=True)
+    inp = synth.make_inputs(synth.scaled(w, steps=1))
+    X = _f64(inp["X"])
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    d = tg.oracle_desc(oracle, w, 1)
+    ref = oracle.layer(d, X, *Wts, heads=w.heads)
+    print(f"  oracle done; destinations with Z < 1e-20: {ref['clamps']}", flush=True)
+    Z_ref, Y_ref, idx_ref = ref["Z"], ref["Y"], ref["idx"]
+    del ref
+    dv = tg.Device(w, inp, 1)
+    Y, _ = dv.layer(0)
+    assert np.array_equal(dv.idx.cpu().numpy(), idx_ref)
+    _report("Z", tg.host(dv.Z), Z_ref, tol)
+    _report("Y", Y, Y_ref, tol)
+
+
+@pytest.mark.timeout(1200)
+def test_hires_reuse_sequence_tile(oracle):
+    """Ten drifting steps, destinations re-selected every 5 steps, weights recomputed every 2
+    (Sec. 4.3.2); region-local merge.  The oracle follows the same schedule; attention and unmerge
+    are checked on the destinations / tokens of four sampled regions per sample."""
+    w = W["hires"]
+    R, tol = w.P, tg.TOL[w.dtype]
+    inp = synth.make_inputs(w)
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    d = tg.oracle_desc(oracle, w, R)
+    dv = tg.Device(w, inp, R)
+    _, _, token_of = oracle.region_map(w.H, w.W, w.tile_h, w.tile_w)
+    rng = np.random.default_rng(4)
+    regions = [sorted(rng.choice(w.P, 4, replace=False).tolist()) for _ in range(w.B)]
+    rows = np.array([b * w.D + p * w.d_loc + k for b in range(w.B) for p in regions[b] for k in range(w.d_loc)],
+                    np.int32)
+    idx = A = Z = None
+    check_at = {0, 1, 2, 5, 6, 9}
+    for t, (sel, rew) in enumerate(synth.reuse_schedule(w)):
+        flags = 0 if sel else (tb.TOMA_REUSE_IDX if rew else tb.TOMA_REUSE_A)
+        Xt = inp["X_steps"][t]
+        Y, _ = dv.layer(flags, X=Xt)
+        print(f"[hires] step {t}: reselect={sel} reweight={rew}", flush=True)
+        X = _f64(Xt)
+        if sel:
+            idx, _, _ = oracle.select(d, X)
+            assert np.array_equal(dv.idx.cpu().numpy(), idx)
+        if rew:
+            A, Z, _ = oracle.merge_weights(d, X, idx)
+        if t not in check_at:
+            continue
+        Xm = oracle.merge(d, X, A, Z)
+        O_rows = oracle.attend_rows(Xm, None, *Wts, heads=w.heads, rows=rows)
+        O = np.zeros((w.B, w.D, w.C))
+        O.reshape(-1, w.C)[rows] = O_rows
+        Y_ref = oracle.unmerge(d, A, Z, O)
+        for b in range(w.B):
+            toks = np.concatenate([token_of[p] for p in regions[b]])
+            _report(f"Y step {t} sample {b}", Y[b, toks], Y_ref[b, toks], tol)

@@ -38,6 +38,18 @@ def test_extra_tokens_join_after_the_merged_ones(oracle):
     assert np.allclose(O, _mha_torch(np.concatenate([Xm, Xe], axis=1), *W, heads), atol=1e-12)
 
 
+def test_sampled_rows_equal_the_full_attention(oracle):
+    rng = np.random.default_rng(37)
+    B, D, T, C, heads = 2, 21, 4, 16, 4
+    Xm, Xe = rng.standard_normal((B, D, C)), rng.standard_normal((B, T, C))
+    W = _weights(rng, C)
+    full = oracle.attend(Xm, Xe, *W, heads=heads).reshape(B * (D + T), C)
+    rows = np.array([0, 7, 24, 25, 49, 30], np.int32)
+    part = oracle.attend_rows(Xm, Xe, *W, heads=heads, rows=rows)
+    assert np.allclose(part, full[rows], atol=1e-13)
+    assert np.allclose(part, _mha_torch(np.concatenate([Xm, Xe], axis=1), *W, heads).reshape(-1, C)[rows], atol=1e-12)
+
+
 def test_output_projection_and_constant_values(oracle):
     rng = np.random.default_rng(32)
     B, D, C, heads = 1, 9, 8, 2
