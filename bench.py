@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--merge-regions", default="global", choices=["global", "tile"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", default=None, help="also write a per-kernel table (text) to this path")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: three uncached layer calls and one "
+                         "256 MiB device copy (the calibration kernel), nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -100,26 +103,63 @@ def main():
     Y = torch.empty((w.B, w.N, w.C), dtype=tdt, device="cuda")
     Ye = torch.empty((w.B, w.T_extra, w.C), dtype=tdt, device="cuda") if w.T_extra else None
 
-    def call(flags):
-        tb.toma_layer(desc, attn, flags, X, Xe, idx, A, Z, Wq, Wk, Wv, None, Y, Ye, ws)
+    # a denoising-like sequence keeps every step's tokens resident and follows the reuse schedule
+    # (destinations re-selected / weights recomputed every few steps, cached otherwise)
+    seq = w.steps > 1
+    if seq:
+        X_steps = [dev(x) for x in inp["X_steps"]]
+        plan = [0 if sel else (tb.TOMA_REUSE_IDX if rew else tb.TOMA_REUSE_A)
+                for sel, rew in synth.reuse_schedule(w)]
+
+    def call(flags, x=None):
+        tb.toma_layer(desc, attn, flags, X if x is None else x, Xe, idx, A, Z, Wq, Wk, Wv, None, Y, Ye, ws)
 
     def timed(flags, steps):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            call(flags)
+        for i in range(steps):
+            if seq and flags is None:
+                call(plan[i % w.steps], X_steps[i % w.steps])
+            else:
+                call(flags)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps     # ms per step
 
-    for _ in range(args.warmup):
+    if args.traffic_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            call(0)
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": w.name, "merge_regions": R, "layer_calls": 3, "copy_bytes": 256 << 20}))
+        return
+
+    main_flags = None if seq else 0
+    for _ in range(max(args.warmup, 1)):
         call(0)
-    ms = timed(0, args.steps)
+    ms = timed(main_flags, args.steps)
     ms_idx = timed(tb.TOMA_REUSE_IDX, args.steps)
     ms_a = timed(tb.TOMA_REUSE_A, args.steps)
+    per_position = None
+    if seq:
+        ms_full = timed(0, max(args.steps // 4, w.steps))
+        # per schedule position, HIP events on the launch stream (torch's current stream)
+        reps = max(args.steps // w.steps, 3)
+        acc = [0.0] * w.steps
+        for _ in range(reps):
+            for t in range(w.steps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                call(plan[t], X_steps[t])
+                e1.record()
+                e1.synchronize()
+                acc[t] += e0.elapsed_time(e1) * 1e3
+        per_position = [a / reps for a in acc]
 
     # per-kernel durations: the same K steps with every launch bracketed by HIP events
     tb.toma_profile_enable(True)
-    timed(0, args.steps)
+    timed(main_flags, args.steps)
     per_kernel = {}
     for name in tb.toma_profile_kernel_names():
         n, total = tb.toma_profile_read(name)
@@ -133,6 +173,17 @@ def main():
     dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
     roofline = roofline_entry(dominant, work, per_kernel[dominant]["avg_us"])
     roofline["avg_us"] = per_kernel[dominant]["avg_us"]
+    # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/), when recorded
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+            rec = json.load(fh)[w.name][args.merge_regions]
+        for name, t in rec.items():
+            if name in per_kernel:
+                per_kernel[name]["traffic"] = t["read_bytes"] + t["written_bytes"]
+        if dominant in rec:
+            roofline["traffic"] = rec[dominant]["read_bytes"] + rec[dominant]["written_bytes"]
+    except (OSError, KeyError, ValueError):
+        pass
     mfma_k = [k for k in per_kernel if per_kernel[k]["bound"] == "mfma" and k != "gram"]
     mfma_flops = sum(work[k][1] * per_kernel[k]["launches_per_step"] for k in mfma_k)
     mfma_us = sum(per_kernel[k]["us_per_step"] for k in mfma_k)
@@ -145,9 +196,13 @@ def main():
                                f"{w.tile_h}x{w.tile_w} regions (P={w.P}), keep {w.keep:g} (D={w.D}), tau={w.tau}, "
                                f"{w.heads} heads x {w.head_dim}, extra tokens {w.T_extra}, "
                                f"merge_regions={R} ({args.merge_regions})",
-                   "call": "toma_layer, nothing cached (select + weights + merge + attention + unmerge)"},
+                   "call": ("toma_layer along the reuse schedule (amortised over the sequence)" if seq else
+                            "toma_layer, nothing cached (select + weights + merge + attention + unmerge)")},
         "roofline": roofline,
         "us_idx_cached": ms_idx * 1e3, "us_idx_and_weights_cached": ms_a * 1e3,
+        "sequence": None if not seq else {
+            "schedule": ["select+weights" if f == 0 else ("weights" if f == tb.TOMA_REUSE_IDX else "cached") for f in plan],
+            "us_per_position": per_position, "us_amortised": ms * 1e3, "us_nothing_cached": ms_full * 1e3},
         "mfma_stages": {"tflops": mfma_flops / (mfma_us * 1e-6) / 1e12 if mfma_us else None,
                         "frac_of_peak": (mfma_flops / (mfma_us * 1e-6) / 1e12) / PEAK["bf16" if w.dtype == "bf16" else "f32"]
                         if mfma_us else None, "us_per_step": mfma_us},
@@ -157,24 +212,34 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import toma_oracle as orc
         f64 = lambda a: None if a is None else np.asarray(a, dtype=np.float64)
-        od = orc.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, R, w.tau)
+        # bounded sample: the whole call when it is a few seconds of CPU work, else one sample of the
+        # batch in region-local mode (stated in the record)
+        heavy = w.N > 8192
+        ob = 1 if heavy else w.B
+        oR = w.P if heavy else R
+        od = orc.make_desc(ob, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, oR, w.tau)
+        ox = f64(inp["X"][:ob])
+        oxe = None if inp["X_extra"] is None else f64(inp["X_extra"][:ob])
         t0 = time.perf_counter()
-        ref = orc.layer(od, f64(inp["X"]), f64(inp["Wq"]), f64(inp["Wk"]), f64(inp["Wv"]), heads=w.heads,
-                        Xe=f64(inp["X_extra"]))
+        ref = orc.layer(od, ox, f64(inp["Wq"]), f64(inp["Wk"]), f64(inp["Wv"]), heads=w.heads, Xe=oxe)
         cpu_s = time.perf_counter() - t0
+        sample = ("1 full layer call of the same workload (all samples, all regions)" if not heavy else
+                  f"1 full layer call on sample 0 only (B=1 of {w.B}), region-local merge, step 0")
         out["cpu_baseline"] = {"value": cpu_s * 1e6, "unit": "us", "cores": orc.threads(), "kind": "oracle",
-                               "sample": "1 full layer call of the same workload (all samples, all regions)"}
-        call(0)
-        torch.cuda.synchronize()
-        idx_gpu = idx.cpu().numpy()
-        rel_gap = ref["gap"] / np.maximum(ref["gain"], 1e-30)
-        y = Y.to(torch.float64).cpu().numpy()
-        out["parity"] = {
-            "regions_with_different_picks": int((~np.all(idx_gpu == ref["idx"], axis=2)).sum()),
-            "near_tie_steps": int((rel_gap[..., :-1] < 1e-6).sum()), "exact_tie_steps": int((ref["gap"][..., :-1] == 0).sum()),
-            "clamped_destinations": int(ref["clamps"]),
-            "max_rel_err_Y": float(np.abs(y - ref["Y"]).max() / np.abs(ref["Y"]).max()),
-        }
+                               "sample": sample}
+        if not heavy:
+            call(0)
+            torch.cuda.synchronize()
+            idx_gpu = idx.cpu().numpy()
+            rel_gap = ref["gap"] / np.maximum(ref["gain"], 1e-30)
+            y = Y.to(torch.float64).cpu().numpy()
+            out["parity"] = {
+                "regions_with_different_picks": int((~np.all(idx_gpu == ref["idx"], axis=2)).sum()),
+                "near_tie_steps": int((rel_gap[..., :-1] < 1e-6).sum()),
+                "exact_tie_steps": int((ref["gap"][..., :-1] == 0).sum()),
+                "clamped_destinations": int(ref["clamps"]),
+                "max_rel_err_Y": float(np.abs(y - ref["Y"]).max() / np.abs(ref["Y"]).max()),
+            }
     out["context"] = {"paper": "merge 38.8 us / unmerge 40.5 us at N=1024 on RTX6000 (Table 6); SDXL/Flux "
                                "end-to-end latency -24% / -23% (abstract); other hardware, context only"}
     if args.report:
