@@ -47,6 +47,8 @@ def kernel_work(w, R, esize):
         "scale_rows": ("hbm", 2 * w.B * w.D * w.C * esize),
         "unmerge": (mm, f["unmerge"]),
         "copy_extra": ("hbm", 2 * w.B * w.T_extra * w.C * esize),
+        # second pass of a K-split merge / unmerge product: at least two fp32 partials in, one tile out
+        "split_finish": ("hbm", w.B * w.D * w.C * (2 * 4 + esize)),
         "_a_bytes": ("hbm", a_bytes),
     }
 
@@ -187,6 +189,7 @@ def main():
     mfma_k = [k for k in per_kernel if per_kernel[k]["bound"] == "mfma" and k != "gram"]
     mfma_flops = sum(work[k][1] * per_kernel[k]["launches_per_step"] for k in mfma_k)
     mfma_us = sum(per_kernel[k]["us_per_step"] for k in mfma_k)
+    mfma_us += per_kernel.get("split_finish", {"us_per_step": 0.0})["us_per_step"]   # part of the split products
 
     out = {
         "metric": METRIC, "value": ms * 1e3, "unit": "us", "n_gpus": 1, "steps": args.steps,

@@ -1,6 +1,8 @@
 // C-ABI entry points of libtoma: argument checks on the host, workspace layout, stage launches.
 #include <math.h>
 
+#include <algorithm>
+
 #include "toma_internal.h"
 
 namespace toma {
@@ -45,10 +47,16 @@ void plan_workspace(const Shape &s, Workspace *w) {
   size_t es = s.dtype == TOMA_BF16 ? 2 : 4;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
-  // row strides of the partial-result arrays: enough for the smallest GEMM tile (two wave slices of
-  // 32 per 64-wide tile)
-  w->stat_parts = 2 * ((s.Dr + kGemmMinTile - 1) / kGemmMinTile);
-  w->z_parts = 2 * ((s.Nr + kGemmMinTile - 1) / kGemmMinTile);
+  // row strides of the partial-result arrays: one entry per wave slice of the weights product
+  // (sources x destinations x C), whose block tile is planned here exactly as at launch
+  if (gemm_async_fits(s.Nr, s.Dr, s.C, (int)es)) {
+    const GemmPlan pw = plan_gemm_async(s.Nr, s.Dr, s.C, s.B * s.R, (int)es, false);
+    w->stat_parts = 2 * ((s.Dr + pw.bn - 1) / pw.bn);
+    w->z_parts = 4 * ((s.Nr + pw.bm - 1) / pw.bm);
+  } else {
+    w->stat_parts = 2 * ((s.Dr + 63) / 64);
+    w->z_parts = 2 * ((s.Nr + 63) / 64);
+  }
   w->sim = take((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(float));
   w->stats = take((size_t)s.B * s.N * w->stat_parts * 2 * sizeof(float));
   w->lse = take((size_t)s.B * s.N * sizeof(float));
@@ -58,6 +66,17 @@ void plan_workspace(const Shape &s, Workspace *w) {
   w->q = take(qkv); w->k = take(qkv); w->v = take(qkv); w->oh = take(qkv);
   w->xm = take((size_t)s.B * s.D * s.C * es);  // merged tokens and attention output of toma_layer
   w->o = take(qkv);
+  // fp32 partial tiles of the merge / unmerge products when their K is split between workgroups
+  size_t part = 0;
+  if (gemm_async_fits(s.Dr, s.C, s.Nr, (int)es)) {
+    const GemmPlan pm = plan_gemm_async(s.Dr, s.C, s.Nr, s.B * s.R, (int)es, true);
+    if (pm.nsplit > 1) part = (size_t)pm.nsplit * s.B * s.D * s.C * sizeof(float);
+  }
+  if (gemm_async_fits(s.Nr, s.C, s.Dr, (int)es)) {
+    const GemmPlan pu = plan_gemm_async(s.Nr, s.C, s.Dr, s.B * s.R, (int)es, true);
+    if (pu.nsplit > 1) part = std::max(part, (size_t)pu.nsplit * s.B * s.N * s.C * sizeof(float));
+  }
+  w->split = take(part);
   w->total = off;
 }
 
@@ -122,7 +141,7 @@ TOMA_API int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx
   hipStream_t st = static_cast<hipStream_t>(stream);
   rc = launch_weights(s, X, idx, A, Z, static_cast<char *>(ws), w, st);
   if (rc != TOMA_OK) return rc;
-  return launch_merge(s, X, A, Z, Xm, st);
+  return launch_merge(s, X, A, Z, Xm, static_cast<char *>(ws), w, st);
 }
 
 TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void *A, const float *Z, void *Xm,
@@ -132,7 +151,7 @@ TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void 
   if (rc != TOMA_OK) return rc;
   if (!X || !A || !Z || !Xm) return TOMA_ERR_NULL;
   if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Xm, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
-  return launch_merge(s, X, A, Z, Xm, static_cast<hipStream_t>(stream));
+  return launch_merge(s, X, A, Z, Xm, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
 }
 
 TOMA_API int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *Xm,
@@ -194,7 +213,7 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
     rc = launch_weights(s, X, idx, A, Z, wsb, w, st);
     if (rc != TOMA_OK) return rc;
   }
-  rc = launch_merge(s, X, A, Z, Xm, st);
+  rc = launch_merge(s, X, A, Z, Xm, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   // inside the layer the attention writes its merged rows already divided by Z (the unmerge's
   // input), so no separate scaling pass runs; the extra-token rows stay as they are

@@ -21,6 +21,9 @@
 //   const T* b_ptr(ctx, int n, int k)     there runs along k (k-contiguous) or along m / n (k-major)
 //   bool a_linear(int step), b_linear(int step)   address is affine in k over multiples of `step`
 //   void epilogue<TM, TN>(ctx, acc, m_w, n_w, lane)  consume the wave's accumulators
+//   static constexpr bool SPLIT_K         K may be split between workgroups; then also
+//   float* split_buffer()                 fp32 partial tiles [split][batch][M][N], and
+//   void finish(ctx, m, n, f32x4 v)       output step for four consecutive columns of a summed row
 // The policy itself is never written to, so it stays in the kernel-argument segment.
 // Extents along a packet's direction must be multiples of the packet length (8 bf16 / 4 fp32).
 #pragma once
@@ -29,7 +32,7 @@
 
 namespace toma {
 
-struct GemmCtx { int M, N, K, b, rho, z; };
+struct GemmCtx { int M, N, K, b, rho, z, split; };
 
 template <typename T, int BM, int BN> struct GemmTile {
   static constexpr int ES = (int)sizeof(T);
@@ -45,6 +48,26 @@ template <typename T, int BM, int BN> struct GemmTile {
 };
 
 template <int TM, int TN> struct WaveAccT { f32x4 t[TM][TN]; };
+
+// K split between workgroups: the raw fp32 accumulators go to part[split][z][M][N].
+template <int TM, int TN>
+__device__ __forceinline__ void store_partial(float *part, const GemmCtx &x, const WaveAccT<TM, TN> &acc, int nbatch,
+                                              int m_w, int n_w, int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  float *base = part + ((size_t)x.split * nbatch + x.z) * x.M * x.N;
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      const int m = m_w + 16 * i + 4 * g + r;
+      if (m >= x.M) continue;
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const int n = n_w + 16 * j + c;
+        if (n < x.N) base[(size_t)m * x.N + n] = acc.t[i][j][r];
+      }
+    }
+}
 
 // Linear workgroup id -> tile id such that the ids an XCD receives (id mod 8) form a contiguous
 // run of tiles.
@@ -244,10 +267,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | (((N >> 4) & 3) << 14));
 }
 
-template <typename T, typename Pol, int BM, int BN, int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_async(const Pol pol, int tiles_m, int tiles_n) {
+// Workgroup: 8 waves as 4 x 2, two waves per SIMD (a single wave cannot keep a matrix core busy:
+// operand fetch and execution of successive MFMAs only overlap across waves).  With bf16 a K step
+// has two 32-wide sub-steps and the fragment reads run one sub-step ahead of the products, so the
+// LDS latency hides behind the matrix cores; the single barrier of a step sits between its two
+// halves, after this wave's last read of the current stage and before its first read of the next.
+// nsplit > 1 splits K between workgroups; their fp32 partial tiles are combined by k_split_finish.
+template <typename T, typename Pol, int BM, int BN, int STAGES>
+__global__ __launch_bounds__(512) void k_gemm_async(const Pol pol, int tiles_m, int tiles_n, int nbatch, int nsplit) {
   typedef GemmTile<T, BM, BN> G;
-  constexpr int NWAVES = WGM * WGN;
+  constexpr int WGM = 4, WGN = 2, NWAVES = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;               // wave tile
   constexpr int TM = WTM / 16, TN = WTN / 16;                 // 16 x 16 MFMA tiles per wave
   constexpr int A_ELEMS = BM * G::BK, B_ELEMS = BN * G::BK;   // dense: 128 bytes per row / k-row
@@ -258,13 +287,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_async(const Pol pol, in
 
   int tile = xcd_remap(blockIdx.x, gridDim.x);
   const int per_batch = tiles_m * tiles_n;
-  const int z = tile / per_batch;
-  tile -= z * per_batch;
+  const int zs = tile / per_batch;
+  tile -= zs * per_batch;
+  const int z = zs / nsplit, split = zs - z * nsplit;
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
-  const GemmCtx ctx = pol.setup(z);
+  GemmCtx ctx = pol.setup(z);
+  ctx.split = split;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w / WGN, wn = w % WGN;
   const int g = lane >> 4, c = lane & 15;
-  const int K = ctx.K, nk = K / G::BK;
+  // this workgroup's share of the K steps
+  const int nk_all = ctx.K / G::BK;
+  const int kt0 = (int)((long long)nk_all * split / nsplit), kt1 = (int)((long long)nk_all * (split + 1) / nsplit);
+  const int nk = kt1 - kt0, kbase = kt0 * G::BK;
 
   // what this lane fetches for chunk `ch` (1 KiB = 64 packets) of a tile: tile coordinates
   int a_i[NIA], a_k[NIA], b_i[NIB], b_k[NIB];
@@ -298,31 +332,57 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_async(const Pol pol, in
 
   // Operand addresses advance by a fixed amount per K step when the operand is linear in k (all
   // operands except a k-major walk over a region whose width does not divide the step): keep the
-  // step-0 address and the per-step delta instead of recomputing maps and gathers every step.
+  // first step's address and the per-step delta instead of recomputing maps and gathers every step.
   const bool lin_a = pol.a_linear(G::BK), lin_b = pol.b_linear(G::BK);
   const T *pa[NIA], *pb[NIB];
-  int da[NIA], db[NIB];
 #pragma unroll
-  for (int t = 0; t < NIA; t++) {
-    pa[t] = pol.a_ptr(ctx, m0 + a_i[t], a_k[t]);
-    da[t] = lin_a ? (int)(pol.a_ptr(ctx, m0 + a_i[t], a_k[t] + G::BK) - pa[t]) : 0;
-  }
+  for (int t = 0; t < NIA; t++) pa[t] = pol.a_ptr(ctx, m0 + a_i[t], kbase + a_k[t]);
 #pragma unroll
-  for (int t = 0; t < NIB; t++) {
-    pb[t] = pol.b_ptr(ctx, n0 + b_i[t], b_k[t]);
-    db[t] = lin_b ? (int)(pol.b_ptr(ctx, n0 + b_i[t], b_k[t] + G::BK) - pb[t]) : 0;
-  }
+  for (int t = 0; t < NIB; t++) pb[t] = pol.b_ptr(ctx, n0 + b_i[t], kbase + b_k[t]);
+  // the per-step delta of a linear operand is the same for every packet: keep it in a scalar register
+  const int da = lin_a ? __builtin_amdgcn_readfirstlane((int)(pol.a_ptr(ctx, m0 + a_i[0], kbase + a_k[0] + G::BK) - pa[0])) : 0;
+  const int db = lin_b ? __builtin_amdgcn_readfirstlane((int)(pol.b_ptr(ctx, n0 + b_i[0], kbase + b_k[0] + G::BK) - pb[0])) : 0;
   auto issue = [&](int kt) {
-    const int st = kt % STAGES, k0 = kt * G::BK;
+    const int st = kt % STAGES, k0 = kbase + kt * G::BK;
 #pragma unroll
     for (int t = 0; t < NIA; t++) {
-      const T *src = lin_a ? pa[t] + (ptrdiff_t)kt * da[t] : pol.a_ptr(ctx, m0 + a_i[t], k0 + a_k[t]);
+      const T *src = lin_a ? pa[t] + (ptrdiff_t)kt * da : pol.a_ptr(ctx, m0 + a_i[t], k0 + a_k[t]);
       load_to_lds16(src, As[st] + (w * NIA + t) * (1024 / G::ES));
     }
 #pragma unroll
     for (int t = 0; t < NIB; t++) {
-      const T *src = lin_b ? pb[t] + (ptrdiff_t)kt * db[t] : pol.b_ptr(ctx, n0 + b_i[t], k0 + b_k[t]);
+      const T *src = lin_b ? pb[t] + (ptrdiff_t)kt * db : pol.b_ptr(ctx, n0 + b_i[t], k0 + b_k[t]);
       load_to_lds16(src, Bs[st] + (w * NIB + t) * (1024 / G::ES));
+    }
+  };
+  // this wave's loads of step kt are the oldest outstanding ones: wait until at most the younger
+  // steps' loads remain
+  auto wait_stage = [&](int kt) {
+    const int younger = min(nk - 1 - kt, STAGES - 2);
+    if (STAGES >= 4 && younger >= 2) wait_vmcnt<2 * (NIA + NIB)>();
+    else if (STAGES >= 3 && younger >= 1) wait_vmcnt<NIA + NIB>();
+    else wait_vmcnt<0>();
+  };
+  // workgroup barrier that the compiler may not move memory accesses across
+  auto meet = [&]() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  auto frags = [&](Frag<T> (&fa)[TM], Frag<T> (&fb)[TN], int kt, int kk) {
+    const T *at = As[kt % STAGES], *bt = Bs[kt % STAGES];
+    const int kf = 32 * kk + 8 * g;
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      const int row = wm * WTM + 16 * i;
+      if (Pol::A_KS) frag_load_ks_sw<PPR_A>(fa[i], at, kf, kf + 4, row, lane);
+      else frag_load_kc_sw(fa[i], at, row + c, kf);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int col = wn * WTN + 16 * j;
+      if (Pol::B_KS) frag_load_ks_sw<PPR_B>(fb[j], bt, kf, kf + 4, col, lane);
+      else frag_load_kc_sw(fb[j], bt, col + c, kf);
     }
   };
 
@@ -331,45 +391,55 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_async(const Pol pol, in
   for (int i = 0; i < TM; i++)
 #pragma unroll
     for (int j = 0; j < TN; j++) acc.t[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  auto products = [&](const Frag<T> (&fa)[TM], const Frag<T> (&fb)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) mma16(acc.t[i][j], fa[i], fb[j]);
+  };
 
 #pragma unroll
   for (int s = 0; s < STAGES - 1; s++)
     if (s < nk) issue(s);
 
-  for (int kt = 0; kt < nk; kt++) {
-    // this wave's loads of step kt are the oldest outstanding ones: wait until at most the
-    // younger steps' loads remain, then meet the other waves
-    const int younger = min(nk - 1 - kt, STAGES - 2);
-    if (younger >= 2) wait_vmcnt<2 * (NIA + NIB)>();
-    else if (younger == 1) wait_vmcnt<NIA + NIB>();
-    else wait_vmcnt<0>();
-    // every wave's part of tile kt has landed, and every wave is done reading tile kt - 1
-    __builtin_amdgcn_s_barrier();
-    if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
-    const T *at = As[kt % STAGES], *bt = Bs[kt % STAGES];
+  if (G::KSUB == 2) {
+    Frag<T> fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    wait_stage(0);
+    meet();
+    frags(fa0, fb0, 0, 0);
+    for (int kt = 0; kt < nk; kt++) {
+      // every wave is past the barrier of step kt - 1: the stage of step kt - 1 is free
+      if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
+      frags(fa1, fb1, kt, 1);
+      products(fa0, fb0);
+      if (kt + 1 < nk) wait_stage(kt + 1);
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's reads of stage kt have returned
+      meet();
+      if (kt + 1 < nk) frags(fa0, fb0, kt + 1, 0);
+      products(fa1, fb1);
+    }
+  } else {
+    for (int kt = 0; kt < nk; kt++) {
+      wait_stage(kt);
+      // every wave's part of tile kt has landed, and every wave is done reading tile kt - 1
+      meet();
+      if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
 #pragma unroll
-    for (int kk = 0; kk < G::KSUB; kk++) {
-      Frag<T> fa[TM], fb[TN];
-      const int kf = 32 * kk + 8 * g;
-#pragma unroll
-      for (int i = 0; i < TM; i++) {
-        const int row = wm * WTM + 16 * i;
-        if (Pol::A_KS) frag_load_ks_sw<PPR_A>(fa[i], at, kf, kf + 4, row, lane);
-        else frag_load_kc_sw(fa[i], at, row + c, kf);
+      for (int kk = 0; kk < G::KSUB; kk++) {
+        Frag<T> fa[TM], fb[TN];
+        frags(fa, fb, kt, kk);
+        products(fa, fb);
       }
-#pragma unroll
-      for (int j = 0; j < TN; j++) {
-        const int col = wn * WTN + 16 * j;
-        if (Pol::B_KS) frag_load_ks_sw<PPR_B>(fb[j], bt, kf, kf + 4, col, lane);
-        else frag_load_kc_sw(fb[j], bt, col + c, kf);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++) mma16(acc.t[i][j], fa[i], fb[j]);
+      __builtin_amdgcn_s_waitcnt(0xc07f);
     }
   }
 
+  if constexpr (Pol::SPLIT_K) {
+    if (nsplit > 1) {
+      store_partial<TM, TN>(pol.split_buffer(), ctx, acc, nbatch, m0 + wm * WTM, n0 + wn * WTN, lane);
+      return;
+    }
+  }
   pol.template epilogue<TM, TN>(ctx, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
 }
 
@@ -394,28 +464,28 @@ __device__ __forceinline__ void store_rows(const WaveAccT<TM, TN> &acc, int m_w,
     }
 }
 
-struct GemmShape { int bm, bn, wgm, wgn, tiles_m, tiles_n; };
-
-inline GemmShape make_gemm_shape(int M, int N, int bm, int bn, int wgm, int wgn) {
-  return GemmShape{bm, bn, wgm, wgn, (M + bm - 1) / bm, (N + bn - 1) / bn};
+// Sum of the K-split partial tiles in a fixed order, then the policy's own output step.  One thread
+// per four consecutive columns.
+template <typename T, typename Pol>
+__global__ __launch_bounds__(256) void k_split_finish(const Pol pol, int nbatch, int nsplit) {
+  const int z = blockIdx.y;
+  GemmCtx ctx = pol.setup(z);
+  ctx.split = 0;
+  const int n4 = ctx.N >> 2;
+  const size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= (size_t)ctx.M * n4) return;
+  const int m = (int)(q / n4), n = (int)(q % n4) * 4;
+  const float *part = pol.split_buffer();
+  f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < nsplit; s++)
+    v += *reinterpret_cast<const f32x4 *>(part + (((size_t)s * nbatch + z) * ctx.M + m) * ctx.N + n);
+  pol.finish(ctx, m, n, v);
 }
 
-// Tile shape for the load-to-LDS kernel.  The kernel is fed from L2 at a few tens of bytes per
-// clock and CU, so a workgroup's time per K step grows with the tile perimeter (BM + BN) while
-// its work grows with the area: take the shape with the least perimeter * (rounds of workgroups
-// over the 256 CUs; every shape keeps one workgroup per CU resident).
-inline GemmShape choose_async_shape(int M, int N, int batch) {
-  const GemmShape cands[4] = {make_gemm_shape(M, N, 256, 128, 4, 2), make_gemm_shape(M, N, 128, 128, 2, 2),
-                              make_gemm_shape(M, N, 128, 64, 2, 2), make_gemm_shape(M, N, 64, 64, 2, 2)};
-  int best = 0;
-  long long best_cost = -1;
-  for (int i = 0; i < 4; i++) {
-    long long blocks = (long long)cands[i].tiles_m * cands[i].tiles_n * batch;
-    long long rounds = (blocks + 255) / 256;
-    long long cost = rounds * (cands[i].bm + cands[i].bn);
-    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = i; }
-  }
-  return cands[best];
+struct GemmShape { int bm, bn, wgm, wgn, tiles_m, tiles_n, nsplit; };
+
+inline GemmShape make_gemm_shape(int M, int N, int bm, int bn, int wgm, int wgn) {
+  return GemmShape{bm, bn, wgm, wgn, (M + bm - 1) / bm, (N + bn - 1) / bn, 1};
 }
 
 // Tile shape for the register-staged kernel: the largest that still gives about two workgroups per CU.
@@ -430,25 +500,35 @@ inline GemmShape choose_gemm_shape(int M, int N, int batch) {
 
 template <typename T, typename Pol>
 inline GemmShape launch_gemm(int kernel_id, const Pol &pol, int M, int N, int K, int batch, hipStream_t st) {
-  constexpr int BK = 128 / (int)sizeof(T), EPP = 16 / (int)sizeof(T);
-  const bool fits = K % BK == 0 && M >= EPP && N >= EPP;
-  KernelTimer kt(kernel_id, st);
-  if (fits) {
+  if (gemm_async_fits(M, N, K, (int)sizeof(T))) {
     // load-to-LDS pipeline
-    const GemmShape g = choose_async_shape(M, N, batch);
-    const dim3 grid(g.tiles_m * g.tiles_n * batch);
-    if (g.bm == 256)
-      hipLaunchKernelGGL((k_gemm_async<T, Pol, 256, 128, 4, 2, 3>), grid, dim3(512), 0, st, pol, g.tiles_m, g.tiles_n);
-    else if (g.bm == 128 && g.bn == 128)
-      hipLaunchKernelGGL((k_gemm_async<T, Pol, 128, 128, 2, 2, 4>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
-    else if (g.bm == 128)
-      hipLaunchKernelGGL((k_gemm_async<T, Pol, 128, 64, 2, 2, 4>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
-    else
-      hipLaunchKernelGGL((k_gemm_async<T, Pol, 64, 64, 2, 2, 4>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
+    const GemmPlan pl = plan_gemm_async(M, N, K, batch, (int)sizeof(T), Pol::SPLIT_K);
+    const GemmShape g{pl.bm, pl.bn, 4, 2, (M + pl.bm - 1) / pl.bm, (N + pl.bn - 1) / pl.bn, pl.nsplit};
+    const dim3 grid(g.tiles_m * g.tiles_n * batch * g.nsplit);
+    {
+      KernelTimer kt(kernel_id, st);
+      if (g.bm == 256 && g.bn == 256)
+        hipLaunchKernelGGL((k_gemm_async<T, Pol, 256, 256, 2>), grid, dim3(512), 0, st, pol, g.tiles_m, g.tiles_n, batch, g.nsplit);
+      else if (g.bm == 256)
+        hipLaunchKernelGGL((k_gemm_async<T, Pol, 256, 128, 3>), grid, dim3(512), 0, st, pol, g.tiles_m, g.tiles_n, batch, g.nsplit);
+      else if (g.bm == 128 && g.bn == 128)
+        hipLaunchKernelGGL((k_gemm_async<T, Pol, 128, 128, 4>), grid, dim3(512), 0, st, pol, g.tiles_m, g.tiles_n, batch, g.nsplit);
+      else if (g.bm == 128)
+        hipLaunchKernelGGL((k_gemm_async<T, Pol, 128, 64, 4>), grid, dim3(512), 0, st, pol, g.tiles_m, g.tiles_n, batch, g.nsplit);
+      else
+        hipLaunchKernelGGL((k_gemm_async<T, Pol, 64, 64, 4>), grid, dim3(512), 0, st, pol, g.tiles_m, g.tiles_n, batch, g.nsplit);
+    }
+    if constexpr (Pol::SPLIT_K) if (g.nsplit > 1) {
+      KernelTimer kt(K_SPLIT, st);
+      const size_t quads = (size_t)M * (N / 4);
+      hipLaunchKernelGGL((k_split_finish<T, Pol>), dim3((unsigned)((quads + 255) / 256), batch), dim3(256), 0, st, pol,
+                         batch, g.nsplit);
+    }
     return g;
   }
   const GemmShape g = choose_gemm_shape(M, N, batch);
   const dim3 grid(g.tiles_m * g.tiles_n * batch);
+  KernelTimer kt(kernel_id, st);
   if (g.bm == 128 && g.bn == 128)
     hipLaunchKernelGGL((k_gemm<T, Pol, 128, 128>), grid, dim3(256), 0, st, pol, g.tiles_m, g.tiles_n);
   else if (g.bm == 128)

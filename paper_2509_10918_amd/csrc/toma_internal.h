@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "../../include/toma.h"
 
 namespace toma {
@@ -19,11 +21,45 @@ struct Shape {
 
 // Offsets (bytes) of the scratch sections inside the caller's workspace.
 struct Workspace {
-  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, total;
+  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, total;
   int stat_parts, z_parts;
 };
 
-constexpr int kGemmMinTile = 64;  // smallest block tile edge of the MFMA GEMM kernels
+constexpr int kGemmMinSlice = 16;  // narrowest wave slice of a GEMM block tile (rows or columns)
+
+// ---- shape planning of the load-to-LDS GEMM (host side; the workspace layout depends on it) ----
+// The kernel needs K to be a multiple of its K step (128 bytes of elements) and at least one
+// 16-byte packet of rows and columns.
+inline bool gemm_async_fits(int M, int N, int K, int elem_size) {
+  const int bk = 128 / elem_size, epp = 16 / elem_size;
+  return K % bk == 0 && M >= epp && N >= epp;
+}
+struct GemmPlan { int bm, bn, nsplit; };
+// Cost model in shader clocks, from measurements of the kernel on MI355X: a K step of a workgroup
+// costs about step[] (bound by the 50 B/clk a CU moves from L2 into LDS, and by the matrix cores for
+// the largest tile), a workgroup pays a fixed prologue + epilogue, and the grid runs in rounds of
+// one workgroup per CU (two for the 64 x 64 tile).  Splitting K adds a pass over the fp32 partials.
+inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, bool may_split) {
+  static const int bm[5] = {256, 256, 128, 128, 64}, bn[5] = {256, 128, 128, 64, 64};
+  static const int step[5] = {3600, 2200, 1300, 1000, 700}, per_cu[5] = {1, 1, 1, 1, 2};
+  const int nk = K / (128 / elem_size);
+  GemmPlan best{128, 128, 1};
+  double best_cost = -1.0;
+  for (int i = 0; i < 5; i++) {
+    const long long tiles = (long long)((M + bm[i] - 1) / bm[i]) * ((N + bn[i] - 1) / bn[i]) * batch;
+    for (int ns = 1; ns <= (may_split ? 8 : 1); ns++) {
+      if (ns > 1 && nk / ns < 8) break;
+      const long long blocks = tiles * ns, slots = 256ll * per_cu[i];
+      const long long rounds = (blocks + slots - 1) / slots;
+      const double fixed = 3000.0 + bm[i] * bn[i] / 8.0;
+      const long long share = std::min<long long>(per_cu[i], (blocks + 255) / 256);  // workgroups sharing a CU
+      double cost = rounds * (((nk + ns - 1) / ns) * (double)step[i] * share + fixed);
+      if (ns > 1) cost += 6000.0 + 0.02 * ns * (double)M * N * batch / 256.0;
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = GemmPlan{bm[i], bn[i], ns}; }
+    }
+  }
+  return best;
+}
 
 int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s);
 void plan_workspace(const Shape &s, Workspace *w);
@@ -33,7 +69,8 @@ int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, char
                   hipStream_t st);
 int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, char *ws,
                    const Workspace &w, hipStream_t st);
-int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, hipStream_t st);
+int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, char *ws,
+                 const Workspace &w, hipStream_t st);
 // Zs (optional): divide the merged rows of O by max(Z, 1e-20) on the way out (the unmerge input)
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
                   const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
@@ -45,7 +82,7 @@ int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t 
 
 // Kernel identifiers of the profiling aid (toma_profile_*): one per kernel of the path.
 enum KernelId { K_GRAM = 0, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
-                K_SCALE, K_UNMERGE, K_COPY, K_COUNT };
+                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_COUNT };
 
 // Brackets one launch with HIP events on its stream while profiling is enabled; free otherwise.
 struct KernelTimer {

@@ -29,7 +29,7 @@ template <typename T> struct RegionView {
 
 // ---- pass 1 and pass 2 of the weights ----------------------------------------------------------
 template <typename T, bool WRITE> struct WeightsPol {
-  static constexpr bool A_KS = false, B_KS = false;
+  static constexpr bool A_KS = false, B_KS = false, SPLIT_K = false;
   RegionView<T> v;
   const int32_t *idx;
   float scale;
@@ -152,12 +152,27 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
 }
 
 // ---- merge -------------------------------------------------------------------------------------
+// four consecutive output elements as one store
+template <typename T> __device__ __forceinline__ void store4(T *dst, f32x4 v) {
+  alignas(16) T o[4];
+#pragma unroll
+  for (int i = 0; i < 4; i++) o[i] = from_f32<T>(v[i]);
+  if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
+  else *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<u32x4 *>(o);
+}
+
 template <typename T> struct MergePol {
-  static constexpr bool A_KS = false, B_KS = true;
+  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true;
   RegionView<T> v;
   const T *A;
   const float *Z;
   T *Xm;
+  float *part;
+  __device__ __forceinline__ float *split_buffer() const { return part; }
+  __device__ __forceinline__ void finish(const GemmCtx &x, int m, int n, f32x4 acc) const {
+    const size_t row = (size_t)x.b * v.D + x.rho * v.Dr + m;
+    store4<T>(Xm + row * v.C + n, acc * (1.0f / fmaxf(Z[row], 1e-20f)));
+  }
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Dr, v.C, v.Nr, bz / v.R, bz % v.R, bz};
   }
@@ -183,12 +198,17 @@ template <typename T> struct MergePol {
 
 // ---- unmerge -----------------------------------------------------------------------------------
 template <typename T> struct UnmergePol {
-  static constexpr bool A_KS = true, B_KS = true;
+  static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true;
   RegionView<T> v;
   const T *A;
   const T *Os;  // [B][os_rows][C], rows [0, D) already divided by Z
   int os_rows;
   T *Y;
+  float *part;
+  __device__ __forceinline__ float *split_buffer() const { return part; }
+  __device__ __forceinline__ void finish(const GemmCtx &x, int m, int n, f32x4 acc) const {
+    store4<T>(Y + ((size_t)x.b * v.N + v.token(x.rho, m)) * v.C + n, acc);
+  }
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Nr, v.C, v.Dr, bz / v.R, bz % v.R, bz};
   }
@@ -273,16 +293,20 @@ int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, f
 }
 
 template <typename T>
-static int merge_typed(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, hipStream_t st) {
+static int merge_typed(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, char *ws,
+                       const Workspace &w, hipStream_t st) {
   MergePol<T> p{};
   p.v = make_view<T>(s, X);
   p.A = static_cast<const T *>(A); p.Z = Z; p.Xm = static_cast<T *>(Xm);
+  p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_MERGE, p, s.Dr, s.C, s.Nr, s.B * s.R, st);
   return launch_status();
 }
 
-int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? merge_typed<bf16_t>(s, X, A, Z, Xm, st) : merge_typed<float>(s, X, A, Z, Xm, st);
+int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, char *ws,
+                 const Workspace &w, hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? merge_typed<bf16_t>(s, X, A, Z, Xm, ws, w, st)
+                              : merge_typed<float>(s, X, A, Z, Xm, ws, w, st);
 }
 
 template <typename T>
@@ -301,6 +325,7 @@ static int unmerge_typed(const Shape &s, const void *A, const float *Z, const vo
   }
   p.v = make_view<T>(s, nullptr);
   p.A = static_cast<const T *>(A); p.Y = static_cast<T *>(Y);
+  p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_UNMERGE, p, s.Nr, s.C, s.Dr, s.B * s.R, st);
   return launch_status();
 }

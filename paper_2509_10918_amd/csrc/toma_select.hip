@@ -182,10 +182,6 @@ __device__ __forceinline__ uint32_t wave_max32_u32(uint32_t v) {
   return max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16));
 }
 
-#define TOMA_ROWS32(X) \
-  X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18) \
-  X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30) X(31)
-
 template <int NT>
 __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *__restrict__ S,
                                                              int32_t *__restrict__ idx,
@@ -206,7 +202,10 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int32_t *Sr = S + (size_t)bp * NL * NL;
 
-  int32_t s[32][CPL];
+  // sv[u][r]: column lane + 64 u of row 32 w + r.  One 32-wide register vector per u, so that a
+  // wave-uniform row number r indexes the registers directly (relative addressing), no dispatch.
+  typedef int32_t i32x32 __attribute__((ext_vector_type(32)));
+  i32x32 sv[CPL];
   int32_t m[CPL];
   bool col_ok[CPL];
 #pragma unroll
@@ -219,7 +218,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
 #pragma unroll
     for (int u = 0; u < CPL; u++) {
       int row = 32 * w + r;
-      s[r][u] = (row < NL && col_ok[u]) ? Sr[(size_t)row * NL + lane + 64 * u] : 0;
+      sv[u][r] = (row < NL && col_ok[u]) ? Sr[(size_t)row * NL + lane + 64 * u] : 0;
     }
   int32_t msum = 0;  // sum of this lane's m: sum_u max(0, s - m) = sum_u max(s, m) - msum
 
@@ -229,33 +228,23 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
 
   // value of row r of this wave (r is wave-uniform): first step = row sum, later = sum max(0, S - m)
   auto eval = [&](int r, bool first) -> uint32_t {
-    int32_t part = 0;
-    switch (r) {
-#define TOMA_EVAL_CASE(R)                                                                            \
-  case R:                                                                                            \
-    _Pragma("unroll") for (int u = 0; u < CPL; u++) part += first ? s[R][u] : max(s[R][u], m[u]);     \
-    break;
-      TOMA_ROWS32(TOMA_EVAL_CASE)
-#undef TOMA_EVAL_CASE
+    int32_t part = first ? 0 : -msum;
+#pragma unroll
+    for (int u = 0; u < CPL; u++) {
+      const int32_t v = sv[u][r];
+      part += first ? v : max(v, m[u]);
     }
-    if (!first) part -= msum;
     return wave_sum_u32((uint32_t)part);
   };
-  // the same, and the row is also posted to rowbuf[buf][w] (one dispatch for both)
+  // the same, and the row is also posted to rowbuf[buf][w]
   auto eval_post = [&](int buf, int r) -> uint32_t {
-    int32_t part = 0;
-    switch (r) {
-#define TOMA_EVALP_CASE(R)                                                       \
-  case R:                                                                        \
-    _Pragma("unroll") for (int u = 0; u < CPL; u++) {                            \
-      part += max(s[R][u], m[u]);                                                \
-      rowbuf[buf][w][lane + 64 * u] = s[R][u];                                   \
-    }                                                                            \
-    break;
-      TOMA_ROWS32(TOMA_EVALP_CASE)
-#undef TOMA_EVALP_CASE
+    int32_t part = -msum;
+#pragma unroll
+    for (int u = 0; u < CPL; u++) {
+      const int32_t v = sv[u][r];
+      part += max(v, m[u]);
+      rowbuf[buf][w][lane + 64 * u] = v;
     }
-    part -= msum;
     return wave_sum_u32((uint32_t)part);
   };
   // refresh the keys of all live rows of this wave at once (straight-line code, independent chains)
@@ -264,20 +253,14 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
     for (int r = 0; r < 32; r++) {
       int32_t part = first ? 0 : -msum;
 #pragma unroll
-      for (int u = 0; u < CPL; u++) part += first ? s[r][u] : max(s[r][u], m[u]);
+      for (int u = 0; u < CPL; u++) part += first ? sv[u][r] : max(sv[u][r], m[u]);
       uint32_t g = wave_sum_u32((uint32_t)part);
       if (lane == r && (first ? my_live0 : key != 0)) key = g + 1u + (first ? kBias0 : 0u);
     }
   };
   auto post_row = [&](int buf, int r) {
-    switch (r) {
-#define TOMA_POST_CASE(R)                                                                      \
-  case R:                                                                                      \
-    _Pragma("unroll") for (int u = 0; u < CPL; u++) rowbuf[buf][w][lane + 64 * u] = s[R][u];   \
-    break;
-      TOMA_ROWS32(TOMA_POST_CASE)
-#undef TOMA_POST_CASE
-    }
+#pragma unroll
+    for (int u = 0; u < CPL; u++) rowbuf[buf][w][lane + 64 * u] = sv[u][r];
   };
   auto read_slot = [&](const unsigned long long *ptr) -> unsigned long long {
     unsigned long long v = *ptr;
