@@ -182,6 +182,9 @@ __device__ __forceinline__ uint32_t wave_max32_u32(uint32_t v) {
   return max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16));
 }
 
+#ifndef TOMA_GREEDY_TOPK
+#define TOMA_GREEDY_TOPK 2
+#endif
 template <int NT>
 __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *__restrict__ S,
                                                              int32_t *__restrict__ idx,
@@ -192,11 +195,12 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
   constexpr int CPL = (NT + 3) / 4;    // columns per lane
   constexpr int32_t kPad = 1 << 23;    // m of a padding column: above every S, so it never contributes
   constexpr uint32_t kBias0 = 1u << 30;  // first step: row sums are signed, |sum| <= 2^30
-  constexpr int kBulk = 6;             // refresh all rows at once when at least this many are due
+  constexpr int kBulk = 12;            // refresh all rows at once when at least this many are due
+  constexpr int kTopK = TOMA_GREEDY_TOPK;  // keys per wave that phase 1 refreshes
   __shared__ int32_t rowbuf[2][NW][64 * CPL];   // [round parity]: each wave's candidate row
   // packed best candidates, rotated over three rounds so that a slot is cleared two rounds
   // before it is written again: [round % 3][0 fresh, 1 best stale runner-up, 2 after phase 2]
-  __shared__ unsigned long long slot[3][4];
+  __shared__ __align__(16) unsigned long long slot[3][4];
 
   const int bp = blockIdx.x, p = bp % P;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -262,11 +266,26 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
 #pragma unroll
     for (int u = 0; u < CPL; u++) rowbuf[buf][w][lane + 64 * u] = sv[u][r];
   };
+  // slots 0 and 1 of a round in one 16-byte LDS read
+  auto read_slots = [&](const unsigned long long *ptr, unsigned long long &a, unsigned long long &b) {
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(ptr);
+    const uint32_t a0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[0]);
+    const uint32_t a1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[1]);
+    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[2]);
+    const uint32_t b1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[3]);
+    a = ((unsigned long long)a1 << 32) | a0;
+    b = ((unsigned long long)b1 << 32) | b0;
+  };
   auto read_slot = [&](const unsigned long long *ptr) -> unsigned long long {
     unsigned long long v = *ptr;
     uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
     return ((unsigned long long)hi << 32) | lo;
+  };
+  // one LDS atomic from the calling lane (no wave-wide combining code around it)
+  auto lds_max_u64 = [&](unsigned long long *ptr, unsigned long long v) {
+    const uint32_t addr = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)ptr;
+    asm volatile("ds_max_u64 %0, %1" ::"v"(addr), "v"(v) : "memory");
   };
   auto pack = [&](uint32_t k, int r) -> unsigned long long {
     return ((unsigned long long)k << 8) | (unsigned)(255 - (32 * w + r));
@@ -299,31 +318,68 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
       fresh = true;
     }
     {
-      uint32_t top = wave_max32_u32(key);
+      const uint32_t top = wave_max32_u32(key);
       if (top != 0) {
-        int r = __builtin_ctzll(__ballot(key == top && lane < 32));
-        uint32_t g = top;
-        if (!first) {
-          g = eval_post(buf, r) + 1u;
-          const bool mine = lane == r;
+        const int r1 = __builtin_ctzll(__ballot(key == top && lane < 32));
+        if (first) {
+          post_row(buf, r1);
+          if (lane == 0) lds_max_u64(&sl[0], pack(top, r1));
+        } else if (kTopK > 1) {
+          // the kTopK largest keys are refreshed together (independent chains); the best of the
+          // remaining keys stays a stale bound
+          uint32_t kk = key, tk[kTopK];
+          int rk[kTopK];
+          tk[0] = top; rk[0] = r1;
+#pragma unroll
+          for (int i = 1; i < kTopK; i++) {
+            kk = lane == rk[i - 1] ? 0u : kk;
+            tk[i] = tk[i - 1] ? wave_max32_u32(kk) : 0u;
+            rk[i] = tk[i] ? __builtin_ctzll(__ballot(kk == tk[i] && lane < 32)) : rk[0];
+          }
+          kk = lane == rk[kTopK - 1] ? 0u : kk;
+          const uint32_t rest = tk[kTopK - 1] ? wave_max32_u32(kk) : 0u;
+          const unsigned long long rest_lanes = __ballot(kk == rest && lane < 32);
+          uint32_t gk[kTopK];
+#pragma unroll
+          for (int i = 0; i < kTopK; i++) gk[i] = tk[i] ? eval(rk[i], false) + 1u : 0u;
+          uint32_t gc = gk[0];
+          int rc = rk[0];
+          fresh = lane == rk[0];
+          key = lane == rk[0] ? gk[0] : key;
+#pragma unroll
+          for (int i = 1; i < kTopK; i++) {
+            if (tk[i]) {
+              key = lane == rk[i] ? gk[i] : key;
+              fresh = fresh || lane == rk[i];
+              if (gk[i] > gc || (gk[i] == gc && rk[i] < rc)) { gc = gk[i]; rc = rk[i]; }
+            }
+          }
+          post_row(buf, rc);
+          if (lane == 0) {
+            lds_max_u64(&sl[0], pack(gc, rc));
+            if (rest != 0) lds_max_u64(&sl[1], pack(rest, __builtin_ctzll(rest_lanes)));
+          }
+        } else {
+          // the best of the other keys stays a stale bound (independent of the refresh below)
+          const uint32_t k2 = lane == r1 ? 0u : key;
+          const uint32_t rest = wave_max32_u32(k2);
+          const unsigned long long rest_lanes = __ballot(k2 == rest && lane < 32);
+          const uint32_t g = eval_post(buf, r1) + 1u;
+          const bool mine = lane == r1;
           key = mine ? g : key;
           fresh = mine;
-        } else {
-          post_row(buf, r);
-        }
-        uint32_t rest = first ? 0u : wave_max32_u32(lane == r ? 0u : key);
-        unsigned long long rest_lanes = __ballot(key == rest && lane < 32 && lane != r);
-        if (lane == 0) {
-          atomicMax(&sl[0], pack(g, r));
-          if (rest != 0) atomicMax(&sl[1], pack(rest, __builtin_ctzll(rest_lanes)));
+          if (lane == 0) {
+            lds_max_u64(&sl[0], pack(g, r1));
+            if (rest != 0) lds_max_u64(&sl[1], pack(rest, __builtin_ctzll(rest_lanes)));
+          }
         }
       }
     }
     lds_barrier();
     if (threadIdx.x < 4) slot[q3 == 0 ? 2 : q3 - 1][threadIdx.x] = 0;  // the slots of round step + 2
-    unsigned long long best = read_slot(&sl[0]);
+    unsigned long long best, stale;
+    read_slots(sl, best, stale);
     if (!first) {
-      const unsigned long long stale = read_slot(&sl[1]);
       if (stale > best) {
         // ---- phase 2: some stale key still beats the best fresh candidate: refresh those rows ----
         uint32_t g0 = (uint32_t)(best >> 8);
@@ -333,18 +389,22 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
         if (__builtin_popcountll(need) >= kBulk) {
           eval_all(false);
         } else {
+          // two rows per turn: their reduction chains are independent and interleave
           while (need) {
-            int r = __builtin_ctzll(need);
+            const int ra = __builtin_ctzll(need);
             need &= need - 1;
-            uint32_t g = eval(r, false) + 1u;
-            key = lane == r ? g : key;
+            const int rb = need ? __builtin_ctzll(need) : ra;
+            need &= need - 1;
+            const uint32_t ga = eval(ra, false) + 1u, gb = eval(rb, false) + 1u;
+            key = lane == ra ? ga : key;
+            key = lane == rb ? gb : key;
           }
         }
         uint32_t top = wave_max32_u32(key);
         if (top != 0) {
           int r = __builtin_ctzll(__ballot(key == top && lane < 32));
           post_row(buf, r);
-          if (lane == 0) atomicMax(&sl[2], pack(top, r));
+          if (lane == 0) lds_max_u64(&sl[2], pack(top, r));
         }
         lds_barrier();
         best = read_slot(&sl[2]);
