@@ -137,309 +137,171 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
 }
 
 // ------------------------------------------------------------------------------------------------
-// Greedy facility location, one workgroup per (sample, region), exact and lazy.
+// Greedy facility location, one workgroup per (sample, region): exact, with incremental gains.
 //
 // Arithmetic.  S is on a grid of 2^-22 (kSimScale): a term max(0, S_ij - m_j) is at most 2^23 and a
 // 256-term sum fits an unsigned 32-bit register, so values, sums and comparisons are plain 32-bit
-// integer instructions and every cross-lane step is a single DPP-modified add or max.
-// Layout.  Wave w owns rows 32w .. 32w+31 of the region's S; lane l holds, of each of those rows,
-// the columns l + 64u.  Evaluating one row's value is a few integer operations per lane plus one
-// 64-lane reduction, and WHICH rows are evaluated is a wave-uniform (scalar) decision.
-// Keys.  Lane r < 32 of wave w keeps key = value + 1 of row 32w + r (0 = chosen or absent).
-// Across waves a candidate travels as (key << 8) | (255 - row): the largest packed word is the
-// largest value and, among equals, the lowest index, so the workgroup's argmax is one LDS
-// atomic max per wave.
-// Laziness.  Values only shrink as m grows (diminishing returns, paper Sec. 3.2), so a key from an
-// earlier round is an upper bound.  In a round every wave re-evaluates its row with the largest
-// stale key and posts that fresh candidate together with the best of its remaining stale keys.
-// If no stale key in the workgroup beats the best fresh candidate B0, B0 is the pick (one barrier
-// per round, the common case).  Otherwise every wave re-evaluates exactly its rows whose stale key
-// still beats B0 and the waves vote again.  Rows that are skipped cannot win, so the pick is the
-// one a full rescan (Alg. 2) makes.
+// integer instructions, independent of any summation order.
+// Incremental gains.  After a pick t only the columns j with S_tj > m_j change their coverage, and
+// the value of row i drops by exactly  sum over those j of  med(S_ij, m_j, m_j') - m_j  (m' the new
+// coverage).  Because the arithmetic is exact, subtracting these differences keeps every row's value
+// equal to the full rescan sum_j max(0, S_ij - m_j) of Alg. 2, at a cost proportional to the number
+// of changed columns (a handful per round once a few destinations exist) instead of N_loc^2.
+// The first pick (largest row sum) is the same rule started from the coverage m = -1 everywhere:
+// sum_j max(0, S_ij + 1) = row sum + N_loc, so the loop has no special first round.
+// Layout.  With NW waves, wave w owns the columns NW c + w (c < 32) of S for ALL rows (neighbouring
+// columns, which tend to change together, belong to different waves); lane l holds the rows
+// RPL l + v, sv[v][c] = S[RPL l + v][NW c + w] (128 registers for a 256-token region).  The
+// coverage of the own columns lives in lanes 0..31.  A changed column costs its owner a few
+// instructions with the column's (m, m') as scalar operands and the column's registers addressed
+// relative to the wave-uniform column number (scalar branches cost far more here than indexing).
+// Exchange, two barriers per round.  The rows' comparison keys (value + 1; 0 = picked or absent)
+// live in LDS.  (1) Every wave reads all keys (RPL per lane) and finds the same argmax t on its own
+// (one DPP reduction and a ballot: lanes are in row order, so the lowest lane among equals holds the
+// lowest index).  By symmetry the owner of column t holds the whole row t, one word per (lane, v):
+// it posts the row to LDS, ordered so that every wave then reads its own columns as one contiguous
+// run.  Barrier.  (2) Each wave subtracts its rows' decreases from the keys with integer LDS
+// atomics (they commute, so the result does not depend on their order).  A picked row's value falls
+// to exactly zero with its own pick's decrease; one more atomic takes away the + 1, which leaves
+// key 0 for good.  Barrier.
 // ------------------------------------------------------------------------------------------------
 template <int CTRL, int ROW_MASK = 0xf> __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
 }
 constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppRor4 = 0x124, kDppRor8 = 0x128;
-constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;
 
-// sum over the 64 lanes (mod 2^32); the result is uniform
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
-  v += dpp_u32<kDppXor1>(v);
-  v += dpp_u32<kDppXor2>(v);
-  v += dpp_u32<kDppRor4>(v);
-  v += dpp_u32<kDppRor8>(v);               // every lane: total of its row of 16
-  v += dpp_u32<kDppBcast15, 0xa>(v);       // rows 1, 3 += rows 0, 2
-  v += dpp_u32<kDppBcast31, 0xc>(v);       // rows 2, 3 += rows 0 + 1
-  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-}
-// max over lanes 0..31; the result is uniform
-__device__ __forceinline__ uint32_t wave_max32_u32(uint32_t v) {
+// max over the 64 lanes; the result is uniform
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   v = max(v, dpp_u32<kDppXor1>(v));
   v = max(v, dpp_u32<kDppXor2>(v));
   v = max(v, dpp_u32<kDppRor4>(v));
-  v = max(v, dpp_u32<kDppRor8>(v));
-  return max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16));
+  v = max(v, dpp_u32<kDppRor8>(v));  // every lane: maximum of its row of 16
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return max(max(a, b), max(c, d));
 }
 
-#ifndef TOMA_GREEDY_TOPK
-#define TOMA_GREEDY_TOPK 2
-#endif
 template <int NT>
 __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *__restrict__ S,
                                                              int32_t *__restrict__ idx,
                                                              float *__restrict__ gain_out, RegionMap map,
                                                              int P, int d_loc) {
   constexpr int NL = 16 * NT;          // tokens in the region
-  constexpr int NW = (NT + 1) / 2;     // waves, 32 rows each
-  constexpr int CPL = (NT + 3) / 4;    // columns per lane
-  constexpr int32_t kPad = 1 << 23;    // m of a padding column: above every S, so it never contributes
-  constexpr uint32_t kBias0 = 1u << 30;  // first step: row sums are signed, |sum| <= 2^30
-  constexpr int kBulk = 12;            // refresh all rows at once when at least this many are due
-  constexpr int kTopK = TOMA_GREEDY_TOPK;  // keys per wave that phase 1 refreshes
-  __shared__ int32_t rowbuf[2][NW][64 * CPL];   // [round parity]: each wave's candidate row
-  // packed best candidates, rotated over three rounds so that a slot is cleared two rounds
-  // before it is written again: [round % 3][0 fresh, 1 best stale runner-up, 2 after phase 2]
-  __shared__ __align__(16) unsigned long long slot[3][4];
+  constexpr int NW = (NT + 1) / 2;     // waves, up to 32 columns each
+  constexpr int RPL = (NL + 63) / 64;  // rows per lane: lane l holds rows RPL l .. RPL l + RPL - 1
+  constexpr int32_t kPad = 1 << 23;    // coverage of a padding column: above every S, so it never changes
+  constexpr int32_t kFloor = -(1 << 22);  // similarity -1: the coverage before the first pick
+  __shared__ uint32_t keys[RPL * 64];     // [64 v + l]: value + 1 of row RPL l + v, 0 once picked
+  __shared__ int32_t rowt[NW * 32];       // row t, column NW c + w at [32 w + c]
+  __shared__ int32_t picks[2][RPL * 64];  // [0] row, [1] value of every pick
 
   const int bp = blockIdx.x, p = bp % P;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, cl = lane & 31;
   const int32_t *Sr = S + (size_t)bp * NL * NL;
 
-  // sv[u][r]: column lane + 64 u of row 32 w + r.  One 32-wide register vector per u, so that a
-  // wave-uniform row number r indexes the registers directly (relative addressing), no dispatch.
+  // Loaded through the symmetric element S[NW c + w][RPL l + v]: a lane reads RPL consecutive
+  // words and consecutive lanes continue the run.
+  typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
   typedef int32_t i32x32 __attribute__((ext_vector_type(32)));
-  i32x32 sv[CPL];
-  int32_t m[CPL];
-  bool col_ok[CPL];
+  i32x32 sv[RPL];  // register vectors, indexed by wave-uniform column numbers (relative addressing)
 #pragma unroll
-  for (int u = 0; u < CPL; u++) {
-    col_ok[u] = lane + 64 * u < NL;
-    m[u] = kPad;
+  for (int c = 0; c < 32; c++) {
+    const int col = NW * c + w;
+    if constexpr (RPL == 4) {  // NL is a multiple of 16: the four rows of a lane exist together
+      const bool ok = col < NL && 4 * lane < NL;
+      const i32x4 q = ok ? *reinterpret_cast<const i32x4 *>(Sr + (size_t)col * NL + 4 * lane) : (i32x4){0, 0, 0, 0};
+      sv[0][c] = q[0]; sv[1][c] = q[1]; sv[2][c] = q[2]; sv[3][c] = q[3];
+    } else {
+#pragma unroll
+      for (int v = 0; v < RPL; v++) {
+        const int row = RPL * lane + v;
+        sv[v][c] = (col < NL && row < NL) ? Sr[(size_t)col * NL + row] : 0;
+      }
+    }
   }
+  const bool col_ok = NW * cl + w < NL;
+  int32_t m = col_ok ? kFloor : kPad;  // coverage of column NW cl + w (lanes l and l + 32 hold the same)
+  // where this lane's rows go in rowt (as columns, by symmetry)
+  int post_at[RPL];
 #pragma unroll
-  for (int r = 0; r < 32; r++)
-#pragma unroll
-    for (int u = 0; u < CPL; u++) {
-      int row = 32 * w + r;
-      sv[u][r] = (row < NL && col_ok[u]) ? Sr[(size_t)row * NL + lane + 64 * u] : 0;
-    }
-  int32_t msum = 0;  // sum of this lane's m: sum_u max(0, s - m) = sum_u max(s, m) - msum
+  for (int v = 0; v < RPL; v++) {
+    const int j = RPL * lane + v;
+    post_at[v] = j < NL ? (j % NW) * 32 + j / NW : -1;
+  }
 
-  const int my_row = 32 * w + lane;
-  const bool my_live0 = lane < 32 && my_row < NL;
-  uint32_t key = 0;  // lane r < 32: value + 1 of row 32w + r, an upper bound between refreshes
+  auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-  // value of row r of this wave (r is wave-uniform): first step = row sum, later = sum max(0, S - m)
-  auto eval = [&](int r, bool first) -> uint32_t {
-    int32_t part = first ? 0 : -msum;
+  // keys under the starting coverage: 1 + sum_j (S_ij + 1)
+  for (int i = threadIdx.x; i < RPL * 64; i += 64 * NW) keys[i] = RPL * (i & 63) + (i >> 6) < NL ? 1u : 0u;
+  lds_barrier();
 #pragma unroll
-    for (int u = 0; u < CPL; u++) {
-      const int32_t v = sv[u][r];
-      part += first ? v : max(v, m[u]);
-    }
-    return wave_sum_u32((uint32_t)part);
-  };
-  // the same, and the row is also posted to rowbuf[buf][w]
-  auto eval_post = [&](int buf, int r) -> uint32_t {
-    int32_t part = -msum;
+  for (int v = 0; v < RPL; v++) {
+    uint32_t part = 0;
 #pragma unroll
-    for (int u = 0; u < CPL; u++) {
-      const int32_t v = sv[u][r];
-      part += max(v, m[u]);
-      rowbuf[buf][w][lane + 64 * u] = v;
-    }
-    return wave_sum_u32((uint32_t)part);
-  };
-  // refresh the keys of all live rows of this wave at once (straight-line code, independent chains)
-  auto eval_all = [&](bool first) {
-#pragma unroll
-    for (int r = 0; r < 32; r++) {
-      int32_t part = first ? 0 : -msum;
-#pragma unroll
-      for (int u = 0; u < CPL; u++) part += first ? sv[u][r] : max(sv[u][r], m[u]);
-      uint32_t g = wave_sum_u32((uint32_t)part);
-      if (lane == r && (first ? my_live0 : key != 0)) key = g + 1u + (first ? kBias0 : 0u);
-    }
-  };
-  auto post_row = [&](int buf, int r) {
-#pragma unroll
-    for (int u = 0; u < CPL; u++) rowbuf[buf][w][lane + 64 * u] = sv[u][r];
-  };
-  // slots 0 and 1 of a round in one 16-byte LDS read
-  auto read_slots = [&](const unsigned long long *ptr, unsigned long long &a, unsigned long long &b) {
-    const u32x4 v = *reinterpret_cast<const u32x4 *>(ptr);
-    const uint32_t a0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[0]);
-    const uint32_t a1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[1]);
-    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[2]);
-    const uint32_t b1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v[3]);
-    a = ((unsigned long long)a1 << 32) | a0;
-    b = ((unsigned long long)b1 << 32) | b0;
-  };
-  auto read_slot = [&](const unsigned long long *ptr) -> unsigned long long {
-    unsigned long long v = *ptr;
-    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
-    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
-    return ((unsigned long long)hi << 32) | lo;
-  };
-  // one LDS atomic from the calling lane (no wave-wide combining code around it)
-  auto lds_max_u64 = [&](unsigned long long *ptr, unsigned long long v) {
-    const uint32_t addr = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)ptr;
-    asm volatile("ds_max_u64 %0, %1" ::"v"(addr), "v"(v) : "memory");
-  };
-  auto pack = [&](uint32_t k, int r) -> unsigned long long {
-    return ((unsigned long long)k << 8) | (unsigned)(255 - (32 * w + r));
-  };
-
-  // LDS traffic is the only thing the waves exchange inside the loop: wait for it, then meet
-  auto lds_barrier = [&]() {
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-  };
-  // picks and their values are kept in registers of wave 0 (pick k in lane k % 64) and written
-  // once at the end, so that no global store sits on the loop's critical path
-  int32_t pick_row[CPL];
-  uint32_t pick_key[CPL];
-#pragma unroll
-  for (int u = 0; u < CPL; u++) { pick_row[u] = 0; pick_key[u] = 0; }
-
-  if (threadIdx.x < 12) slot[threadIdx.x / 4][threadIdx.x % 4] = 0;
+    for (int c = 0; c < 32; c++)
+      if (NW * c + w < NL) part += (uint32_t)(sv[v][c] - kFloor);
+    if (RPL * lane + v < NL)
+      __hip_atomic_fetch_add(&keys[64 * v + lane], part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
   lds_barrier();
 
-  int q3 = 0;  // step % 3
   for (int step = 0; step < d_loc; step++) {
-    const bool first = step == 0;
-    const int buf = step & 1;
-    unsigned long long *sl = slot[q3];
-    bool fresh = false;
-    // ---- phase 1: refresh the row with the largest stale key; post it, and the best of the rest ----
-    if (first) {
-      eval_all(true);
-      fresh = true;
-    }
-    {
-      const uint32_t top = wave_max32_u32(key);
-      if (top != 0) {
-        const int r1 = __builtin_ctzll(__ballot(key == top && lane < 32));
-        if (first) {
-          post_row(buf, r1);
-          if (lane == 0) lds_max_u64(&sl[0], pack(top, r1));
-        } else if (kTopK > 1) {
-          // the kTopK largest keys are refreshed together (independent chains); the best of the
-          // remaining keys stays a stale bound
-          uint32_t kk = key, tk[kTopK];
-          int rk[kTopK];
-          tk[0] = top; rk[0] = r1;
+    // ---- argmax of the keys (lowest index among equals) ----
+    uint32_t bk = 0;
+    int bv = 0;
 #pragma unroll
-          for (int i = 1; i < kTopK; i++) {
-            kk = lane == rk[i - 1] ? 0u : kk;
-            tk[i] = tk[i - 1] ? wave_max32_u32(kk) : 0u;
-            rk[i] = tk[i] ? __builtin_ctzll(__ballot(kk == tk[i] && lane < 32)) : rk[0];
-          }
-          kk = lane == rk[kTopK - 1] ? 0u : kk;
-          const uint32_t rest = tk[kTopK - 1] ? wave_max32_u32(kk) : 0u;
-          const unsigned long long rest_lanes = __ballot(kk == rest && lane < 32);
-          uint32_t gk[kTopK];
-#pragma unroll
-          for (int i = 0; i < kTopK; i++) gk[i] = tk[i] ? eval(rk[i], false) + 1u : 0u;
-          uint32_t gc = gk[0];
-          int rc = rk[0];
-          fresh = lane == rk[0];
-          key = lane == rk[0] ? gk[0] : key;
-#pragma unroll
-          for (int i = 1; i < kTopK; i++) {
-            if (tk[i]) {
-              key = lane == rk[i] ? gk[i] : key;
-              fresh = fresh || lane == rk[i];
-              if (gk[i] > gc || (gk[i] == gc && rk[i] < rc)) { gc = gk[i]; rc = rk[i]; }
-            }
-          }
-          post_row(buf, rc);
-          if (lane == 0) {
-            lds_max_u64(&sl[0], pack(gc, rc));
-            if (rest != 0) lds_max_u64(&sl[1], pack(rest, __builtin_ctzll(rest_lanes)));
-          }
-        } else {
-          // the best of the other keys stays a stale bound (independent of the refresh below)
-          const uint32_t k2 = lane == r1 ? 0u : key;
-          const uint32_t rest = wave_max32_u32(k2);
-          const unsigned long long rest_lanes = __ballot(k2 == rest && lane < 32);
-          const uint32_t g = eval_post(buf, r1) + 1u;
-          const bool mine = lane == r1;
-          key = mine ? g : key;
-          fresh = mine;
-          if (lane == 0) {
-            lds_max_u64(&sl[0], pack(g, r1));
-            if (rest != 0) lds_max_u64(&sl[1], pack(rest, __builtin_ctzll(rest_lanes)));
-          }
-        }
-      }
+    for (int v = 0; v < RPL; v++) {
+      const uint32_t key = keys[64 * v + lane];
+      if (v == 0 || key > bk) { bk = key; bv = v; }
     }
-    lds_barrier();
-    if (threadIdx.x < 4) slot[q3 == 0 ? 2 : q3 - 1][threadIdx.x] = 0;  // the slots of round step + 2
-    unsigned long long best, stale;
-    read_slots(sl, best, stale);
-    if (!first) {
-      if (stale > best) {
-        // ---- phase 2: some stale key still beats the best fresh candidate: refresh those rows ----
-        uint32_t g0 = (uint32_t)(best >> 8);
-        int i0 = 255 - (int)(best & 255u);
-        bool beats = key > g0 || (key == g0 && my_row < i0);
-        unsigned long long need = __ballot(key != 0 && !fresh && beats && lane < 32);
-        if (__builtin_popcountll(need) >= kBulk) {
-          eval_all(false);
-        } else {
-          // two rows per turn: their reduction chains are independent and interleave
-          while (need) {
-            const int ra = __builtin_ctzll(need);
-            need &= need - 1;
-            const int rb = need ? __builtin_ctzll(need) : ra;
-            need &= need - 1;
-            const uint32_t ga = eval(ra, false) + 1u, gb = eval(rb, false) + 1u;
-            key = lane == ra ? ga : key;
-            key = lane == rb ? gb : key;
-          }
-        }
-        uint32_t top = wave_max32_u32(key);
-        if (top != 0) {
-          int r = __builtin_ctzll(__ballot(key == top && lane < 32));
-          post_row(buf, r);
-          if (lane == 0) lds_max_u64(&sl[2], pack(top, r));
-        }
-        lds_barrier();
-        best = read_slot(&sl[2]);
-      }
-    }
-    const uint32_t G = (uint32_t)(best >> 8);
-    const int I = 255 - (int)(best & 255u);
-    const int ww = I >> 5;
-    msum = 0;
+    const uint32_t top = wave_max_u32(bk);
+    const int tl = __builtin_ctzll(__ballot(bk == top));
+    const int tv = __builtin_amdgcn_readlane(bv, tl);
+    const int t = RPL * tl + tv;
+
+    // ---- the owner of column t posts row t ----
+    if (w == t % NW) {
+      const int ct = t / NW;  // wave-uniform register index
 #pragma unroll
-    for (int u = 0; u < CPL; u++) {
-      int32_t mv = rowbuf[buf][ww][lane + 64 * u];
-      m[u] = !col_ok[u] ? kPad : (first ? mv : max(m[u], mv));
-      msum += m[u];
+      for (int v = 0; v < RPL; v++)
+        if (post_at[v] >= 0) rowt[post_at[v]] = sv[v][ct];
     }
-    if (first && my_live0) key = 0xffffffffu;  // row sums are no bounds on later values: force a refresh
-    key = (w == ww && lane == (I & 31)) ? 0u : key;
+    if (threadIdx.x == 0) { picks[0][step] = t; picks[1][step] = (int32_t)(top - 1u); }
+    lds_barrier();  // every wave has read the keys; row t is posted
+
+    // ---- new coverage of the own columns; the changed ones lower the rows' values ----
+    if (threadIdx.x == 0)  // t is picked: its key ends at 0
+      __hip_atomic_fetch_add(&keys[64 * tv + tl], 0u - 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const int32_t x = rowt[32 * w + cl];
+    const int32_t m_old = m;
+    m = max(m, x);
+    uint32_t changed = (uint32_t)__ballot(x > m_old && lane < 32);
+    if (changed) {
+      int32_t dec[RPL];
 #pragma unroll
-    for (int u = 0; u < CPL; u++) {
-      const bool here = step == lane + 64 * u;
-      pick_row[u] = here ? I : pick_row[u];
-      pick_key[u] = here ? G : pick_key[u];
+      for (int v = 0; v < RPL; v++) dec[v] = 0;
+      int32_t sum_a = 0;
+      do {
+        const int c = __builtin_ctz(changed);
+        changed &= changed - 1;
+        const int32_t a = __builtin_amdgcn_readlane(m_old, c), b = __builtin_amdgcn_readlane(m, c);
+        sum_a += a;
+#pragma unroll
+        for (int v = 0; v < RPL; v++) dec[v] += min(max(sv[v][c], a), b);
+      } while (changed);
+#pragma unroll
+      for (int v = 0; v < RPL; v++)
+        if (RPL * lane + v < NL)
+          __hip_atomic_fetch_add(&keys[64 * v + lane], (uint32_t)(sum_a - dec[v]), __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_WORKGROUP);
     }
-    q3 = q3 == 2 ? 0 : q3 + 1;
+    lds_barrier();  // the keys are final for the next round; every wave has read row t
   }
-  if (w == 0) {
-#pragma unroll
-    for (int u = 0; u < CPL; u++) {
-      const int k = lane + 64 * u;
-      if (k < d_loc) {
-        idx[(size_t)bp * d_loc + k] = map.token(p, pick_row[u]);
-        const double v = (double)pick_key[u] - 1.0 - (k == 0 ? (double)kBias0 : 0.0);
-        if (gain_out) gain_out[(size_t)bp * d_loc + k] = (float)(v / kSimScale);
-      }
-    }
+  for (int k = threadIdx.x; k < d_loc; k += 64 * NW) {
+    idx[(size_t)bp * d_loc + k] = map.token(p, picks[0][k]);
+    // the first value is the row sum shifted by N_loc (coverage -1 everywhere)
+    const double val0 = (double)(uint32_t)picks[1][k] - (k == 0 ? (double)NL * 4194304.0 : 0.0);
+    if (gain_out) gain_out[(size_t)bp * d_loc + k] = (float)(val0 / kSimScale);
   }
 }
 
