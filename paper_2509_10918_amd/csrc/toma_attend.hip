@@ -19,7 +19,7 @@
 namespace toma {
 
 template <typename T> struct QkvPol {
-  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false;
+  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false, ACC_T = true;
   const T *Xm, *Xe;
   const T *W[3];
   T *out[3];
@@ -37,19 +37,18 @@ template <typename T> struct QkvPol {
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
                                            int lane) const {
+    // head-major output [B][H][L][dh]: a row's part and a column's part of the offset add up
     T *o = out[x.z];
     const int L_ = L, H_ = H, dh_ = dh;
     store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
-                  [=](int m, int n) {
-                    int b = m / L_, l = m % L_, h = n / dh_, dd = n % dh_;
-                    return o + (((size_t)b * H_ + h) * L_ + l) * dh_ + dd;
-                  },
+                  [=](int m) { const int b = m / L_, l = m - b * L_; return o + ((size_t)b * H_ * L_ + l) * dh_; },
+                  [=](int n) { const int h = n / dh_; return (size_t)h * L_ * dh_ + (n - h * dh_); },
                   [](int) { return 1.0f; });
   }
 };
 
 template <typename T> struct ProjPol {
-  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false;
+  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false, ACC_T = true;
   const T *In, *Wt;
   T *Out;
   const float *Zs;  // when set: rows l < D of every sample are divided by max(Z, 1e-20)
@@ -65,7 +64,8 @@ template <typename T> struct ProjPol {
     T *o = Out;
     const int C_ = C, L_ = L, D_ = D;
     const float *zs = Zs;
-    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N, [=](int m, int n) { return o + (size_t)m * C_ + n; },
+    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N, [=](int m) { return o + (size_t)m * C_; },
+                          [](int n) { return n; },
                           [=](int m) {
                             int b = m / L_, l = m % L_;
                             return (zs && l < D_) ? 1.0f / fmaxf(zs[(size_t)b * D_ + l], 1e-20f) : 1.0f;

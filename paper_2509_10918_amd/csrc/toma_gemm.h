@@ -20,6 +20,12 @@
 //   const T* a_ptr(ctx, int m, int k)     address of element (m, k); the 16-byte packet starting
 //   const T* b_ptr(ctx, int n, int k)     there runs along k (k-contiguous) or along m / n (k-major)
 //   bool a_linear(int step), b_linear(int step)   address is affine in k over multiples of `step`
+//   static constexpr bool ACC_T           accumulator orientation: false = lane holds column
+//                                         n_w + 16 j + lane % 16 and rows m_w + 16 i + 4 (lane / 16) + r;
+//                                         true = the transposed product (operands swapped in the MFMA):
+//                                         lane holds row m_w + 16 i + lane % 16 and the four CONSECUTIVE
+//                                         columns n_w + 16 j + 4 (lane / 16) + r, which a row-major
+//                                         output stores as one 8- or 16-byte packet
 //   void epilogue<TM, TN>(ctx, acc, m_w, n_w, lane)  consume the wave's accumulators
 //   static constexpr bool SPLIT_K         K may be split between workgroups; then also
 //   float* split_buffer()                 fp32 partial tiles [split][batch][M][N], and
@@ -50,23 +56,36 @@ template <typename T, int BM, int BN> struct GemmTile {
 template <int TM, int TN> struct WaveAccT { f32x4 t[TM][TN]; };
 
 // K split between workgroups: the raw fp32 accumulators go to part[split][z][M][N].
-template <int TM, int TN>
+template <bool ACC_T, int TM, int TN>
 __device__ __forceinline__ void store_partial(float *part, const GemmCtx &x, const WaveAccT<TM, TN> &acc, int nbatch,
                                               int m_w, int n_w, int lane) {
   const int g = lane >> 4, c = lane & 15;
   float *base = part + ((size_t)x.split * nbatch + x.z) * x.M * x.N;
+  if constexpr (ACC_T) {
 #pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      const int m = m_w + 16 * i + 4 * g + r;
+    for (int i = 0; i < TM; i++) {
+      const int m = m_w + 16 * i + c;
       if (m >= x.M) continue;
 #pragma unroll
       for (int j = 0; j < TN; j++) {
-        const int n = n_w + 16 * j + c;
-        if (n < x.N) base[(size_t)m * x.N + n] = acc.t[i][j][r];
+        const int n = n_w + 16 * j + 4 * g;
+        if (n < x.N) *reinterpret_cast<f32x4 *>(base + (size_t)m * x.N + n) = acc.t[i][j];
       }
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int m = m_w + 16 * i + 4 * g + r;
+        if (m >= x.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          const int n = n_w + 16 * j + c;
+          if (n < x.N) base[(size_t)m * x.N + n] = acc.t[i][j][r];
+        }
+      }
+  }
 }
 
 // Linear workgroup id -> tile id such that the ids an XCD receives (id mod 8) form a contiguous
@@ -173,7 +192,10 @@ __global__ __launch_bounds__(256) void k_gemm(const Pol pol, int tiles_m, int ti
 #pragma unroll
       for (int i = 0; i < G::TM; i++)
 #pragma unroll
-        for (int j = 0; j < G::TN; j++) mma16(acc.t[i][j], fa[i], fb[j]);
+        for (int j = 0; j < G::TN; j++) {
+          if constexpr (Pol::ACC_T) mma16(acc.t[i][j], fb[j], fa[i]);
+          else mma16(acc.t[i][j], fa[i], fb[j]);
+        }
     }
     if (more) stash(stage ^ 1);
     __syncthreads();
@@ -395,7 +417,10 @@ __global__ __launch_bounds__(512) void k_gemm_async(const Pol pol, int tiles_m, 
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
-      for (int j = 0; j < TN; j++) mma16(acc.t[i][j], fa[i], fb[j]);
+      for (int j = 0; j < TN; j++) {
+        if constexpr (Pol::ACC_T) mma16(acc.t[i][j], fb[j], fa[i]);
+        else mma16(acc.t[i][j], fa[i], fb[j]);
+      }
   };
 
 #pragma unroll
@@ -436,32 +461,41 @@ __global__ __launch_bounds__(512) void k_gemm_async(const Pol pol, int tiles_m, 
 
   if constexpr (Pol::SPLIT_K) {
     if (nsplit > 1) {
-      store_partial<TM, TN>(pol.split_buffer(), ctx, acc, nbatch, m0 + wm * WTM, n0 + wn * WTN, lane);
+      store_partial<Pol::ACC_T, TM, TN>(pol.split_buffer(), ctx, acc, nbatch, m0 + wm * WTM, n0 + wn * WTN, lane);
       return;
     }
   }
   pol.template epilogue<TM, TN>(ctx, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
 }
 
-// Row-major store of a wave's accumulators: element (m, n) goes to ptr(m, n), scaled per row.
-// ptr must be contiguous in n inside an aligned run of 16 columns.
-template <typename T, int TM, int TN, typename PtrFn, typename RowScaleFn>
+// four consecutive output elements as one store
+template <typename T> __device__ __forceinline__ void store4(T *dst, f32x4 v) {
+  alignas(16) T o[4];
+#pragma unroll
+  for (int i = 0; i < 4; i++) o[i] = from_f32<T>(v[i]);
+  if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
+  else *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<u32x4 *>(o);
+}
+
+// Row-major store of a wave's TRANSPOSED accumulators (ACC_T): the four consecutive columns a lane
+// holds of row m go to row(m) + col(n) as one packet, scaled per row.  col(n) .. col(n) + 3 must be
+// contiguous for n a multiple of 4, and N a multiple of 4.
+template <typename T, int TM, int TN, typename RowFn, typename ColFn, typename RowScaleFn>
 __device__ __forceinline__ void store_rows(const WaveAccT<TM, TN> &acc, int m_w, int n_w, int lane, int M, int N,
-                                           PtrFn ptr, RowScaleFn row_scale) {
+                                           RowFn row, ColFn col, RowScaleFn row_scale) {
   const int g = lane >> 4, c = lane & 15;
 #pragma unroll
-  for (int i = 0; i < TM; i++)
+  for (int i = 0; i < TM; i++) {
+    const int m = m_w + 16 * i + c;
+    if (m >= M) continue;
+    T *base = row(m);
+    const float sc = row_scale(m);
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      int m = m_w + 16 * i + 4 * g + r;
-      if (m >= M) continue;
-      float sc = row_scale(m);
-#pragma unroll
-      for (int j = 0; j < TN; j++) {
-        int n = n_w + 16 * j + c;
-        if (n < N) *ptr(m, n) = from_f32<T>(acc.t[i][j][r] * sc);
-      }
+    for (int j = 0; j < TN; j++) {
+      const int n = n_w + 16 * j + 4 * g;
+      if (n < N) store4<T>(base + col(n), acc.t[i][j] * sc);
     }
+  }
 }
 
 // Sum of the K-split partial tiles in a fixed order, then the policy's own output step.  One thread

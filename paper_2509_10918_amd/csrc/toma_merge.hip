@@ -29,7 +29,7 @@ template <typename T> struct RegionView {
 
 // ---- pass 1 and pass 2 of the weights ----------------------------------------------------------
 template <typename T, bool WRITE> struct WeightsPol {
-  static constexpr bool A_KS = false, B_KS = false, SPLIT_K = false;
+  static constexpr bool A_KS = false, B_KS = false, SPLIT_K = false, ACC_T = false;
   RegionView<T> v;
   const int32_t *idx;
   float scale;
@@ -152,17 +152,8 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
 }
 
 // ---- merge -------------------------------------------------------------------------------------
-// four consecutive output elements as one store
-template <typename T> __device__ __forceinline__ void store4(T *dst, f32x4 v) {
-  alignas(16) T o[4];
-#pragma unroll
-  for (int i = 0; i < 4; i++) o[i] = from_f32<T>(v[i]);
-  if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
-  else *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<u32x4 *>(o);
-}
-
 template <typename T> struct MergePol {
-  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true;
+  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true;
   RegionView<T> v;
   const T *A;
   const float *Z;
@@ -191,14 +182,14 @@ template <typename T> struct MergePol {
     T *out = Xm + ((size_t)x.b * v.D + x.rho * v.Dr) * v.C;
     const int Cc = v.C;
     store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
-                  [=](int m, int n) { return out + (size_t)m * Cc + n; },
+                  [=](int m) { return out + (size_t)m * Cc; }, [](int n) { return n; },
                   [=](int m) { return 1.0f / fmaxf(Zr[m], 1e-20f); });
   }
 };
 
 // ---- unmerge -----------------------------------------------------------------------------------
 template <typename T> struct UnmergePol {
-  static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true;
+  static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true, ACC_T = true;
   RegionView<T> v;
   const T *A;
   const T *Os;  // [B][os_rows][C], rows [0, D) already divided by Z
@@ -227,7 +218,7 @@ template <typename T> struct UnmergePol {
     const RegionView<T> vv = v;
     const int rr = x.rho;
     store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
-                  [=](int m, int n) { return out + (size_t)vv.token(rr, m) * vv.C + n; },
+                  [=](int m) { return out + (size_t)vv.token(rr, m) * vv.C; }, [](int n) { return n; },
                   [](int) { return 1.0f; });
   }
 };
