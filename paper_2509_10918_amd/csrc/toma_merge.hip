@@ -36,7 +36,8 @@ template <typename T, bool WRITE> struct WeightsPol {
   float2 *stats;   // pass 1 out: [B*R][Nr][parts]
   int parts;
   const float *lse;  // pass 2 in: [B*R][Nr]
-  T *A;              // pass 2 out: [B*R][Dr][Nr]
+  T *A;              // pass 2 out: [B*R][Dr][lda], lda >= Nr
+  int lda;
   float *zpart;      // pass 2 out: [B*R][Dr][zparts]
   int zparts;
   __device__ __forceinline__ GemmCtx setup(int bz) const {
@@ -102,7 +103,7 @@ template <typename T, bool WRITE> struct WeightsPol {
             o[r] = from_f32<T>(__expf(acc.t[i][j][r] * scale - l4[r]));
             colsum[j] += to_f32(o[r]);
           }
-          T *dst = A + ((size_t)z * N + n) * M + mb;
+          T *dst = A + ((size_t)z * N + n) * lda + mb;
           if (sizeof(T) == 2) {
             *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
           } else {
@@ -155,7 +156,8 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
 template <typename T> struct MergePol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true;
   RegionView<T> v;
-  const T *A;
+  const T *A;  // [B*R][Dr][lda]
+  int lda;
   const float *Z;
   T *Xm;
   float *part;
@@ -170,7 +172,7 @@ template <typename T> struct MergePol {
   __device__ __forceinline__ bool a_linear(int) const { return true; }
   __device__ __forceinline__ bool b_linear(int step) const { return v.token_linear(step); }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &x, int m, int k) const {
-    return A + ((size_t)x.z * x.M + m) * x.K + k;
+    return A + ((size_t)x.z * x.M + m) * lda + k;
   }
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
     return v.X + ((size_t)x.b * v.N + v.token(x.rho, k)) * v.C + n;
@@ -191,7 +193,8 @@ template <typename T> struct MergePol {
 template <typename T> struct UnmergePol {
   static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true, ACC_T = true;
   RegionView<T> v;
-  const T *A;
+  const T *A;  // [B*R][Dr][lda]
+  int lda;
   const T *Os;  // [B][os_rows][C], rows [0, D) already divided by Z
   int os_rows;
   T *Y;
@@ -206,7 +209,7 @@ template <typename T> struct UnmergePol {
   __device__ __forceinline__ bool a_linear(int) const { return true; }
   __device__ __forceinline__ bool b_linear(int) const { return true; }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &x, int m, int k) const {
-    return A + ((size_t)x.z * x.K + k) * x.M + m;
+    return A + ((size_t)x.z * x.K + k) * lda + m;
   }
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
     return Os + ((size_t)x.b * os_rows + x.rho * v.Dr + k) * v.C + n;
@@ -268,7 +271,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
     hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n); }
   WeightsPol<T, true> p2{};
   p2.v = p1.v; p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
-  p2.A = static_cast<T *>(A);
+  p2.A = static_cast<T *>(A); p2.lda = s.Nr;
   p2.zpart = reinterpret_cast<float *>(ws + w.zpart); p2.zparts = w.z_parts;
   const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
   int zr = s.B * s.D;
@@ -288,7 +291,7 @@ static int merge_typed(const Shape &s, const void *X, const void *A, const float
                        const Workspace &w, hipStream_t st) {
   MergePol<T> p{};
   p.v = make_view<T>(s, X);
-  p.A = static_cast<const T *>(A); p.Z = Z; p.Xm = static_cast<T *>(Xm);
+  p.A = static_cast<const T *>(A); p.lda = s.Nr; p.Z = Z; p.Xm = static_cast<T *>(Xm);
   p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_MERGE, p, s.Dr, s.C, s.Nr, s.B * s.R, st);
   return launch_status();
@@ -315,7 +318,7 @@ static int unmerge_typed(const Shape &s, const void *A, const float *Z, const vo
     p.Os = Os; p.os_rows = s.D;
   }
   p.v = make_view<T>(s, nullptr);
-  p.A = static_cast<const T *>(A); p.Y = static_cast<T *>(Y);
+  p.A = static_cast<const T *>(A); p.lda = s.Nr; p.Y = static_cast<T *>(Y);
   p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_UNMERGE, p, s.Nr, s.C, s.Dr, s.B * s.R, st);
   return launch_status();

@@ -10,7 +10,8 @@
 //             mathematically tied candidates (common: two tokens that only improve each other's
 //             coverage) are exact ties that go to the lowest index.
 //   k_greedy  one workgroup per (sample, region); the region's whole S (up to 256 x 256 words)
-//             lives in the workgroup's vector registers (see the comment at the kernel).
+//             lives in the workgroup's vector registers and the rows' values are kept up to date
+//             incrementally (see the comment at the kernel).
 #include "toma_common.h"
 #include "toma_internal.h"
 
@@ -21,118 +22,94 @@ namespace toma {
 constexpr double kSimScale = 4194304.0;
 
 // ------------------------------------------------------------------------------------------------
-// 64 x 64 block of one region's similarity matrix per workgroup, 2 x 2 waves of 32 x 32.  S is
-// symmetric: only blocks on or above the diagonal are computed and each value is stored twice.
-// The token norms come out of the same pass: while a K slice sits in LDS, the first 128 threads add
-// the squares of one row each (64 rows of the left operand, 64 of the right) in double.
+// One wave per 16 x 16 block of one region's similarity matrix.  S is symmetric: only blocks on or
+// above the diagonal are computed and each value is stored twice.
+// The fp64 matrix cores are slow enough (one 16 x 16 x 4 product keeps them busy for tens of
+// cycles) that operand traffic does not matter: every lane reads its fragments straight from global
+// memory (row = lane % 16, eight consecutive channels of k-group lane / 16 per 32-channel chunk), no
+// LDS and no barrier, two chunks ahead of the products; small independent units spread evenly over
+// the chip's SIMDs, which is what bounds this kernel.  The token norms come out of the same pass
+// (sums of squares of the values a lane holds anyway, combined across the four k-groups).
 template <typename T>
 __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *__restrict__ S, RegionMap map,
-                                             int N, int C, int P, int n_loc, int tiles) {
-  constexpr int BK = 32;
-  constexpr int EPP = 16 / (int)sizeof(T);
-  constexpr int LDK = BK + EPP;
-  constexpr int PPR = BK / EPP;
-  constexpr int NP = 64 * PPR / 256;
-  __shared__ __align__(16) T As[64 * LDK];
-  __shared__ __align__(16) T Bs[64 * LDK];
-  __shared__ double nrm[128];
-
-  // blockIdx.x enumerates the pairs (tm <= tn) row by row
-  int tm = 0, rest = blockIdx.x;
+                                             int N, int C, int P, int n_loc, int tiles, int units) {
+  constexpr int EPP = 16 / (int)sizeof(T);  // elements per 16-byte packet
+  constexpr int NPK = 8 / EPP;              // packets per fragment (eight channels)
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const int unit = blockIdx.x * 4 + w;
+  if (unit >= units) return;  // whole wave (no barrier below)
+  // unit enumerates the pairs (tm <= tn) row by row
+  int tm = 0, rest = unit;
   while (rest >= tiles - tm) { rest -= tiles - tm; tm++; }
   const int tn = tm + rest;
   const int bp = blockIdx.y, b = bp / P, p = bp % P;
-  const int m0 = tm * 64, n0 = tn * 64;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
-  const int g = lane >> 4, c = lane & 15;
   const T *Xb = X + (size_t)b * N * C;
+  const T *pa = Xb + (size_t)map.token(p, 16 * tm + c) * C + 8 * g;
+  const T *pb = Xb + (size_t)map.token(p, 16 * tn + c) * C + 8 * g;
 
-  const T *pa[NP], *pb[NP];
-  int lo[NP];
+  struct Chunk { Pkt a[NPK], b[NPK]; };
+  auto fetch = [&](Chunk &ch, int k0) {
 #pragma unroll
-  for (int i = 0; i < NP; i++) {
-    int q = tid + 256 * i, row = q / PPR, kp = q % PPR;
-    lo[i] = row * LDK + kp * EPP;
-    int la = m0 + row, lb = n0 + row;
-    pa[i] = la < n_loc ? Xb + (size_t)map.token(p, la) * C + kp * EPP : nullptr;
-    pb[i] = lb < n_loc ? Xb + (size_t)map.token(p, lb) * C + kp * EPP : nullptr;
-  }
-
-  f64x4 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; i++)
-#pragma unroll
-    for (int j = 0; j < 2; j++) acc[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
-  double sq = 0.0;
-  const T *my_row = tid < 64 ? As + tid * LDK : Bs + (tid - 64) * LDK;
-
-  Pkt ra[NP], rb[NP];
-#pragma unroll
-  for (int i = 0; i < NP; i++) {
-    ra[i] = pa[i] ? pkt_load(pa[i]) : pkt_zero();
-    rb[i] = pb[i] ? pkt_load(pb[i]) : pkt_zero();
-  }
-  for (int k0 = 0; k0 < C; k0 += BK) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < NP; i++) {
-      pkt_store(As + lo[i], ra[i]);
-      pkt_store(Bs + lo[i], rb[i]);
+    for (int i = 0; i < NPK; i++) {
+      ch.a[i] = pkt_load(pa + k0 + i * EPP);
+      ch.b[i] = pkt_load(pb + k0 + i * EPP);
     }
-    __syncthreads();
-    if (k0 + BK < C) {
+  };
+  auto value = [&](const Pkt (&pk)[NPK], int s8) -> double {
+    if constexpr (sizeof(T) == 2) {
+      // bf16 -> fp32 is a 16-bit shift
+      const u32x4 q = pk[0].v;
+      const uint32_t word = q[s8 >> 1];
+      return (double)__builtin_bit_cast(float, (s8 & 1) ? (word & 0xffff0000u) : (word << 16));
+    } else {
+      const u32x4 q = pk[s8 >> 2].v;
+      const uint32_t word = q[s8 & 3];
+      return (double)__builtin_bit_cast(float, word);
+    }
+  };
+
+  // two accumulators: consecutive products do not wait for each other
+  f64x4 acc = (f64x4){0.0, 0.0, 0.0, 0.0}, acc1 = (f64x4){0.0, 0.0, 0.0, 0.0};
+  double sqa = 0.0, sqb = 0.0;
+  const int nchunk = C / 32;
+  Chunk c0, c1, c2;
+  fetch(c0, 0);
+  if (nchunk > 1) fetch(c1, 32);
+  for (int i = 0; i < nchunk; i += 3) {
+    // three-deep rotation written out so that the buffers stay in registers
+    auto work = [&](Chunk &cur, Chunk &nxt2, int ii) {
+      if (ii + 2 < nchunk) fetch(nxt2, (ii + 2) * 32);
 #pragma unroll
-      for (int i = 0; i < NP; i++) {
-        ra[i] = pa[i] ? pkt_load(pa[i] + k0 + BK) : pkt_zero();
-        rb[i] = pb[i] ? pkt_load(pb[i] + k0 + BK) : pkt_zero();
+      for (int s8 = 0; s8 < 8; s8++) {
+        const double av = value(cur.a, s8), bv = value(cur.b, s8);
+        sqa += av * av;
+        sqb += bv * bv;
+        if (s8 & 1) acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc1, 0, 0, 0);
+        else acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
       }
-    }
-    if (tid < 128) {
-#pragma unroll
-      for (int k = 0; k < BK; k++) {
-        double v = (double)to_f32(my_row[k]);
-        sq += v * v;
-      }
-    }
-    Frag<T> fa[2], fb[2];
-#pragma unroll
-    for (int i = 0; i < 2; i++) {
-      frag_load_kc(fa[i], As + (wm * 32 + 16 * i + c) * LDK + 8 * g);
-      frag_load_kc(fb[i], Bs + (wn * 32 + 16 * i + c) * LDK + 8 * g);
-    }
-#pragma unroll
-    for (int s8 = 0; s8 < 8; s8++)
-#pragma unroll
-      for (int i = 0; i < 2; i++)
-#pragma unroll
-        for (int j = 0; j < 2; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)to_f32(fa[i].v[s8]), (double)to_f32(fb[j].v[s8]),
-                                                           acc[i][j], 0, 0, 0);
+    };
+    work(c0, c2, i);
+    if (i + 1 < nchunk) work(c1, c0, i + 1);
+    if (i + 2 < nchunk) work(c2, c1, i + 2);
   }
-  if (tid < 128) {
-    double n = sqrt(sq);
-    nrm[tid] = n > 1e-12 ? n : 1e-12;
-  }
-  __syncthreads();
+  acc += acc1;
+  // norms of row 16 tm + c and of row 16 tn + c: sum over the four k-groups
+  sqa += wave_xor_f64(sqa, 16); sqa += wave_xor_f64(sqa, 32);
+  sqb += wave_xor_f64(sqb, 16); sqb += wave_xor_f64(sqb, 32);
+  double na = sqrt(sqa), nb = sqrt(sqb);
+  na = na > 1e-12 ? na : 1e-12;
+  nb = nb > 1e-12 ? nb : 1e-12;
 
   // fp64 accumulator tile: lane holds column lane % 16 and rows (lane / 16) + 4 r.
   int32_t *Sr = S + (size_t)bp * n_loc * n_loc;
+  const int col = 16 * tn + c;
 #pragma unroll
-  for (int j = 0; j < 2; j++) {
-    int cl = wn * 32 + 16 * j + c, col = n0 + cl;
-    if (col >= n_loc) continue;
-    double ncol = nrm[64 + cl];
-#pragma unroll
-    for (int i = 0; i < 2; i++)
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        int rl = wm * 32 + 16 * i + g + 4 * r, row = m0 + rl;
-        if (row < n_loc) {
-          int32_t v = (int32_t)rint(acc[i][j][r] / (nrm[rl] * ncol) * kSimScale);
-          Sr[(size_t)row * n_loc + col] = v;
-          if (tm != tn) Sr[(size_t)col * n_loc + row] = v;
-        }
-      }
+  for (int r = 0; r < 4; r++) {
+    const int rl = g + 4 * r, row = 16 * tm + rl;
+    const double nrow = __shfl(na, rl, 64);
+    const int32_t v = (int32_t)rint(acc[r] / (nrow * nb) * kSimScale);
+    Sr[(size_t)row * n_loc + col] = v;
+    if (tm != tn) Sr[(size_t)col * n_loc + row] = v;
   }
 }
 
@@ -310,10 +287,10 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, c
                         hipStream_t st) {
   int32_t *S = reinterpret_cast<int32_t *>(ws + w.sim);
   RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
-  int tiles = (s.n_loc + 63) / 64;
+  const int tiles = s.n_loc / 16, units = tiles * (tiles + 1) / 2;
   { KernelTimer kt(K_GRAM, st);
-  hipLaunchKernelGGL(k_gram<T>, dim3(tiles * (tiles + 1) / 2, s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C,
-                     s.P, s.n_loc, tiles); }
+  hipLaunchKernelGGL(k_gram<T>, dim3((units + 3) / 4, s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
+                     s.n_loc, tiles, units); }
   int regions = s.B * s.P;
   KernelTimer kt(K_GREEDY, st);
   switch (s.n_loc / 16) {
