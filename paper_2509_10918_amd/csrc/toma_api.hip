@@ -50,7 +50,7 @@ void plan_workspace(const Shape &s, Workspace *w) {
   // row strides of the partial-result arrays: one entry per wave slice of the weights product
   // (sources x destinations x C), whose block tile is planned here exactly as at launch
   if (gemm_async_fits(s.Nr, s.Dr, s.C, (int)es)) {
-    const GemmPlan pw = plan_gemm_async(s.Nr, s.Dr, s.C, s.B * s.R, (int)es, false);
+    const GemmPlan pw = plan_gemm_async(s.Nr, s.Dr, s.C, s.B * s.R, (int)es, false, false, false, 3);
     w->stat_parts = 2 * ((s.Dr + pw.bn - 1) / pw.bn);
     w->z_parts = 4 * ((s.Nr + pw.bm - 1) / pw.bm);
   } else {
@@ -69,11 +69,11 @@ void plan_workspace(const Shape &s, Workspace *w) {
   // fp32 partial tiles of the merge / unmerge products when their K is split between workgroups
   size_t part = 0;
   if (gemm_async_fits(s.Dr, s.C, s.Nr, (int)es)) {
-    const GemmPlan pm = plan_gemm_async(s.Dr, s.C, s.Nr, s.B * s.R, (int)es, true);
+    const GemmPlan pm = plan_gemm_async(s.Dr, s.C, s.Nr, s.B * s.R, (int)es, true, false, true, 1);
     if (pm.nsplit > 1) part = (size_t)pm.nsplit * s.B * s.D * s.C * sizeof(float);
   }
   if (gemm_async_fits(s.Nr, s.C, s.Dr, (int)es)) {
-    const GemmPlan pu = plan_gemm_async(s.Nr, s.C, s.Dr, s.B * s.R, (int)es, true);
+    const GemmPlan pu = plan_gemm_async(s.Nr, s.C, s.Dr, s.B * s.R, (int)es, true, true, true, 1);
     if (pu.nsplit > 1) part = std::max(part, (size_t)pu.nsplit * s.B * s.N * s.C * sizeof(float));
   }
   w->split = take(part);

@@ -20,6 +20,7 @@ namespace toma {
 
 template <typename T> struct QkvPol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false, ACC_T = true;
+  static constexpr int EPI = 1;
   const T *Xm, *Xe;
   const T *W[3];
   T *out[3];
@@ -49,6 +50,7 @@ template <typename T> struct QkvPol {
 
 template <typename T> struct ProjPol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false, ACC_T = true;
+  static constexpr int EPI = 1;
   const T *In, *Wt;
   T *Out;
   const float *Zs;  // when set: rows l < D of every sample are divided by max(Z, 1e-20)

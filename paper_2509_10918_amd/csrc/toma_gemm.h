@@ -27,6 +27,7 @@
 //                                         columns n_w + 16 j + 4 (lane / 16) + r, which a row-major
 //                                         output stores as one 8- or 16-byte packet
 //   void epilogue<TM, TN>(ctx, acc, m_w, n_w, lane)  consume the wave's accumulators
+//   static constexpr int EPI              weight of the epilogue in the tile planner's cost model
 //   static constexpr bool SPLIT_K         K may be split between workgroups; then also
 //   float* split_buffer()                 fp32 partial tiles [split][batch][M][N], and
 //   void finish(ctx, m, n, f32x4 v)       output step for four consecutive columns of a summed row
@@ -536,7 +537,7 @@ template <typename T, typename Pol>
 inline GemmShape launch_gemm(int kernel_id, const Pol &pol, int M, int N, int K, int batch, hipStream_t st) {
   if (gemm_async_fits(M, N, K, (int)sizeof(T))) {
     // load-to-LDS pipeline
-    const GemmPlan pl = plan_gemm_async(M, N, K, batch, (int)sizeof(T), Pol::SPLIT_K);
+    const GemmPlan pl = plan_gemm_async(M, N, K, batch, (int)sizeof(T), Pol::SPLIT_K, Pol::A_KS, Pol::B_KS, Pol::EPI);
     const GemmShape g{pl.bm, pl.bn, 4, 2, (M + pl.bm - 1) / pl.bm, (N + pl.bn - 1) / pl.bn, pl.nsplit};
     const dim3 grid(g.tiles_m * g.tiles_n * batch * g.nsplit);
     {

@@ -35,13 +35,21 @@ inline bool gemm_async_fits(int M, int N, int K, int elem_size) {
   return K % bk == 0 && M >= epp && N >= epp;
 }
 struct GemmPlan { int bm, bn, nsplit; };
-// Cost model in shader clocks, from measurements of the kernel on MI355X: a K step of a workgroup
-// costs about step[] (bound by the 50 B/clk a CU moves from L2 into LDS, and by the matrix cores for
-// the largest tile), a workgroup pays a fixed prologue + epilogue, and the grid runs in rounds of
-// one workgroup per CU (two for the 64 x 64 tile).  Splitting K adds a pass over the fp32 partials.
-inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, bool may_split) {
+// Cost model in shader clocks, fitted to measurements of the kernel on MI355X (sweeps of every tile
+// and split on the SDXL-sized products): a K step of a workgroup costs about step[][] (it depends on
+// which operands are k-major: their fragment reads go through the LDS transpose path), a workgroup
+// pays a fixed prologue + epilogue (epi weighs the epilogue: 1 = plain stores, 3 = the softmax
+// statistics / exponentials of the merge weights), and the grid runs in rounds of one workgroup per
+// CU (two for the narrow tiles).  Splitting K adds a pass that reads every fp32 partial tile and
+// writes the output.
+inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, bool may_split, bool a_ks, bool b_ks,
+                                int epi) {
   static const int bm[5] = {256, 256, 128, 128, 64}, bn[5] = {256, 128, 128, 64, 64};
-  static const int step[5] = {3600, 2200, 1300, 1000, 700}, per_cu[5] = {1, 1, 1, 1, 2};
+  static const int step[3][5] = {{3400, 2500, 1500, 1250, 700},   // both operands k-contiguous
+                                 {6300, 2700, 1800, 1050, 700},   // one k-major
+                                 {4300, 2700, 1600, 1100, 700}};  // both k-major
+  static const int per_cu[5] = {1, 1, 1, 2, 2};
+  const int kind = (a_ks ? 1 : 0) + (b_ks ? 1 : 0);
   const int nk = K / (128 / elem_size);
   GemmPlan best{128, 128, 1};
   double best_cost = -1.0;
@@ -51,10 +59,10 @@ inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, b
       if (ns > 1 && nk / ns < 8) break;
       const long long blocks = tiles * ns, slots = 256ll * per_cu[i];
       const long long rounds = (blocks + slots - 1) / slots;
-      const double fixed = 3000.0 + bm[i] * bn[i] / 8.0;
+      const double fixed = 4000.0 + epi * bm[i] * bn[i] / 8.0;
       const long long share = std::min<long long>(per_cu[i], (blocks + 255) / 256);  // workgroups sharing a CU
-      double cost = rounds * (((nk + ns - 1) / ns) * (double)step[i] * share + fixed);
-      if (ns > 1) cost += 6000.0 + 0.02 * ns * (double)M * N * batch / 256.0;
+      double cost = rounds * (((nk + ns - 1) / ns) * (double)step[kind][i] * share + fixed);
+      if (ns > 1) cost += 8000.0 + (4.0 * ns + elem_size) * (double)M * N * batch / 1500.0;
       if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = GemmPlan{bm[i], bn[i], ns}; }
     }
   }

@@ -30,6 +30,7 @@ template <typename T> struct RegionView {
 // ---- pass 1 and pass 2 of the weights ----------------------------------------------------------
 template <typename T, bool WRITE> struct WeightsPol {
   static constexpr bool A_KS = false, B_KS = false, SPLIT_K = false, ACC_T = false;
+  static constexpr int EPI = 3;
   RegionView<T> v;
   const int32_t *idx;
   float scale;
@@ -155,6 +156,7 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
 // ---- merge -------------------------------------------------------------------------------------
 template <typename T> struct MergePol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true;
+  static constexpr int EPI = 1;
   RegionView<T> v;
   const T *A;  // [B*R][Dr][lda]
   int lda;
@@ -192,6 +194,7 @@ template <typename T> struct MergePol {
 // ---- unmerge -----------------------------------------------------------------------------------
 template <typename T> struct UnmergePol {
   static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true, ACC_T = true;
+  static constexpr int EPI = 1;
   RegionView<T> v;
   const T *A;  // [B*R][Dr][lda]
   int lda;
