@@ -251,16 +251,41 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
   }
 }
 
+// Maximum / sum over the four 16-lane rows of a wave without LDS traffic: the gfx950 row-swap
+// instructions exchange odd with even rows (16) and the upper with the lower half (32); after each
+// swap the two results hold the two partners of every lane.
+__device__ __forceinline__ float rows4_max_f32(float v) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m = fmaxf(__builtin_bit_cast(float, (uint32_t)a[0]), __builtin_bit_cast(float, (uint32_t)a[1]));
+  const uint32_t w = __builtin_bit_cast(uint32_t, m);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)b[0]), __builtin_bit_cast(float, (uint32_t)b[1]));
+}
+__device__ __forceinline__ float rows4_sum_f32(float v) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m = __builtin_bit_cast(float, (uint32_t)a[0]) + __builtin_bit_cast(float, (uint32_t)a[1]);
+  const uint32_t w = __builtin_bit_cast(uint32_t, m);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return __builtin_bit_cast(float, (uint32_t)b[0]) + __builtin_bit_cast(float, (uint32_t)b[1]);
+}
+
 // The same attention with K and V tiles copied global -> LDS by the load-to-LDS path through a ring
-// of three tiles (one barrier per 64 keys, two tiles of loads in flight behind the matrix cores)
-// and bank-conflict-free swizzled tiles; the softmax scale is folded into the exponent's FMA.
-template <typename T, int DH>
-__global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, const T *__restrict__ Kx,
-                                                   const T *__restrict__ V, T *__restrict__ O, int L, int H,
-                                                   float scale_log2, const float *__restrict__ Zs, int D) {
+// of four tiles (one barrier per 64 keys, two tiles of loads in flight) and bank-conflict-free
+// swizzled tiles; the softmax scale is folded into the exponent's FMA.
+// Software pipeline inside each wave: the score products of tile t + 1 are issued BEFORE the
+// softmax of tile t, so that the matrix cores work on them while the vector ALU does the maxima,
+// exponentials and packing of tile t (a wave executes in order; with one or two waves per SIMD
+// nothing else would overlap the two).
+template <typename T, int DH, int QT>
+__global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn_async(const T *__restrict__ Q, const T *__restrict__ Kx,
+                                                                     const T *__restrict__ V, T *__restrict__ O, int L,
+                                                                     int H, float scale_log2,
+                                                                     const float *__restrict__ Zs, int D) {
   constexpr int ES = (int)sizeof(T), EPP = 16 / ES;
   constexpr int PPR = DH / EPP;       // 16-byte packets per K / V row
-  constexpr int KK = DH / 32, DT = DH / 16, QT = 2, STAGES = 3;
+  constexpr int KK = DH / 32, DT = DH / 16, STAGES = 4;  // QT: query tiles (of 16) per wave
   constexpr int CH = PPR;             // 1 KiB chunks per 64-row tile
   constexpr int NI = CH / 4;          // load instructions per wave per tile, for K and for V
   constexpr int TILE = 64 * DH;
@@ -271,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, 
   const int h = blockIdx.y, b = blockIdx.z;
   const size_t head = ((size_t)b * H + h) * L * DH;
   const T *Qh = Q + head, *Kh = Kx + head, *Vh = V + head;
-  const int q_w = blockIdx.x * 128 + w * 32;
+  const int q_w = blockIdx.x * (64 * QT) + w * (16 * QT);
   const int nt = (L + 63) / 64;
 
   Frag<T> fq[QT][KK];
@@ -324,22 +349,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, 
 #pragma unroll
   for (int qt = 0; qt < QT; qt++) { m_run[qt] = -__builtin_inff(); l_run[qt] = 0.f; }
 
-  // the query loads must have landed before the ring starts: from here on only the ring's own
-  // loads are outstanding, and only the waits below order them
-  wait_vmcnt<0>();
-  issue(0, 0);
-  if (nt > 1) issue(1, 1);
-  // one step per 64 keys; the ring position is a compile-time constant of each of the three
-  // unrolled copies, so LDS addresses of the fragment reads are loop-invariant plus an immediate
-  auto tile_step = [&](auto stage_c, int it) {
-    constexpr int ST = decltype(stage_c)::value;
-    if (it + 1 < nt) wait_vmcnt<2 * NI>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    if (it + 2 < nt) issue((ST + 2) % STAGES, it + 2);
-    const T *kt_ = Ks[ST], *vt_ = Vs[ST];
-    const int key0 = it * 64;
-
-    f32x4 st[4][QT];
+  // transposed scores of one tile: st[kt][qt] holds keys 16 kt + 4 g + r (rows) of query c (column)
+  auto scores = [&](f32x4 (&st)[4][QT], const T *kt_) {
 #pragma unroll
     for (int kk = 0; kk < KK; kk++)
 #pragma unroll
@@ -352,7 +363,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, 
           mma16(st[kt][qt], fk, fq[qt][kk]);
         }
       }
-
+  };
+  // online softmax of one tile's scores and O^T += V^T P^T
+  auto softmax_pv = [&](f32x4 (&st)[4][QT], const T *vt_, int key0) {
     if (key0 + 64 > L) {  // only the last tile can reach past the end (uniform branch)
 #pragma unroll
       for (int qt = 0; qt < QT; qt++)
@@ -370,8 +383,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, 
       for (int kt = 0; kt < 4; kt++)
 #pragma unroll
         for (int r = 0; r < 4; r++) mx = fmaxf(mx, st[kt][qt][r]);
-      mx = fmaxf(mx, wave_xor_f32(mx, 16));
-      mx = fmaxf(mx, wave_xor_f32(mx, 32));
+      mx = rows4_max_f32(mx);
       const float m_new = fmaxf(m_run[qt], mx);
       const bool grew = __any(m_new != m_run[qt]);  // the output is rescaled only when some maximum moved
       const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * scale_log2);
@@ -396,7 +408,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, 
       pack_probs(fp[qt][0], st[0][qt], st[1][qt]);
       pack_probs(fp[qt][1], st[2][qt], st[3][qt]);
     }
-
+    // slot s of k-group g is key 32 u + 4 g + s (s < 4) or 32 u + 16 + 4 g + s - 4, matching how
+    // the probabilities were packed
 #pragma unroll
     for (int u = 0; u < 2; u++)
 #pragma unroll
@@ -407,18 +420,43 @@ __global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, 
         for (int qt = 0; qt < QT; qt++) mma16(oacc[dt][qt], fv, fp[qt][u]);
       }
   };
-  for (int it = 0; it < nt; it += 3) {
-    tile_step(std::integral_constant<int, 0>{}, it);
-    if (it + 1 < nt) tile_step(std::integral_constant<int, 1>{}, it + 1);
-    if (it + 2 < nt) tile_step(std::integral_constant<int, 2>{}, it + 2);
+
+  // the query loads must have landed before the ring starts: from here on only the ring's own
+  // loads are outstanding, and only the waits below order them
+  wait_vmcnt<0>();
+  issue(0, 0);
+  if (nt > 1) issue(1, 1);
+  if (nt > 2) issue(2, 2);
+  if (nt > 2) wait_vmcnt<4 * NI>(); else if (nt > 1) wait_vmcnt<2 * NI>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  f32x4 sa[4][QT], sb[4][QT];
+  scores(sa, Ks[0]);
+  // one step per 64 keys; ring position and score buffer are compile-time constants of each of
+  // the four unrolled copies
+  auto tile_step = [&](auto stage_c, f32x4 (&cur)[4][QT], f32x4 (&nxt)[4][QT], int it) {
+    constexpr int ST = decltype(stage_c)::value;
+    if (it + 1 < nt) {
+      // this wave's part of tile it + 1 has landed (tile it + 2 may still be in flight); after the
+      // barrier so has everyone's, and every wave is done with tile it - 1
+      if (it + 2 < nt) wait_vmcnt<2 * NI>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      if (it + 3 < nt) issue((ST + 3) % STAGES, it + 3);
+      scores(nxt, Ks[(ST + 1) % STAGES]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    softmax_pv(cur, Vs[ST], it * 64);
+  };
+  for (int it = 0; it < nt; it += 4) {
+    tile_step(std::integral_constant<int, 0>{}, sa, sb, it);
+    if (it + 1 < nt) tile_step(std::integral_constant<int, 1>{}, sb, sa, it + 1);
+    if (it + 2 < nt) tile_step(std::integral_constant<int, 2>{}, sa, sb, it + 2);
+    if (it + 3 < nt) tile_step(std::integral_constant<int, 3>{}, sb, sa, it + 3);
   }
 
   const int Cw = H * DH;
 #pragma unroll
   for (int qt = 0; qt < QT; qt++) {
-    float l = l_run[qt];
-    l += wave_xor_f32(l, 16);
-    l += wave_xor_f32(l, 32);
+    const float l = rows4_sum_f32(l_run[qt]);
     float inv = 1.0f / l;
     int q = q_w + 16 * qt + c;
     if (q >= L) continue;
@@ -435,17 +473,27 @@ __global__ __launch_bounds__(256, 2) void k_attn_async(const T *__restrict__ Q, 
   }
 }
 
+#ifndef TOMA_ATTN_QT
+#define TOMA_ATTN_QT 2
+#endif
 template <typename T, int DH>
-static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, const float *Zs, hipStream_t st) {
+static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, const float *Zs, hipStream_t st,
+                        int qt = TOMA_ATTN_QT) {
   float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  dim3 grid((s.L + 127) / 128, s.heads, s.B);
   KernelTimer kt(K_ATTN, st);
-  // load-to-LDS pipeline when a row is at least eight packets and three tiles fit the LDS
+  // load-to-LDS pipeline when a row is at least eight packets and the ring of four tiles fits the LDS
   constexpr int kRowPackets = DH * (int)sizeof(T) / 16;
-  if constexpr (kRowPackets >= 8 && 3 * 2 * 64 * DH * (int)sizeof(T) <= 160 * 1024 - 4096) {
-    hipLaunchKernelGGL((k_attn_async<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+  if constexpr (kRowPackets >= 8 && 4 * 2 * 64 * DH * (int)sizeof(T) <= 160 * 1024 - 4096) {
+    if (qt == 1) {
+      dim3 grid((s.L + 63) / 64, s.heads, s.B);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+    } else {
+      dim3 grid((s.L + 127) / 128, s.heads, s.B);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 2>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+    }
     return;
   }
+  dim3 grid((s.L + 127) / 128, s.heads, s.B);
   hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
 }
 
