@@ -326,7 +326,7 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
     const int ch = w * NI + t, row = ch * (64 / PPR) + lane / PPR, pos = lane % PPR;
     k_row[t] = row;
     kp[t] = Kh + (size_t)row * DH + ((pos & ~7) | ((pos ^ row) & 7)) * EPP;
-    vp[t] = Vh + (size_t)row * DH + (pos ^ ((row & 3) << 1)) * EPP;
+    vp[t] = Vh + (size_t)row * DH + SwzTile<T>::template ks_slot<PPR>(row, pos) * EPP;
   }
   auto issue = [&](int st, int it) {
     const ptrdiff_t adv = (ptrdiff_t)it * 64 * DH;

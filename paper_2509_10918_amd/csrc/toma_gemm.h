@@ -225,9 +225,17 @@ template <typename T> struct SwzTile {
   template <int PPR> __device__ static __forceinline__ int kcw(int row, int kp) {
     return (row * PPR + ((kp & ~7) | ((kp ^ row) & 7))) * EPP;
   }
-  // k-major tile: rows of PPR packets; packet pi of row k sits at slot pi ^ ((k & 3) << 1)
+  // k-major tile: rows of PPR packets; packet pi of row k sits at slot ks_slot(k, pi).  A transpose
+  // read touches, per 16 lanes, four consecutive k-rows x 32 bytes: the low bits of k spread them
+  // over one 128-byte bank group; bit 3 of k (the second 16 lanes of each half wave sit eight rows
+  // further) selects the other 128-byte group when a row is long enough to have one.
+  template <int PPR> __device__ static __forceinline__ int ks_slot(int k, int pi) {
+    int s = pi ^ ((k & 3) << 1);
+    if (PPR >= 16) s ^= ((k >> 3) & 1) << 3;
+    return s;
+  }
   template <int PPR> __device__ static __forceinline__ int ks(int k, int pi) {
-    return (k * PPR + (pi ^ ((k & 3) << 1))) * EPP;
+    return (k * PPR + ks_slot<PPR>(k, pi)) * EPP;
   }
 };
 
@@ -330,7 +338,7 @@ __global__ __launch_bounds__(512) void k_gemm_async(const Pol pol, int tiles_m, 
     const int ch = w * NIA + t;
     if (Pol::A_KS) {
       const int k = ch * (64 / PPR_A) + lane / PPR_A, pos = lane % PPR_A;
-      a_k[t] = k; a_i[t] = (pos ^ ((k & 3) << 1)) * G::EPP;
+      a_k[t] = k; a_i[t] = SwzTile<T>::template ks_slot<PPR_A>(k, pos) * G::EPP;
     } else {
       const int row = ch * 8 + (lane >> 3);
       a_i[t] = row; a_k[t] = ((lane & 7) ^ (row & 7)) * G::EPP;
@@ -344,7 +352,7 @@ __global__ __launch_bounds__(512) void k_gemm_async(const Pol pol, int tiles_m, 
     const int ch = w * NIB + t;
     if (Pol::B_KS) {
       const int k = ch * (64 / PPR_B) + lane / PPR_B, pos = lane % PPR_B;
-      b_k[t] = k; b_i[t] = (pos ^ ((k & 3) << 1)) * G::EPP;
+      b_k[t] = k; b_i[t] = SwzTile<T>::template ks_slot<PPR_B>(k, pos) * G::EPP;
     } else {
       const int row = ch * 8 + (lane >> 3);
       b_i[t] = row; b_k[t] = ((lane & 7) ^ (row & 7)) * G::EPP;

@@ -69,6 +69,15 @@ inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, b
   return best;
 }
 
+// The single-pass merge-weight kernel keeps a (32 sources) x (all destinations of the merge region)
+// logit tile in the accumulators of one workgroup: it needs the destinations of a region to be
+// 128 * {1, 2, 4, 8, 16}, the sources a multiple of 32, and rows of a multiple of 128 bytes.
+inline bool weights_fused_fits(int Nr, int Dr, int C, int elem_size) {
+  const int nj = Dr / 128;
+  return Dr % 128 == 0 && (nj == 1 || nj == 2 || nj == 4 || nj == 8 || nj == 16) && Nr % 32 == 0 &&
+         (C * elem_size) % 128 == 0;
+}
+
 int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s);
 void plan_workspace(const Shape &s, Workspace *w);
 

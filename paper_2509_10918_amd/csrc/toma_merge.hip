@@ -13,6 +13,8 @@
 // Unmerge.  Y = A^T diag(1/Z) O: both operands are k-major; O is scaled by 1/Z beforehand.
 // The destination gather X[idx] and the region split / reassembly are address arithmetic inside
 // the tile loads and stores; no token is ever copied into a region-major layout.
+#include <type_traits>
+
 #include "toma_gemm.h"
 #include "toma_internal.h"
 
@@ -153,6 +155,198 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
   if (c == 0) Z[row] = sum;
 }
 
+// ---- weights in one pass ------------------------------------------------------------------------
+// One workgroup (8 waves) holds the logits of 32 sources against ALL Dr = 128 NJ destinations of the
+// merge region in its accumulators (wave w: destinations 16 NJ w .. 16 NJ (w + 1) - 1, 2 x NJ MFMA
+// tiles), so the softmax over destinations needs no second product: the statistics are exchanged
+// through LDS and A is written straight from the accumulators.
+// A K step is 128 bytes of every row: two 32-channel fragments (bf16) or one (fp32).  A destination
+// row is used by one wave only: every wave streams its own rows through a PRIVATE ring of LDS
+// stages (two MFMA tiles = 4 KiB each) with the load-to-LDS path, three stages ahead of the
+// products, and only its own s_waitcnt orders them.  The 32 source rows of a step are shared: four
+// waves fetch them into a double buffer and the workgroup meets once per K step.
+// Partial row sums of the STORED weights go to zpart[.][source tile] for k_zsum, as in the
+// two-pass path.
+template <typename T, int NJ>
+__global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, const int32_t *__restrict__ idx, float scale,
+                                                     T *__restrict__ A, int lda, float *__restrict__ zpart,
+                                                     int zparts) {
+  constexpr int ES = (int)sizeof(T), EPS = 128 / ES;   // elements per K step
+  constexpr int EPP = 16 / ES;
+  constexpr int NH = ES == 2 ? 2 : 1;                  // fragments per row per K step
+  constexpr int JS = NJ < 2 ? 1 : 2;                   // MFMA tiles per stage
+  constexpr int SPS = NJ / JS;                         // stages per K step
+  constexpr int RS = 4;                                // ring stages per wave
+  constexpr int LPS = 2 * JS;                          // load instructions (1 KiB) per stage
+  constexpr int STAGE = JS * 16 * EPS;                 // elements per stage
+  __shared__ __align__(1024) T Bs[8][RS][2 * 16 * EPS];  // per wave ring (sized for two tiles per stage)
+  __shared__ __align__(1024) T As[2][32 * EPS];          // the step's 32 source rows, double buffered
+  __shared__ int boff[8][NJ][16];    // element offset of destination row (wave, tile j, row) inside the sample
+  __shared__ float red[8][32];       // per wave partial statistic of the 32 source rows
+  __shared__ float rowstat[32];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
+  const int z = blockIdx.y, b = z / v.R, rho = z % v.R;
+  const int m0 = blockIdx.x * 32;
+  const T *Xb = v.X + (size_t)b * v.N * v.C;
+  for (int e = tid; e < 8 * 16 * NJ; e += 512) {
+    const int ww = e / (16 * NJ), jj = (e / 16) % NJ, rr = e % 16;
+    int t = idx[(size_t)b * v.D + rho * v.Dr + ww * 16 * NJ + 16 * jj + rr];
+    t = t < 0 ? 0 : (t >= v.N ? v.N - 1 : t);
+    boff[ww][jj][rr] = t * v.C;
+  }
+  __syncthreads();
+
+  // what this lane fetches of a 1 KiB chunk (8 rows x 128 bytes): row lane / 8, and the packet that
+  // the swizzle places at position lane % 8 of that row
+  const int l_row = lane >> 3;
+  const int l_pkt = ((lane & 7) ^ (l_row & 7)) * EPP;
+  // source rows: wave w < 4 fetches rows 8 w .. 8 w + 7 of every step
+  const T *a_src = Xb + (size_t)v.token(rho, m0 + 8 * (w & 3) + l_row) * v.C + l_pkt;
+  const int nsteps = v.C / EPS, U = nsteps * SPS;
+  auto issue_a = [&](int s) { load_to_lds16(a_src + s * EPS, As[s & 1] + (w & 3) * (1024 / ES)); };
+  auto issue_b = [&](int u) {
+    const int s = u / SPS, q = u - s * SPS;
+    T *dst = Bs[w][u & (RS - 1)];
+#pragma unroll
+    for (int ch = 0; ch < LPS; ch++) {
+      const int row_off = boff[w][q * JS + (ch >> 1)][8 * (ch & 1) + l_row];
+      load_to_lds16(Xb + row_off + s * EPS + l_pkt, dst + ch * (1024 / ES));
+    }
+  };
+  auto fence = [&]() { asm volatile("" ::: "memory"); };
+
+  f32x4 acc[2][NJ];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < NJ; j++) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // the offset reads above are LDS reads: they must have returned before M0-based loads reuse the
+  // registers (the compiler's own waits cover them); from here on vmcnt counts only ring loads
+  wait_vmcnt<0>();
+  if (w < 4) issue_a(0);
+#pragma unroll
+  for (int u = 0; u < RS - 1; u++)
+    if (u < U) issue_b(u);
+  wait_vmcnt<0>();
+  fence();
+  __builtin_amdgcn_s_barrier();
+  fence();
+
+  for (int s = 0; s < nsteps; s++) {
+    if (w < 4 && s + 1 < nsteps) issue_a(s + 1);
+    Frag<T> fa[2][NH];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int h = 0; h < NH; h++) frag_load_kc_sw(fa[i][h], As[s & 1], 16 * i + c, 32 * h + 8 * g);
+#pragma unroll
+    for (int q = 0; q < SPS; q++) {
+      const int u = s * SPS + q;
+      if (u + RS - 1 < U) issue_b(u + RS - 1);
+      // this wave's loads of stage u are the oldest outstanding ones
+      const int younger = min(U - 1 - u, RS - 1);
+      if (younger >= 3) wait_vmcnt<3 * LPS>();
+      else if (younger == 2) wait_vmcnt<2 * LPS>();
+      else if (younger == 1) wait_vmcnt<LPS>();
+      else wait_vmcnt<0>();
+      fence();
+      const T *bt = Bs[w][u & (RS - 1)];
+#pragma unroll
+      for (int t = 0; t < JS; t++)
+#pragma unroll
+        for (int h = 0; h < NH; h++) {
+          Frag<T> fb;
+          frag_load_kc_sw(fb, bt, 16 * t + c, 32 * h + 8 * g);
+#pragma unroll
+          for (int i = 0; i < 2; i++) mma16(acc[i][q * JS + t], fa[i][h], fb);
+        }
+      // the fragment reads of this stage have returned before its slot is refilled (next trip)
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      fence();
+    }
+    // the next step's source rows have landed (they are older than the ring loads issued during a
+    // long step; a short step waits for them explicitly), and every wave is done with this step's
+    constexpr int kAfterA = SPS * LPS < (RS - 1) * LPS ? SPS * LPS : (RS - 1) * LPS;
+    if ((s + 1) * SPS + RS - 1 <= U) wait_vmcnt<kAfterA>();  // every stage of this step issued a refill after them
+    else wait_vmcnt<0>();                                     // (the last steps issue fewer)
+    fence();
+    __builtin_amdgcn_s_barrier();
+    fence();
+  }
+
+  // ---- softmax over the destinations of every source row ----
+  // lane holds, of rows 16 i + 4 g + r, the columns 16 j + c of its wave's slice
+  float mx[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      float m = -__builtin_inff();
+#pragma unroll
+      for (int j = 0; j < NJ; j++) {
+        acc[i][j][r] *= scale;
+        m = fmaxf(m, acc[i][j][r]);
+      }
+      m = row16_max_f32(m);
+      if (c == 0) red[w][16 * i + 4 * g + r] = m;
+    }
+  __syncthreads();
+  if (tid < 32) {
+    float m = red[0][tid];
+#pragma unroll
+    for (int ww = 1; ww < 8; ww++) m = fmaxf(m, red[ww][tid]);
+    rowstat[tid] = m;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      mx[i][r] = rowstat[16 * i + 4 * g + r];
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < NJ; j++) sum += __expf(acc[i][j][r] - mx[i][r]);
+      sum = row16_sum_f32(sum);
+      if (c == 0) red[w][16 * i + 4 * g + r] = sum;  // (every wave read rowstat after the barrier above)
+    }
+  __syncthreads();
+  if (tid < 32) {
+    float sum = red[0][tid];
+#pragma unroll
+    for (int ww = 1; ww < 8; ww++) sum += red[ww][tid];  // fixed order
+    rowstat[tid] = rowstat[tid] + __logf(sum);           // lse
+  }
+  __syncthreads();
+  // ---- A[j][s] = exp(L - lse[s]) in dtype, destination-major; partial row sums of the stored values ----
+  float l4[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) l4[i][r] = rowstat[16 * i + 4 * g + r];
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int n = w * 16 * NJ + 16 * j + c;
+    float colsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      alignas(16) T o[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        o[r] = from_f32<T>(__expf(acc[i][j][r] - l4[i][r]));
+        colsum += to_f32(o[r]);
+      }
+      T *dst = A + ((size_t)z * v.Dr + n) * lda + m0 + 16 * i + 4 * g;
+      if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
+      else *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<u32x4 *>(o);
+    }
+    colsum += wave_xor_f32(colsum, 16);
+    colsum += wave_xor_f32(colsum, 32);
+    if (g == 0) zpart[((size_t)z * v.Dr + n) * zparts + blockIdx.x] = colsum;
+  }
+}
+
 // ---- merge -------------------------------------------------------------------------------------
 template <typename T> struct MergePol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true;
@@ -263,6 +457,32 @@ template <typename T>
 static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, char *ws,
                          const Workspace &w, hipStream_t st) {
   int batch = s.B * s.R;
+  const int zr = s.B * s.D;
+  float *zpart = reinterpret_cast<float *>(ws + w.zpart);
+  if (weights_fused_fits(s.Nr, s.Dr, s.C, (int)sizeof(T))) {
+    const RegionView<T> v = make_view<T>(s, X);
+    const dim3 grid(s.Nr / 32, batch);
+    {
+      KernelTimer kt(K_WWRITE, st);
+      switch (s.Dr / 128) {
+#define TOMA_WF_CASE(NJ)                                                                                       \
+  case NJ:                                                                                                     \
+    hipLaunchKernelGGL((k_weights_fused<T, NJ>), grid, dim3(512), 0, st, v, idx, s.scale, static_cast<T *>(A), \
+                       s.Nr, zpart, w.z_parts);                                                                \
+    break;
+        TOMA_WF_CASE(1)
+        TOMA_WF_CASE(2)
+        TOMA_WF_CASE(4)
+        TOMA_WF_CASE(8)
+        TOMA_WF_CASE(16)
+#undef TOMA_WF_CASE
+        default: return TOMA_ERR_UNSUPPORTED;
+      }
+    }
+    KernelTimer kt(K_ZSUM, st);
+    hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, zpart, Z, zr, w.z_parts, s.Nr / 32);
+    return launch_status();
+  }
   WeightsPol<T, false> p1{};
   p1.v = make_view<T>(s, X);
   p1.idx = idx; p1.scale = s.scale;
@@ -275,9 +495,8 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   WeightsPol<T, true> p2{};
   p2.v = p1.v; p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
   p2.A = static_cast<T *>(A); p2.lda = s.Nr;
-  p2.zpart = reinterpret_cast<float *>(ws + w.zpart); p2.zparts = w.z_parts;
+  p2.zpart = zpart; p2.zparts = w.z_parts;
   const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
-  int zr = s.B * s.D;
   { KernelTimer kt(K_ZSUM, st);
     hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
   return launch_status();
