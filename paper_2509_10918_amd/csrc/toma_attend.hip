@@ -293,10 +293,14 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
   __shared__ __align__(1024) T Vs[STAGES][TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
-  const int h = blockIdx.y, b = blockIdx.z;
+  // one-dimensional grid over (sample, head, query block), remapped so that the blocks an XCD
+  // receives are neighbours: the query blocks of a head then share that head's K and V in one L2
+  const int nq = (L + 64 * QT - 1) / (64 * QT);
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  const int qb = work % nq, h = (work / nq) % H, b = work / (nq * H);
   const size_t head = ((size_t)b * H + h) * L * DH;
   const T *Qh = Q + head, *Kh = Kx + head, *Vh = V + head;
-  const int q_w = blockIdx.x * (64 * QT) + w * (16 * QT);
+  const int q_w = qb * (64 * QT) + w * (16 * QT);
   const int nt = (L + 63) / 64;
 
   Frag<T> fq[QT][KK];
@@ -485,10 +489,10 @@ static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O
   constexpr int kRowPackets = DH * (int)sizeof(T) / 16;
   if constexpr (kRowPackets >= 8 && 4 * 2 * 64 * DH * (int)sizeof(T) <= 160 * 1024 - 4096) {
     if (qt == 1) {
-      dim3 grid((s.L + 63) / 64, s.heads, s.B);
+      dim3 grid((s.L + 63) / 64 * s.heads * s.B);
       hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
     } else {
-      dim3 grid((s.L + 127) / 128, s.heads, s.B);
+      dim3 grid((s.L + 127) / 128 * s.heads * s.B);
       hipLaunchKernelGGL((k_attn_async<T, DH, 2>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
     }
     return;

@@ -127,6 +127,13 @@ __device__ __forceinline__ float row16_sum_f32(float v) {
   return v;
 }
 
+// Linear workgroup id -> tile id such that the ids an XCD receives (id mod 8) form a contiguous
+// run of tiles.
+__device__ __forceinline__ int xcd_remap(int id, int total) {
+  const int per = total >> 3, body = per << 3;
+  return id < body ? (id & 7) * per + (id >> 3) : id;
+}
+
 // Wave-level helpers (64 lanes).
 __device__ __forceinline__ float wave_xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 __device__ __forceinline__ double wave_xor_f64(double v, int mask) { return __shfl_xor(v, mask, 64); }

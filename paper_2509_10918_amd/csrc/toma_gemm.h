@@ -89,13 +89,6 @@ __device__ __forceinline__ void store_partial(float *part, const GemmCtx &x, con
   }
 }
 
-// Linear workgroup id -> tile id such that the ids an XCD receives (id mod 8) form a contiguous
-// run of tiles.
-__device__ __forceinline__ int xcd_remap(int id, int total) {
-  const int per = total >> 3, body = per << 3;
-  return id < body ? (id & 7) * per + (id >> 3) : id;
-}
-
 template <typename T, typename Pol, int BM, int BN>
 __global__ __launch_bounds__(256) void k_gemm(const Pol pol, int tiles_m, int tiles_n) {
   typedef GemmTile<T, BM, BN> G;

@@ -36,13 +36,18 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
   constexpr int EPP = 16 / (int)sizeof(T);  // elements per 16-byte packet
   constexpr int NPK = 8 / EPP;              // packets per fragment (eight channels)
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
-  const int unit = blockIdx.x * 4 + w;
+  // one-dimensional grid over (region, group of four units), remapped so that an XCD works on whole
+  // regions: their tokens then stay in that XCD's L2
+  const int groups = (units + 3) / 4;
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  const int bp = work / groups;
+  const int unit = (work - bp * groups) * 4 + w;
   if (unit >= units) return;  // whole wave (no barrier below)
   // unit enumerates the pairs (tm <= tn) row by row
   int tm = 0, rest = unit;
   while (rest >= tiles - tm) { rest -= tiles - tm; tm++; }
   const int tn = tm + rest;
-  const int bp = blockIdx.y, b = bp / P, p = bp % P;
+  const int b = bp / P, p = bp % P;
   const T *Xb = X + (size_t)b * N * C;
   const T *pa = Xb + (size_t)map.token(p, 16 * tm + c) * C + 8 * g;
   const T *pb = Xb + (size_t)map.token(p, 16 * tn + c) * C + 8 * g;
@@ -289,7 +294,7 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, c
   RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
   const int tiles = s.n_loc / 16, units = tiles * (tiles + 1) / 2;
   { KernelTimer kt(K_GRAM, st);
-  hipLaunchKernelGGL(k_gram<T>, dim3((units + 3) / 4, s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
+  hipLaunchKernelGGL(k_gram<T>, dim3((units + 3) / 4 * s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
                      s.n_loc, tiles, units); }
   int regions = s.B * s.P;
   KernelTimer kt(K_GREEDY, st);
