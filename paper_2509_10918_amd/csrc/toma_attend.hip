@@ -21,6 +21,7 @@ namespace toma {
 template <typename T> struct QkvPol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false, ACC_T = true;
   static constexpr int EPI = 1;
+  static constexpr bool EPI_LDS = false;
   const T *Xm, *Xe;
   const T *W[3];
   T *out[3];
@@ -37,7 +38,7 @@ template <typename T> struct QkvPol {
   }
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
-                                           int lane) const {
+                                           int lane, void *wave_lds) const {
     // head-major output [B][H][L][dh]: a row's part and a column's part of the offset add up
     T *o = out[x.z];
     const int L_ = L, H_ = H, dh_ = dh;
@@ -51,6 +52,7 @@ template <typename T> struct QkvPol {
 template <typename T> struct ProjPol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false, ACC_T = true;
   static constexpr int EPI = 1;
+  static constexpr bool EPI_LDS = false;
   const T *In, *Wt;
   T *Out;
   const float *Zs;  // when set: rows l < D of every sample are divided by max(Z, 1e-20)
@@ -62,7 +64,7 @@ template <typename T> struct ProjPol {
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &, int n, int k) const { return Wt + (size_t)k * C + n; }
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
-                                           int lane) const {
+                                           int lane, void *wave_lds) const {
     T *o = Out;
     const int C_ = C, L_ = L, D_ = D;
     const float *zs = Zs;

@@ -28,6 +28,8 @@
 //                                         output stores as one 8- or 16-byte packet
 //   void epilogue<TM, TN>(ctx, acc, m_w, n_w, lane)  consume the wave's accumulators
 //   static constexpr int EPI              weight of the epilogue in the tile planner's cost model
+//   static constexpr bool EPI_LDS         the epilogue wants wave_lds: TM x TN x 256 elements of LDS
+//                                         scratch per wave (else it is passed a null pointer)
 //   static constexpr bool SPLIT_K         K may be split between workgroups; then also
 //   float* split_buffer()                 fp32 partial tiles [split][batch][M][N], and
 //   void finish(ctx, m, n, f32x4 v)       output step for four consecutive columns of a summed row
@@ -196,7 +198,7 @@ __global__ __launch_bounds__(256) void k_gemm(const Pol pol, int tiles_m, int ti
     stage ^= 1;
   }
 
-  pol.template epilogue<G::TM, G::TN>(ctx, acc, m0 + wm * (BM / 2), n0 + wn * (BN / 2), lane);
+  pol.template epilogue<G::TM, G::TN>(ctx, acc, m0 + wm * (BM / 2), n0 + wn * (BN / 2), lane, nullptr);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -297,10 +299,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // LDS latency hides behind the matrix cores; the single barrier of a step sits between its two
 // halves, after this wave's last read of the current stage and before its first read of the next.
 // nsplit > 1 splits K between workgroups; their fp32 partial tiles are combined by k_split_finish.
-template <typename T, typename Pol, int BM, int BN, int STAGES>
-__global__ __launch_bounds__(512) void k_gemm_async(const Pol pol, int tiles_m, int tiles_n, int nbatch, int nsplit) {
+template <typename T, typename Pol, int BM, int BN, int STAGES, int WAVES = 8>
+__global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int tiles_m, int tiles_n, int nbatch, int nsplit) {
   typedef GemmTile<T, BM, BN> G;
-  constexpr int WGM = 4, WGN = 2, NWAVES = WGM * WGN;
+  constexpr int WGM = 4, WGN = WAVES / 4, NWAVES = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;               // wave tile
   constexpr int TM = WTM / 16, TN = WTN / 16;                 // 16 x 16 MFMA tiles per wave
   constexpr int A_ELEMS = BM * G::BK, B_ELEMS = BN * G::BK;   // dense: 128 bytes per row / k-row
@@ -467,7 +469,21 @@ __global__ __launch_bounds__(512) void k_gemm_async(const Pol pol, int tiles_m, 
       return;
     }
   }
-  pol.template epilogue<TM, TN>(ctx, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+  // an epilogue that asked for it gets a share of the (now idle) operand tiles as scratch, one
+  // element per accumulator value of the wave: all waves inside the A tiles when those are large
+  // enough, else half of the waves in the A tiles and half in the B tiles
+  void *wave_lds = nullptr;
+  if constexpr (Pol::EPI_LDS) {
+    constexpr int kWave = WTM * WTN;
+    if constexpr (STAGES * A_ELEMS >= NWAVES * kWave) {
+      meet();  // every wave is done reading the tiles
+      wave_lds = &As[0][0] + w * kWave;
+    } else if constexpr (STAGES * A_ELEMS >= NWAVES / 2 * kWave && STAGES * B_ELEMS >= NWAVES / 2 * kWave) {
+      meet();
+      wave_lds = w < NWAVES / 2 ? &As[0][0] + w * kWave : &Bs[0][0] + (w - NWAVES / 2) * kWave;
+    }
+  }
+  pol.template epilogue<TM, TN>(ctx, acc, m0 + wm * WTM, n0 + wn * WTN, lane, wave_lds);
 }
 
 // four consecutive output elements as one store

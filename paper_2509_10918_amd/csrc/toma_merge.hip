@@ -33,6 +33,7 @@ template <typename T> struct RegionView {
 template <typename T, bool WRITE> struct WeightsPol {
   static constexpr bool A_KS = false, B_KS = false, SPLIT_K = false, ACC_T = false;
   static constexpr int EPI = 3;
+  static constexpr bool EPI_LDS = WRITE;
   RegionView<T> v;
   const int32_t *idx;
   float scale;
@@ -58,7 +59,7 @@ template <typename T, bool WRITE> struct WeightsPol {
   }
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
-                                           int lane) const {
+                                           int lane, void *wave_lds) const {
     const int g = lane >> 4, c = lane & 15;
     const int M = x.M, N = x.N, z = x.z;
     if (!WRITE) {
@@ -106,12 +107,37 @@ template <typename T, bool WRITE> struct WeightsPol {
             o[r] = from_f32<T>(__expf(acc.t[i][j][r] * scale - l4[r]));
             colsum[j] += to_f32(o[r]);
           }
-          T *dst = A + ((size_t)z * N + n) * lda + mb;
+          // straight to memory (8 / 16 bytes per lane), or into this wave's LDS scratch: row = the
+          // destination, 16-byte chunk u of a row at position u ^ (row & 7)
+          T *dst;
+          if (wave_lds) {
+            constexpr int EPC = 16 / (int)sizeof(T);  // elements per chunk
+            const int nl = 16 * j + c, ml = 16 * i + 4 * g;
+            constexpr int CPR = 16 * TM / EPC;        // chunks per row (a power of two)
+            dst = static_cast<T *>(wave_lds) + nl * (16 * TM) + (((ml / EPC) ^ (nl & (CPR - 1) & 7)) * EPC) + ml % EPC;
+          } else {
+            dst = A + ((size_t)z * N + n) * lda + mb;
+          }
           if (sizeof(T) == 2) {
             *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
           } else {
             *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<u32x4 *>(o);
           }
+        }
+      }
+      if (wave_lds) {
+        // whole destination rows of the wave tile (16 TM sources = 128 / 256 bytes) leave as 16-byte
+        // packets of consecutive lanes: full cache lines instead of 32-byte pieces
+        constexpr int EPC = 16 / (int)sizeof(T), CPR = 16 * TM / EPC;  // chunks per row
+        constexpr int RPP = 64 / CPR;                                   // rows per pass
+        const int u = lane % CPR, rl = lane / CPR;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // LDS is in order within the wave; this pins the compiler
+#pragma unroll
+        for (int p = 0; p < 16 * TN / RPP; p++) {
+          const int nl = p * RPP + rl, n = n_w + nl, m = m_w + u * EPC;
+          const u32x4 pk = *reinterpret_cast<const u32x4 *>(static_cast<const T *>(wave_lds) + nl * (16 * TM) +
+                                                             ((u ^ (nl & (CPR - 1) & 7)) * EPC));
+          if (n < N && m < M) *reinterpret_cast<u32x4 *>(A + ((size_t)z * N + n) * lda + m) = pk;
         }
       }
       const int part = m_w / (16 * TM);
@@ -351,6 +377,7 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
 template <typename T> struct MergePol {
   static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true;
   static constexpr int EPI = 1;
+  static constexpr bool EPI_LDS = false;
   RegionView<T> v;
   const T *A;  // [B*R][Dr][lda]
   int lda;
@@ -375,7 +402,7 @@ template <typename T> struct MergePol {
   }
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
-                                           int lane) const {
+                                           int lane, void *wave_lds) const {
     const float *Zr = Z + (size_t)x.b * v.D + x.rho * v.Dr;
     T *out = Xm + ((size_t)x.b * v.D + x.rho * v.Dr) * v.C;
     const int Cc = v.C;
@@ -389,6 +416,7 @@ template <typename T> struct MergePol {
 template <typename T> struct UnmergePol {
   static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true, ACC_T = true;
   static constexpr int EPI = 1;
+  static constexpr bool EPI_LDS = false;
   RegionView<T> v;
   const T *A;  // [B*R][Dr][lda]
   int lda;
@@ -413,7 +441,7 @@ template <typename T> struct UnmergePol {
   }
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
-                                           int lane) const {
+                                           int lane, void *wave_lds) const {
     T *out = Y + (size_t)x.b * v.N * v.C;
     const RegionView<T> vv = v;
     const int rr = x.rho;

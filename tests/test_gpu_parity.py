@@ -117,6 +117,41 @@ def test_stages_isolated(oracle, cases, name, tile_local):
     _check_stage("Y (oracle weights)", Y, Y_ref2, tol)
 
 
+@pytest.mark.parametrize("dtype,grid,tile,keep,C", [
+    ("bf16", (16, 16), (8, 8), 0.5, 64),      # 128 destinations: one 128-wide slice per workgroup
+    ("f32", (32, 16), (8, 8), 0.5, 32),       # 256 destinations
+    ("bf16", (32, 32), (8, 8), 0.5, 128),     # 512 destinations
+    ("bf16", (32, 64), (16, 16), 0.5, 64),    # 1024 destinations
+    ("f32", (64, 64), (16, 16), 0.5, 32),     # 2048 destinations: the largest single-pass case
+    ("bf16", (32, 48), (8, 8), 0.5, 64),      # 768 destinations: not a single-pass size, two-pass path
+    ("bf16", (16, 16), (8, 8), 0.25, 64),     # 64 destinations: two-pass path
+])
+def test_merge_weights_region_sizes(oracle, dtype, grid, tile, keep, C):
+    """Global merge weights over every destination count the single-pass kernel is instantiated for
+    (and sizes it does not take), against the oracle's A / Z, Z and merged tokens."""
+    H, Wd = grid
+    th, tw = tile
+    w = synth.scaled(W["tiny"], name="wsize", dtype=dtype, B=2, H=H, W=Wd, C=C, tile_h=th, tile_w=tw, keep=keep,
+                     heads=1, index=13)
+    print(f"[weights sizes] {dtype} grid {H}x{Wd} tile {th}x{tw} D={w.D} C={C}", flush=True)
+    inp = synth.make_inputs(w)
+    tol = tg.TOL[dtype]
+    X = _f64(inp["X"])
+    d = tg.oracle_desc(oracle, w, 1)
+    idx, _, _ = oracle.select(d, X)
+    A_ref, Z_ref, _ = oracle.merge_weights(d, X, idx)
+    Xm_ref = oracle.merge(d, X, A_ref, Z_ref)
+    dv = tg.Device(w, inp, 1)
+    A, Z, Xm = dv.merge(idx=idx)
+    At_ref = A_ref / np.maximum(Z_ref, 1e-20).reshape(w.B, 1, -1, 1)
+    At = A / np.maximum(Z, 1e-20).reshape(w.B, 1, -1, 1)
+    _check_stage("A~", At, At_ref, tol)
+    _check_stage("Z", Z, Z_ref, tol)
+    _check_stage("Xm", Xm, Xm_ref, tol)
+    # every source token's weights over the destinations sum to one (softmax over destinations)
+    assert np.allclose(A.sum(axis=2), 1.0, atol=3 * tol)
+
+
 @pytest.mark.parametrize("tile_local", [False, True])
 @pytest.mark.parametrize("name", list(CASES))
 def test_layer_chained_and_reuse(oracle, cases, name, tile_local):
