@@ -229,3 +229,34 @@ def test_select_per_region_matches_single_region_runs(oracle):
     idxq, _, _ = oracle.select(dq, X)
     Sq = oracle.cosine(X[1, token_of[2]], round_bits=25)
     assert np.array_equal(idxq[1, 2], token_of[2][oracle.greedy_fl(Sq, k)[0]])
+
+
+def test_incremental_value_update_equals_the_full_rescan(oracle):
+    """The identity the selection kernel is built on, checked against the oracle's Alg. 2: after a
+    pick t only the columns j whose coverage rises (S_tj > m_j) change a row's value, by exactly
+    med(S_ij, m_j, m'_j) - m_j, and the first pick is the same rule started from coverage -1.  On
+    the integer similarity grid every sum is exact, so the incrementally kept values must equal
+    the rescanned ones at every step and reproduce the oracle's picks, ties included."""
+    rng = np.random.default_rng(77)
+    bits = 22
+    for n, k in ((48, 24), (64, 64), (33, 10)):
+        X = rng.standard_normal((n, 12)) + 0.5 * rng.standard_normal((1, 12))
+        X[n // 2] = X[3]                      # duplicated tokens: exact ties
+        S = oracle.cosine(X, round_bits=bits)
+        picks, gains, _ = oracle.greedy_fl(S, k)
+        Si = np.rint(S * (1 << bits)).astype(np.int64)
+        m = np.full(n, -(1 << bits), np.int64)
+        val = (Si - m[None, :]).sum(axis=1)   # sum_j (S_ij + 1): row sum + n on the grid
+        live = np.ones(n, bool)
+        for step in range(k):
+            t = int(np.argmax(np.where(live, val, -1)))      # lowest index among equals
+            assert t == picks[step]
+            shown = val[t] - (n << bits if step == 0 else 0)  # the first value is the plain row sum
+            assert shown == pytest.approx(gains[step] * (1 << bits), abs=1e-3)
+            live[t] = False
+            m_new = np.maximum(m, Si[t])
+            ch = np.nonzero(m_new > m)[0]
+            val = val - (np.clip(Si[:, ch], m[ch][None, :], m_new[ch][None, :]) - m[ch][None, :]).sum(axis=1)
+            m = m_new
+            assert np.array_equal(val, np.maximum(Si - m[None, :], 0).sum(axis=1))
+            assert val[t] == 0                # a picked row's value falls to exactly zero
