@@ -302,7 +302,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 template <typename T, typename Pol, int BM, int BN, int STAGES, int WAVES = 8>
 __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int tiles_m, int tiles_n, int nbatch, int nsplit) {
   typedef GemmTile<T, BM, BN> G;
-  constexpr int WGM = 4, WGN = WAVES / 4, NWAVES = WGM * WGN;
+  constexpr int WGM = WAVES == 4 ? 2 : 4, WGN = WAVES / WGM, NWAVES = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;               // wave tile
   constexpr int TM = WTM / 16, TN = WTN / 16;                 // 16 x 16 MFMA tiles per wave
   constexpr int A_ELEMS = BM * G::BK, B_ELEMS = BN * G::BK;   // dense: 128 bytes per row / k-row

@@ -65,6 +65,9 @@ WORKLOADS = {
     "flux": Workload("flux", 3, "bf16", 1, 64, 64, 3072, 16, 16, 0.25, 24, 512, 2.0, 0.0),
     "hires": Workload("hires", 4, "bf16", 2, 128, 128, 640, 16, 16, 0.5, 10, 0, 3.0, 0.0,
                       steps=10, drift=0.02, reselect_every=5, reweight_every=2),
+    # the SDXL stage-1 shape with stripe-shaped regions (Sec. 4.3.1: contiguous rows, four grid rows
+    # = 256 tokens per region): same inputs as "sdxl1", only the region map differs
+    "sdxl1_stripe": Workload("sdxl1_stripe", 1, "bf16", 2, 64, 64, 640, 4, 64, 0.5, 10, 0, 2.0, 0.2),
 }
 
 
