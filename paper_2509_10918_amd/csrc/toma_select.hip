@@ -269,7 +269,13 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
         const int32_t a = __builtin_amdgcn_readlane(m_old, c), b = __builtin_amdgcn_readlane(m, c);
         sum_a += a;
 #pragma unroll
-        for (int v = 0; v < RPL; v++) dec[v] += min(max(sv[v][c], a), b);
+        for (int v = 0; v < RPL; v++) {
+          // clamp to [a, b] (a < b) as one median instruction; at most one operand may be scalar
+          int32_t cl3;
+          const int32_t bvec = b;
+          asm("v_med3_i32 %0, %1, %2, %3" : "=v"(cl3) : "v"(sv[v][c]), "s"(a), "v"(bvec));
+          dec[v] += cl3;
+        }
       } while (changed);
 #pragma unroll
       for (int v = 0; v < RPL; v++)
