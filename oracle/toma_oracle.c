@@ -495,3 +495,29 @@ ORACLE_API void toma_oracle_unmerge(const oracle_desc *d, const double *A, const
 }
 
 /* Sec. 4.2.2 (Moore-Penrose unmerge, the alternative the paper measures against): not built. */
+
+/* ---------------------------------------------------------------------------------------------
+ * A feed-forward core module (Sec. 4.2: the module between merge and unmerge may be attention
+ * or an MLP; Sec. 5.1's ToMA_once runs every module of a block on the merged tokens):
+ *   out = gelu(X W1) W2,   gelu(x) = x/2 (1 + erf(x / sqrt 2)),
+ * X [rows, C], W1 [C, hidden], W2 [hidden, C], no biases.  (The paper does not fix the MLP's
+ * form; this is the textbook two-layer GELU block.)
+ * --------------------------------------------------------------------------------------------- */
+ORACLE_API void toma_oracle_mlp(int rows, int C, int hidden, const double *X, const double *W1,
+                                const double *W2, double *out) {
+#pragma omp parallel for
+  for (int r = 0; r < rows; r++) {
+    double *h = (double *)malloc(sizeof(double) * (size_t)hidden);
+    for (int j = 0; j < hidden; j++) {
+      double acc = 0.0;
+      for (int k = 0; k < C; k++) acc += X[(size_t)r * C + k] * W1[(size_t)k * hidden + j];
+      h[j] = 0.5 * acc * (1.0 + erf(acc / sqrt(2.0)));
+    }
+    for (int c = 0; c < C; c++) {
+      double acc = 0.0;
+      for (int j = 0; j < hidden; j++) acc += h[j] * W2[(size_t)j * C + c];
+      out[(size_t)r * C + c] = acc;
+    }
+    free(h);
+  }
+}

@@ -176,6 +176,16 @@ def attend_rows(Xm, Xe, Wq, Wk, Wv, heads, rows):
     return out
 
 
+def mlp(X, W1, W2):
+    """gelu(X W1) W2 on the rows of X (any leading shape)."""
+    X, W1, W2 = _f64(X), _f64(W1), _f64(W2)
+    C, hidden = W1.shape
+    rows = X.size // C
+    out = np.empty_like(X)
+    lib().toma_oracle_mlp(rows, C, hidden, _d(X), _d(W1), _d(W2), _d(out))
+    return out
+
+
 def unmerge(d, A, Z, O):
     A, Z, O = _f64(A), _f64(Z), _f64(O)
     N = d.H * d.W

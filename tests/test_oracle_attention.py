@@ -123,3 +123,22 @@ def test_text_rows_pass_through(oracle):
     out = oracle.layer(d, X, *Wt, heads=heads, Xe=Xe)
     assert out["O"].shape == (B, 16 + T, C) and np.array_equal(out["Y_extra"], out["O"][:, 16:])
     assert out["Y"].shape == (B, 64, C)
+
+
+def test_mlp_matches_numpy_and_scipy_erf(oracle):
+    """The feed-forward module against numpy products and scipy's erf (an independent library),
+    plus two closed forms: zero input gives zero, and a large positive pre-activation passes
+    through unchanged (gelu(x) -> x)."""
+    from scipy.special import erf
+    rng = np.random.default_rng(31)
+    X = rng.standard_normal((3, 7, 16))
+    W1 = rng.standard_normal((16, 40)) / 4.0
+    W2 = rng.standard_normal((40, 16)) / 6.0
+    H = X @ W1
+    ref = (0.5 * H * (1.0 + erf(H / np.sqrt(2.0)))) @ W2
+    assert np.allclose(oracle.mlp(X, W1, W2), ref, rtol=1e-12, atol=1e-12)
+    assert np.array_equal(oracle.mlp(np.zeros((2, 16)), W1, W2), np.zeros((2, 16)))
+    big = np.full((1, 16), 50.0)
+    eye = np.eye(16)
+    assert np.allclose(oracle.mlp(big, eye, eye), big, rtol=1e-12)
+    assert np.allclose(oracle.mlp(-big, eye, eye), 0.0, atol=1e-12)
