@@ -147,6 +147,24 @@ int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse
                void *Y_extra_opt, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * A feed-forward core module for merged tokens (Sec. 4.2: the module between merge and unmerge may
+ * be attention or an MLP; the ToMA_once variant of Sec. 5.1 merges once per block and runs every
+ * module of the block on the merged tokens before one unmerge):
+ *   Out = gelu(In W1) W2,   gelu(x) = x/2 (1 + erf(x / sqrt 2)),  no biases.
+ * The paper does not fix the MLP's form; this is the plain two-layer GELU block.  A block in the
+ * ToMA_once style is toma_merge / toma_merge_cached, toma_attend, toma_mlp, toma_unmerge.
+ *   dtype   toma_dtype of every tensor
+ *   In      in       [rows, C]       rows = all token rows of the batch, e.g. B * (D + t_extra)
+ *   W1      in       [C, hidden]     row-major, y = x W
+ *   W2      in       [hidden, C]
+ *   Hbuf    scratch  [rows, hidden]  caller-owned, contents undefined afterwards
+ *   Out     out      [rows, C]       may not alias In
+ * Limits: C % 32 == 0 and hidden % 32 == 0.  Errors as for the other calls.
+ */
+int toma_mlp(int32_t dtype, int32_t rows, int32_t C, int32_t hidden, const void *In, const void *W1,
+             const void *W2, void *Hbuf, void *Out, void *stream);
+
+/*
  * Profiling aid for benchmarks (not part of the method; for callers that want per-kernel times).
  * While enabled, every kernel the library launches is bracketed by two HIP events recorded on the
  * launch stream (this is the one place where the library creates HIP objects: events, kept in a

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libtoma.so")
 TOMA_F32, TOMA_BF16 = 0, 1
 TOMA_REUSE_IDX, TOMA_REUSE_A = 1, 2
 EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_merge",
-           "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer", "toma_profile_enable",
+           "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer", "toma_mlp", "toma_profile_enable",
            "toma_profile_kernel_name", "toma_profile_read")
 
 
@@ -70,7 +70,9 @@ def lib():
         L.toma_attend.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_unmerge.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
         L.toma_layer.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-        for name in ("toma_select", "toma_merge", "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer"):
+        L.toma_mlp.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
+        for name in ("toma_select", "toma_merge", "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer",
+                     "toma_mlp"):
             getattr(L, name).restype = ctypes.c_int
         L.toma_profile_enable.argtypes = [ctypes.c_int]
         L.toma_profile_kernel_name.restype = ctypes.c_char_p
@@ -154,6 +156,15 @@ def toma_layer(desc, attn, reuse_flags, X, X_extra, idx, A, Z, Wq, Wk, Wv, Wo, Y
     _check(lib().toma_layer(_ref(desc), _ref(attn), int(reuse_flags), _ptr(X), _ptr(X_extra), _ptr(idx), _ptr(A),
                             _ptr(Z), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo), _ptr(Y), _ptr(Y_extra), _ptr(ws),
                             ws.numel(), _stream()), "toma_layer")
+
+
+def toma_mlp(In, W1, W2, Hbuf, Out):
+    """Out = gelu(In W1) W2 on the rows of In ([..., C]); Hbuf is [rows, hidden] scratch."""
+    C, hidden = W1.shape
+    rows = In.numel() // C
+    code = TOMA_BF16 if In.dtype == torch.bfloat16 else TOMA_F32
+    _check(lib().toma_mlp(code, rows, C, hidden, _ptr(In), _ptr(W1), _ptr(W2), _ptr(Hbuf), _ptr(Out), _stream()),
+           "toma_mlp")
 
 
 def toma_profile_enable(on):

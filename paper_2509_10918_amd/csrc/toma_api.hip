@@ -227,3 +227,15 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
   if (s.T > 0) rc = launch_copy_extra(s, O, Y_extra_opt, st);
   return rc;
 }
+
+TOMA_API int toma_mlp(int32_t dtype, int32_t rows, int32_t C, int32_t hidden, const void *In, const void *W1,
+                      const void *W2, void *Hbuf, void *Out, void *stream) {
+  if (dtype != TOMA_F32 && dtype != TOMA_BF16) return TOMA_ERR_UNSUPPORTED;
+  if (rows <= 0 || C <= 0 || hidden <= 0) return TOMA_ERR_SHAPE;
+  if (C % 32 || hidden % 32) return TOMA_ERR_UNSUPPORTED;
+  if ((long long)rows * std::max(C, hidden) >= (1ll << 40)) return TOMA_ERR_UNSUPPORTED;
+  if (!In || !W1 || !W2 || !Hbuf || !Out) return TOMA_ERR_NULL;
+  if (misaligned(In, 16) || misaligned(W1, 16) || misaligned(W2, 16) || misaligned(Hbuf, 16) || misaligned(Out, 16))
+    return TOMA_ERR_ALIGN;
+  return launch_mlp(dtype, rows, C, hidden, In, W1, W2, Hbuf, Out, static_cast<hipStream_t>(stream));
+}

@@ -77,6 +77,39 @@ template <typename T> struct ProjPol {
   }
 };
 
+// Out = act(In W) for a dense [rows, K] x [K, N] product (the feed-forward core module).
+struct ElemGelu {  // gelu(x) = x/2 (1 + erf(x / sqrt 2))
+  __device__ __forceinline__ f32x4 operator()(f32x4 v) const {
+#pragma unroll
+    for (int i = 0; i < 4; i++) v[i] = 0.5f * v[i] * (1.0f + erff(v[i] * 0.70710678118654752f));
+    return v;
+  }
+};
+template <typename T, bool GELU> struct LinearPol {
+  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = false, ACC_T = true;
+  static constexpr int EPI = GELU ? 2 : 1;
+  static constexpr bool EPI_LDS = false;
+  const T *In, *Wt;
+  T *Out;
+  int rows, K, N;
+  __device__ __forceinline__ GemmCtx setup(int) const { return GemmCtx{rows, N, K, 0, 0, 0}; }
+  __device__ __forceinline__ bool a_linear(int) const { return true; }
+  __device__ __forceinline__ bool b_linear(int) const { return true; }
+  __device__ __forceinline__ const T *a_ptr(const GemmCtx &, int m, int k) const { return In + (size_t)m * K + k; }
+  __device__ __forceinline__ const T *b_ptr(const GemmCtx &, int n, int k) const { return Wt + (size_t)k * N + n; }
+  template <int TM, int TN>
+  __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
+                                           int lane, void *wave_lds) const {
+    T *o = Out;
+    const int N_ = N;
+    auto row = [=](int m) { return o + (size_t)m * N_; };
+    auto col = [](int n) { return n; };
+    auto one = [](int) { return 1.0f; };
+    if constexpr (GELU) store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N, row, col, one, ElemGelu());
+    else store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N, row, col, one);
+  }
+};
+
 // Probabilities (fp32 accumulator registers) -> B-operand fragment slots.
 __device__ __forceinline__ void pack_probs(Frag<bf16_t> &f, const f32x4 &lo, const f32x4 &hi) {
   typedef float f32x8 __attribute__((ext_vector_type(8)));
@@ -535,6 +568,26 @@ int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq
                   hipStream_t st) {
   return s.dtype == TOMA_BF16 ? attend_typed<bf16_t>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st)
                               : attend_typed<float>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st);
+}
+
+template <typename T>
+static int mlp_typed(int rows, int C, int hidden, const void *In, const void *W1, const void *W2, void *Hbuf, void *Out,
+                     hipStream_t st) {
+  LinearPol<T, true> up{};
+  up.In = static_cast<const T *>(In); up.Wt = static_cast<const T *>(W1); up.Out = static_cast<T *>(Hbuf);
+  up.rows = rows; up.K = C; up.N = hidden;
+  launch_gemm<T>(K_MLP_UP, up, rows, hidden, C, 1, st);
+  LinearPol<T, false> down{};
+  down.In = static_cast<const T *>(Hbuf); down.Wt = static_cast<const T *>(W2); down.Out = static_cast<T *>(Out);
+  down.rows = rows; down.K = hidden; down.N = C;
+  launch_gemm<T>(K_MLP_DOWN, down, rows, C, hidden, 1, st);
+  return launch_status();
+}
+
+int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const void *W1, const void *W2, void *Hbuf,
+               void *Out, hipStream_t st) {
+  return dtype == TOMA_BF16 ? mlp_typed<bf16_t>(rows, C, hidden, In, W1, W2, Hbuf, Out, st)
+                            : mlp_typed<float>(rows, C, hidden, In, W1, W2, Hbuf, Out, st);
 }
 
 }  // namespace toma

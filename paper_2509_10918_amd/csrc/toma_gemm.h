@@ -498,9 +498,10 @@ template <typename T> __device__ __forceinline__ void store4(T *dst, f32x4 v) {
 // Row-major store of a wave's TRANSPOSED accumulators (ACC_T): the four consecutive columns a lane
 // holds of row m go to row(m) + col(n) as one packet, scaled per row.  col(n) .. col(n) + 3 must be
 // contiguous for n a multiple of 4, and N a multiple of 4.
-template <typename T, int TM, int TN, typename RowFn, typename ColFn, typename RowScaleFn>
+struct ElemIdentity { __device__ __forceinline__ f32x4 operator()(f32x4 v) const { return v; } };
+template <typename T, int TM, int TN, typename RowFn, typename ColFn, typename RowScaleFn, typename ElemFn = ElemIdentity>
 __device__ __forceinline__ void store_rows(const WaveAccT<TM, TN> &acc, int m_w, int n_w, int lane, int M, int N,
-                                           RowFn row, ColFn col, RowScaleFn row_scale) {
+                                           RowFn row, ColFn col, RowScaleFn row_scale, ElemFn elem = ElemFn()) {
   const int g = lane >> 4, c = lane & 15;
 #pragma unroll
   for (int i = 0; i < TM; i++) {
@@ -511,7 +512,7 @@ __device__ __forceinline__ void store_rows(const WaveAccT<TM, TN> &acc, int m_w,
 #pragma unroll
     for (int j = 0; j < TN; j++) {
       const int n = n_w + 16 * j + 4 * g;
-      if (n < N) store4<T>(base + col(n), acc.t[i][j] * sc);
+      if (n < N) store4<T>(base + col(n), elem(acc.t[i][j] * sc));
     }
   }
 }

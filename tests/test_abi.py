@@ -77,6 +77,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.toma_unmerge(dp, x, x, x, 100, x, ws, need, None) == 2             # fewer rows than D
     assert L.toma_layer(dp, ap, 4, x, None, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
     assert L.toma_layer(dp, ap, 0, x, None, None, x, x, x, x, x, None, x, None, ws, need, None) == 1
+    # feed-forward module: dtype, shape, divisibility, null and alignment checks
+    assert L.toma_mlp(1, 4096, 640, 2560, x, x, x, x, None, None) == 1
+    assert L.toma_mlp(1, 0, 640, 2560, x, x, x, x, x, None) == 2
+    assert L.toma_mlp(1, 4096, 640, 2500, x, x, x, x, x, None) == 5
+    assert L.toma_mlp(7, 4096, 640, 2560, x, x, x, x, x, None) == 5
+    assert L.toma_mlp(0, 4096, 640, 2560, x, x + 4, x, x, x, None) == 3
 
 
 def test_binding_raises_with_status():

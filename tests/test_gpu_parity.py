@@ -216,6 +216,54 @@ def test_attention_shapes_and_output_projection(oracle, dtype, heads, C, L, T):
     _check_stage("O Wo", O2, oracle.attend(_f64(Xm), Xe, *Wts, heads=heads, Wo=_f64(Wo)), tg.TOL[dtype])
 
 
+@pytest.mark.parametrize("dtype,rows,C,hidden", [("f32", 200, 64, 256), ("bf16", 1000, 128, 512),
+                                                  ("bf16", 333, 96, 160), ("bf16", 2 * 2048, 640, 2560)])
+def test_mlp_module(oracle, dtype, rows, C, hidden):
+    """gelu(X W1) W2 against the oracle: ragged row counts, a width the load-to-LDS GEMM cannot take
+    (96 channels in bf16) and the SDXL stage-1 size."""
+    rng = np.random.default_rng(5)
+    q = lambda a: synth.quantize(synth.scaled(W["tiny"], dtype=dtype), a)
+    X = q(rng.standard_normal((rows, C)))
+    W1 = q(rng.standard_normal((C, hidden)) / np.sqrt(C))
+    W2 = q(rng.standard_normal((hidden, C)) / np.sqrt(hidden))
+    print(f"[mlp] {dtype} rows={rows} C={C} hidden={hidden}", flush=True)
+    Xd, W1d, W2d = (tg.dev(a, dtype) for a in (X, W1, W2))
+    Hb = torch.empty((rows, hidden), dtype=Xd.dtype, device="cuda")
+    Out = torch.empty_like(Xd)
+    tb.toma_mlp(Xd, W1d, W2d, Hb, Out)
+    torch.cuda.synchronize()
+    _check_stage("mlp", tg.host(Out), oracle.mlp(_f64(X), _f64(W1), _f64(W2)), tg.TOL[dtype])
+
+
+def test_block_with_one_merge_and_two_modules(oracle, cases):
+    """A block in the ToMA_once style: one merge, attention and the feed-forward module on the merged
+    tokens (with the residual paths a transformer block has left out), one unmerge, chained on
+    the device and compared with the same chain in the oracle."""
+    w, inp = cases["small_bf16"]
+    tol = tg.TOL[w.dtype]
+    rng = np.random.default_rng(6)
+    hidden = 4 * w.C
+    W1 = synth.quantize(w, rng.standard_normal((w.C, hidden)) / np.sqrt(w.C))
+    W2 = synth.quantize(w, rng.standard_normal((hidden, w.C)) / np.sqrt(hidden))
+    X = _f64(inp["X"])
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    d = tg.oracle_desc(oracle, w, 1)
+    idx, _, _ = oracle.select(d, X)
+    A, Z, _ = oracle.merge_weights(d, X, idx)
+    Xm = oracle.merge(d, X, A, Z)
+    O = oracle.attend(Xm, None, *Wts, heads=w.heads)
+    F = oracle.mlp(O, _f64(W1), _f64(W2))
+    Y_ref = oracle.unmerge(d, A, Z, F)
+    dv = tg.Device(w, inp, 1)
+    dv.merge(idx=idx)
+    dv.attend()
+    Hb = torch.empty((w.B * w.D, hidden), dtype=dv.O.dtype, device="cuda")
+    F_dev = torch.empty_like(dv.O)
+    tb.toma_mlp(dv.O, tg.dev(W1, w.dtype), tg.dev(W2, w.dtype), Hb, F_dev)
+    dv.O.copy_(F_dev)
+    _check_stage("Y after merge, attention, mlp, unmerge", dv.unmerge(), Y_ref, tol)
+
+
 def test_binding_reports_errors_on_device():
     w, = (W["tiny"],)
     inp = synth.make_inputs(w)
