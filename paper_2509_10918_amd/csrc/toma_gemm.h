@@ -1,12 +1,16 @@
 // Block GEMM on the matrix cores with LDS-staged tiles, shared by the merge-weight, merge, QKV /
 // output projection and unmerge stages.
 //
-// One workgroup (4 waves, 2 x 2) computes a BM x BN output tile (128 x 128, 128 x 64 or 64 x 64,
-// chosen per launch so that the grid fills the chip); each wave owns (BM/2) x (BN/2) as 16 x 16
-// MFMA tiles.  K advances 128 bytes per step (64 bf16 / 32 fp32) through two LDS stages: the next
-// step's global loads are issued before the current step's products and stored to the other stage
-// after them, so there is one barrier per step.  Workgroup ids are remapped so that the tiles an
-// XCD works on are neighbours (they share operand rows through that XCD's L2).
+// Two kernels compute a BM x BN output tile per workgroup from 16 x 16 MFMA tiles, K advancing
+// 128 bytes per step (64 bf16 / 32 fp32):
+//   k_gemm_async  the main one: 8 waves (4 x 2), tiles from 256 x 256 down to 64 x 64, operand tiles
+//                 copied global -> LDS by the load-to-LDS path through a ring of 2-4 stages, one
+//                 barrier per step, optional K split between workgroups (see the kernel);
+//   k_gemm        the fallback for shapes the ring cannot take (K not a multiple of the step): 4
+//                 waves (2 x 2), 128 x 128 / 128 x 64 / 64 x 64, operands staged through registers
+//                 into two LDS stages.
+// Workgroup ids are remapped so that the tiles an XCD works on are neighbours (they share operand
+// rows through that XCD's L2).
 //
 // An operand is either k-contiguous in memory (a row of the matrix is a run of k: tokens, rows of
 // A) or k-major (consecutive k are separate rows and the other index is contiguous: X as the right
@@ -26,7 +30,7 @@
 //                                         lane holds row m_w + 16 i + lane % 16 and the four CONSECUTIVE
 //                                         columns n_w + 16 j + 4 (lane / 16) + r, which a row-major
 //                                         output stores as one 8- or 16-byte packet
-//   void epilogue<TM, TN>(ctx, acc, m_w, n_w, lane)  consume the wave's accumulators
+//   void epilogue<TM, TN>(ctx, acc, m_w, n_w, lane, wave_lds)  consume the wave's accumulators
 //   static constexpr int EPI              weight of the epilogue in the tile planner's cost model
 //   static constexpr bool EPI_LDS         the epilogue wants wave_lds: TM x TN x 256 elements of LDS
 //                                         scratch per wave (else it is passed a null pointer)
