@@ -289,13 +289,25 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
 // Maximum / sum over the four 16-lane rows of a wave without LDS traffic: the gfx950 row-swap
 // instructions exchange odd with even rows (16) and the upper with the lower half (32); after each
 // swap the two results hold the two partners of every lane.
+// Maxima as single instructions: fmaxf() would first copy each operand through v_max(x, x) to
+// quiet signalling NaNs, which scores never are.
+__device__ __forceinline__ float max2_f32(float a, float b) {
+  float d;
+  asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+  return d;
+}
+__device__ __forceinline__ float max3_f32(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
 __device__ __forceinline__ float rows4_max_f32(float v) {
   const uint32_t u = __builtin_bit_cast(uint32_t, v);
   const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const float m = fmaxf(__builtin_bit_cast(float, (uint32_t)a[0]), __builtin_bit_cast(float, (uint32_t)a[1]));
+  const float m = max2_f32(__builtin_bit_cast(float, (uint32_t)a[0]), __builtin_bit_cast(float, (uint32_t)a[1]));
   const uint32_t w = __builtin_bit_cast(uint32_t, m);
   const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-  return fmaxf(__builtin_bit_cast(float, (uint32_t)b[0]), __builtin_bit_cast(float, (uint32_t)b[1]));
+  return max2_f32(__builtin_bit_cast(float, (uint32_t)b[0]), __builtin_bit_cast(float, (uint32_t)b[1]));
 }
 __device__ __forceinline__ float rows4_sum_f32(float v) {
   const uint32_t u = __builtin_bit_cast(uint32_t, v);
@@ -367,15 +379,24 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
     kp[t] = Kh + (size_t)row * DH + ((pos & ~7) | ((pos ^ row) & 7)) * EPP;
     vp[t] = Vh + (size_t)row * DH + SwzTile<T>::template ks_slot<PPR>(row, pos) * EPP;
   }
+  // LDS byte addresses of this wave's first chunk in stage 0 (scalar registers)
+  const uint32_t ks_addr = lds_addr_of(&Ks[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(w) * (NI * 1024);
+  const uint32_t vs_addr = lds_addr_of(&Vs[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(w) * (NI * 1024);
   auto issue = [&](int st, int it) {
     const ptrdiff_t adv = (ptrdiff_t)it * 64 * DH;
-    const bool last = (it + 1) * 64 > L;  // rows past the end repeat row L - 1 and are masked below
+    if ((it + 1) * 64 <= L) {  // uniform: only the last tile can reach past the end
 #pragma unroll
-    for (int t = 0; t < NI; t++) {
-      ptrdiff_t a = adv;
-      if (last && it * 64 + k_row[t] >= L) a = (ptrdiff_t)(L - 1 - k_row[t]) * DH;
-      load_to_lds16(kp[t] + a, Ks[st] + (w * NI + t) * (1024 / ES));
-      load_to_lds16(vp[t] + a, Vs[st] + (w * NI + t) * (1024 / ES));
+      for (int t = 0; t < NI; t++) {
+        load_to_lds16_at(kp[t] + adv, ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_at(vp[t] + adv, vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
+      }
+    } else {  // rows past the end repeat row L - 1 and are masked below
+#pragma unroll
+      for (int t = 0; t < NI; t++) {
+        const ptrdiff_t a = it * 64 + k_row[t] >= L ? (ptrdiff_t)(L - 1 - k_row[t]) * DH : adv;
+        load_to_lds16_at(kp[t] + a, ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_at(vp[t] + a, vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
+      }
     }
   };
 
@@ -384,24 +405,32 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
     for (int qt = 0; qt < QT; qt++) oacc[dt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m_run[QT], l_run[QT];  // running maximum (of the raw scores) and sum per query
+  float m_run[QT], l_run[QT];  // reference point (a recent maximum of the raw scores) and sum per query
+  constexpr float kSlackLog2 = 8.0f;
+  const float slack = kSlackLog2 / scale_log2;  // in units of the raw scores
 #pragma unroll
   for (int qt = 0; qt < QT; qt++) { m_run[qt] = -__builtin_inff(); l_run[qt] = 0.f; }
 
   // transposed scores of one tile: st[kt][qt] holds keys 16 kt + 4 g + r (rows) of query c (column)
+  // All K fragments of the tile are requested before the first product (a scheduling fence keeps
+  // the compiler from folding each read back in front of its use: it would wait out the LDS
+  // latency once per fragment instead of once per tile).
   auto scores = [&](f32x4 (&st)[4][QT], const T *kt_) {
+    Frag<T> fk[KK][4];
 #pragma unroll
     for (int kk = 0; kk < KK; kk++)
 #pragma unroll
-      for (int kt = 0; kt < 4; kt++) {
-        Frag<T> fk;
-        frag_load_kcw_sw<PPR>(fk, kt_, 16 * kt + c, 32 * kk + 8 * g);
+      for (int kt = 0; kt < 4; kt++) frag_load_kcw_sw<PPR>(fk[kk][kt], kt_, 16 * kt + c, 32 * kk + 8 * g);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++)
+#pragma unroll
+      for (int kt = 0; kt < 4; kt++)
 #pragma unroll
         for (int qt = 0; qt < QT; qt++) {
           if (kk == 0) st[kt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-          mma16(st[kt][qt], fk, fq[qt][kk]);
+          mma16(st[kt][qt], fk[kk][kt], fq[qt][kk]);
         }
-      }
   };
   // online softmax of one tile's scores and O^T += V^T P^T
   auto softmax_pv = [&](f32x4 (&st)[4][QT], const T *vt_, int key0) {
@@ -417,17 +446,32 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
     Frag<T> fp[QT][2];
 #pragma unroll
     for (int qt = 0; qt < QT; qt++) {
-      float mx = st[0][qt][0];
+      float mx = max3_f32(st[0][qt][0], st[0][qt][1], st[0][qt][2]);
+      mx = max3_f32(mx, st[0][qt][3], st[1][qt][0]);
 #pragma unroll
-      for (int kt = 0; kt < 4; kt++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) mx = fmaxf(mx, st[kt][qt][r]);
+      for (int kt = 1; kt < 4; kt++) {
+        mx = max3_f32(mx, st[kt][qt][1], st[kt][qt][2]);
+        if (kt < 3) mx = max3_f32(mx, st[kt][qt][3], st[kt + 1][qt][0]);
+        else mx = max2_f32(mx, st[kt][qt][3]);
+      }
       mx = rows4_max_f32(mx);
-      const float m_new = fmaxf(m_run[qt], mx);
-      const bool grew = __any(m_new != m_run[qt]);  // the output is rescaled only when some maximum moved
-      const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * scale_log2);
-      const float mc = m_new * scale_log2;
-      m_run[qt] = m_new;
+      // The reference point of the exponentials follows the running maximum lazily: it moves (and
+      // the sums so far are rescaled) only when some row's maximum has grown by more than
+      // kSlackLog2 in the exponent, i.e. almost never after the first tile.  Until then the
+      // exponentials are at most 2^kSlackLog2, and the final O / l does not depend on the
+      // reference point.
+      const bool grew = __any(mx > m_run[qt] + slack);
+      if (grew) {
+        const float m_new = fmaxf(m_run[qt], mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * scale_log2);
+        m_run[qt] = m_new;
+        l_run[qt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+          for (int r = 0; r < 4; r++) oacc[dt][qt][r] *= alpha;
+      }
+      const float mc = m_run[qt] * scale_log2;
       float psum = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 4; kt++)
@@ -437,13 +481,7 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
           st[kt][qt][r] = pv;
           psum += pv;
         }
-      l_run[qt] = l_run[qt] * alpha + psum;
-      if (grew) {
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-          for (int r = 0; r < 4; r++) oacc[dt][qt][r] *= alpha;
-      }
+      l_run[qt] += psum;
       pack_probs(fp[qt][0], st[0][qt], st[1][qt]);
       pack_probs(fp[qt][1], st[2][qt], st[3][qt]);
     }

@@ -292,6 +292,17 @@ __device__ __forceinline__ void load_to_lds16(const T *gptr, T *lds_chunk) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr)
                : "memory", "m0");
 }
+// The same with the LDS byte address already in a scalar register (see lds_addr_of): pipelines
+// that compute their ring addresses once keep the per-load cost at the M0 write and the load.
+__device__ __forceinline__ uint32_t lds_addr_of(const void *lds_ptr) {
+  const uint32_t a = (uint32_t)(size_t)(__attribute__((address_space(3))) const void *)lds_ptr;
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)a);
+}
+template <typename T>
+__device__ __forceinline__ void load_to_lds16_at(const T *gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr)
+               : "memory", "m0");
+}
 // wait until at most n of this wave's vector-memory loads are outstanding (n < 64)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | (((N >> 4) & 3) << 14));
@@ -372,17 +383,27 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   // the per-step delta of a linear operand is the same for every packet: keep it in a scalar register
   const int da = lin_a ? __builtin_amdgcn_readfirstlane((int)(pol.a_ptr(ctx, m0 + a_i[0], kbase + a_k[0] + G::BK) - pa[0])) : 0;
   const int db = lin_b ? __builtin_amdgcn_readfirstlane((int)(pol.b_ptr(ctx, n0 + b_i[0], kbase + b_k[0] + G::BK) - pb[0])) : 0;
-  auto issue = [&](int kt) {
-    const int st = kt % STAGES, k0 = kbase + kt * G::BK;
+  // Ring positions are passed down as plain integers.  For all but the largest tile the K loop
+  // below is unrolled by the number of stages, which makes them constants after inlining: the LDS
+  // addresses of the loads are then scalar constants off one base, and the fragment reads use
+  // fixed offsets off a few per-lane bases instead of being recomputed every step.  (The
+  // 256 x 256 tile has no registers to spare for per-stage bases and keeps a rolled loop.)
+  constexpr bool kUnroll = BM * BN <= 256 * 128;
+  const uint32_t w_s = (uint32_t)__builtin_amdgcn_readfirstlane(w);
+  const uint32_t a_lds = lds_addr_of(&As[0][0]) + w_s * (NIA * 1024);
+  const uint32_t b_lds = lds_addr_of(&Bs[0][0]) + w_s * (NIB * 1024);
+  auto issue = [&](int st, int kt) {
+    const int k0 = kbase + kt * G::BK;
+    const uint32_t a_st = a_lds + (uint32_t)st * (A_ELEMS * G::ES), b_st = b_lds + (uint32_t)st * (B_ELEMS * G::ES);
 #pragma unroll
     for (int t = 0; t < NIA; t++) {
       const T *src = lin_a ? pa[t] + (ptrdiff_t)kt * da : pol.a_ptr(ctx, m0 + a_i[t], k0 + a_k[t]);
-      load_to_lds16(src, As[st] + (w * NIA + t) * (1024 / G::ES));
+      load_to_lds16_at(src, a_st + (uint32_t)(t * 1024));
     }
 #pragma unroll
     for (int t = 0; t < NIB; t++) {
       const T *src = lin_b ? pb[t] + (ptrdiff_t)kt * db : pol.b_ptr(ctx, n0 + b_i[t], k0 + b_k[t]);
-      load_to_lds16(src, Bs[st] + (w * NIB + t) * (1024 / G::ES));
+      load_to_lds16_at(src, b_st + (uint32_t)(t * 1024));
     }
   };
   // this wave's loads of step kt are the oldest outstanding ones: wait until at most the younger
@@ -399,8 +420,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
-  auto frags = [&](Frag<T> (&fa)[TM], Frag<T> (&fb)[TN], int kt, int kk) {
-    const T *at = As[kt % STAGES], *bt = Bs[kt % STAGES];
+  auto frags = [&](Frag<T> (&fa)[TM], Frag<T> (&fb)[TN], int st, int kk) {
+    const T *at = As[st], *bt = Bs[st];
     const int kf = 32 * kk + 8 * g;
 #pragma unroll
     for (int i = 0; i < TM; i++) {
@@ -430,41 +451,57 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
         else mma16(acc.t[i][j], fa[i], fb[j]);
       }
   };
+  auto next_stage = [](int st) { return st + 1 == STAGES ? 0 : st + 1; };
+  auto prev_stage = [](int st) { return st == 0 ? STAGES - 1 : st - 1; };
+  // runs step(st, kt) for kt = 0 .. nk - 1 with st = kt % STAGES
+  auto k_loop = [&](auto &&step) {
+    if constexpr (kUnroll) {
+      for (int kt = 0; kt < nk; kt += STAGES) {
+        step(0, kt);
+        if constexpr (STAGES >= 2) { if (kt + 1 < nk) step(1, kt + 1); }
+        if constexpr (STAGES >= 3) { if (kt + 2 < nk) step(2, kt + 2); }
+        if constexpr (STAGES >= 4) { if (kt + 3 < nk) step(3, kt + 3); }
+      }
+    } else {
+      for (int kt = 0, st = 0; kt < nk; kt++, st = next_stage(st)) step(st, kt);
+    }
+  };
 
+  // prologue: the loads of the first STAGES - 1 steps
 #pragma unroll
   for (int s = 0; s < STAGES - 1; s++)
-    if (s < nk) issue(s);
+    if (s < nk) issue(s, s);
 
-  if (G::KSUB == 2) {
+  if constexpr (G::KSUB == 2) {
     Frag<T> fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     wait_stage(0);
     meet();
     frags(fa0, fb0, 0, 0);
-    for (int kt = 0; kt < nk; kt++) {
+    k_loop([&](int st, int kt) {
       // every wave is past the barrier of step kt - 1: the stage of step kt - 1 is free
-      if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
-      frags(fa1, fb1, kt, 1);
+      if (kt + STAGES - 1 < nk) issue(prev_stage(st), kt + STAGES - 1);
+      frags(fa1, fb1, st, 1);
       products(fa0, fb0);
       if (kt + 1 < nk) wait_stage(kt + 1);
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's reads of stage kt have returned
       meet();
-      if (kt + 1 < nk) frags(fa0, fb0, kt + 1, 0);
+      if (kt + 1 < nk) frags(fa0, fb0, next_stage(st), 0);
       products(fa1, fb1);
-    }
+    });
   } else {
-    for (int kt = 0; kt < nk; kt++) {
+    k_loop([&](int st, int kt) {
       wait_stage(kt);
       // every wave's part of tile kt has landed, and every wave is done reading tile kt - 1
       meet();
-      if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
+      if (kt + STAGES - 1 < nk) issue(prev_stage(st), kt + STAGES - 1);
 #pragma unroll
       for (int kk = 0; kk < G::KSUB; kk++) {
         Frag<T> fa[TM], fb[TN];
-        frags(fa, fb, kt, kk);
+        frags(fa, fb, st, kk);
         products(fa, fb);
       }
       __builtin_amdgcn_s_waitcnt(0xc07f);
-    }
+    });
   }
 
   if constexpr (Pol::SPLIT_K) {

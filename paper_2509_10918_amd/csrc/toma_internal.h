@@ -45,9 +45,9 @@ struct GemmPlan { int bm, bn, nsplit; };
 inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, bool may_split, bool a_ks, bool b_ks,
                                 int epi) {
   static const int bm[5] = {256, 256, 128, 128, 64}, bn[5] = {256, 128, 128, 64, 64};
-  static const int step[3][5] = {{3400, 2500, 1500, 1250, 700},   // both operands k-contiguous
-                                 {6300, 2700, 1800, 1050, 700},   // one k-major
-                                 {4300, 2700, 1600, 1100, 700}};  // both k-major
+  static const int step[3][5] = {{3230, 2200, 1230, 1000, 560},   // both operands k-contiguous
+                                 {5350, 1900, 1300, 810, 560},    // one k-major
+                                 {3400, 2100, 1220, 750, 560}};   // both k-major
   static const int per_cu[5] = {1, 1, 1, 2, 2};
   const int kind = (a_ks ? 1 : 0) + (b_ks ? 1 : 0);
   const int nk = K / (128 / elem_size);

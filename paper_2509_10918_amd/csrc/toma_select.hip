@@ -30,25 +30,29 @@ constexpr double kSimScale = 4194304.0;
 // LDS and no barrier, two chunks ahead of the products; small independent units spread evenly over
 // the chip's SIMDs, which is what bounds this kernel.  The token norms come out of the same pass
 // (sums of squares of the values a lane holds anyway, combined across the four k-groups).
-template <typename T>
+template <typename T, int KS>
 __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *__restrict__ S, RegionMap map,
                                              int N, int C, int P, int n_loc, int tiles, int units) {
   constexpr int EPP = 16 / (int)sizeof(T);  // elements per 16-byte packet
   constexpr int NPK = 8 / EPP;              // packets per fragment (eight channels)
+  constexpr int UPW = 4 / KS;               // units per workgroup: KS waves share one, each a slice of K
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
-  // one-dimensional grid over (region, group of four units), remapped so that an XCD works on whole
+  // one-dimensional grid over (region, group of UPW units), remapped so that an XCD works on whole
   // regions: their tokens then stay in that XCD's L2
-  const int groups = (units + 3) / 4;
+  const int groups = (units + UPW - 1) / UPW;
   const int work = xcd_remap(blockIdx.x, gridDim.x);
   const int bp = work / groups;
-  const int unit = (work - bp * groups) * 4 + w;
-  if (unit >= units) return;  // whole wave (no barrier below)
+  const int unit_raw = (work - bp * groups) * UPW + w / KS, kh = w % KS;
+  const bool live = unit_raw < units;
+  const int unit = live ? unit_raw : units - 1;
   // unit enumerates the pairs (tm <= tn) row by row
   int tm = 0, rest = unit;
   while (rest >= tiles - tm) { rest -= tiles - tm; tm++; }
   const int tn = tm + rest;
   const int b = bp / P, p = bp % P;
-  const T *Xb = X + (size_t)b * N * C;
+  const int nchunk_all = C / 32;
+  const int c_lo = nchunk_all * kh / KS, nchunk = live ? nchunk_all * (kh + 1) / KS - c_lo : 0;
+  const T *Xb = X + (size_t)b * N * C + 32 * c_lo;
   const T *pa = Xb + (size_t)map.token(p, 16 * tm + c) * C + 8 * g;
   const T *pb = Xb + (size_t)map.token(p, 16 * tn + c) * C + 8 * g;
 
@@ -76,9 +80,8 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
   // two accumulators: consecutive products do not wait for each other
   f64x4 acc = (f64x4){0.0, 0.0, 0.0, 0.0}, acc1 = (f64x4){0.0, 0.0, 0.0, 0.0};
   double sqa = 0.0, sqb = 0.0;
-  const int nchunk = C / 32;
   Chunk c0, c1, c2;
-  fetch(c0, 0);
+  if (nchunk > 0) fetch(c0, 0);
   if (nchunk > 1) fetch(c1, 32);
   for (int i = 0; i < nchunk; i += 3) {
     // three-deep rotation written out so that the buffers stay in registers
@@ -98,6 +101,27 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
     if (i + 2 < nchunk) work(c2, c1, i + 2);
   }
   acc += acc1;
+  if constexpr (KS > 1) {
+    // the waves of a unit add their slices of K up in the first of them
+    __shared__ double part[4][6][64];
+    if (kh != 0) {
+#pragma unroll
+      for (int r = 0; r < 4; r++) part[w][r][lane] = acc[r];
+      part[w][4][lane] = sqa;
+      part[w][5][lane] = sqb;
+    }
+    __syncthreads();
+    if (kh != 0 || !live) return;
+#pragma unroll
+    for (int o = 1; o < KS; o++) {
+#pragma unroll
+      for (int r = 0; r < 4; r++) acc[r] += part[w + o][r][lane];
+      sqa += part[w + o][4][lane];
+      sqb += part[w + o][5][lane];
+    }
+  } else {
+    if (!live) return;
+  }
   // norms of row 16 tm + c and of row 16 tn + c: sum over the four k-groups
   sqa += wave_xor_f64(sqa, 16); sqa += wave_xor_f64(sqa, 32);
   sqb += wave_xor_f64(sqb, 16); sqb += wave_xor_f64(sqb, 32);
@@ -293,6 +317,16 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
   }
 }
 
+// Slices of K per 16 x 16 unit: more, smaller pieces of work spread more evenly over the SIMDs when
+// the units alone are only a few per SIMD; each slice still needs a few chunks to fill its pipeline.
+static int gram_k_split(const Shape &s) {
+  const int tiles = s.n_loc / 16;
+  const long long waves = (long long)tiles * (tiles + 1) / 2 * s.B * s.P;
+  const int nchunk = s.C / 32;
+  if (waves < 8 * 1024 && nchunk >= 8) return 2;
+  return 1;
+}
+
 template <typename T>
 static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, char *ws, const Workspace &w,
                         hipStream_t st) {
@@ -300,8 +334,12 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, c
   RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
   const int tiles = s.n_loc / 16, units = tiles * (tiles + 1) / 2;
   { KernelTimer kt(K_GRAM, st);
-  hipLaunchKernelGGL(k_gram<T>, dim3((units + 3) / 4 * s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
-                     s.n_loc, tiles, units); }
+  if (gram_k_split(s) == 2)
+    hipLaunchKernelGGL((k_gram<T, 2>), dim3((units + 1) / 2 * s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
+                       s.n_loc, tiles, units);
+  else
+    hipLaunchKernelGGL((k_gram<T, 1>), dim3((units + 3) / 4 * s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
+                       s.n_loc, tiles, units); }
   int regions = s.B * s.P;
   KernelTimer kt(K_GREEDY, st);
   switch (s.n_loc / 16) {
