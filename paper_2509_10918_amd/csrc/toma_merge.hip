@@ -207,7 +207,6 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
   constexpr int STAGE = JS * 16 * EPS;                 // elements per stage
   __shared__ __align__(1024) T Bs[8][RS][2 * 16 * EPS];  // per wave ring (sized for two tiles per stage)
   __shared__ __align__(1024) T As[2][32 * EPS];          // the step's 32 source rows, double buffered
-  __shared__ int boff[8][NJ][16];    // element offset of destination row (wave, tile j, row) inside the sample
   __shared__ float red[8][32];       // per wave partial statistic of the 32 source rows
   __shared__ float rowstat[32];
 
@@ -215,30 +214,36 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
   const int z = blockIdx.y, b = z / v.R, rho = z % v.R;
   const int m0 = blockIdx.x * 32;
   const T *Xb = v.X + (size_t)b * v.N * v.C;
-  for (int e = tid; e < 8 * 16 * NJ; e += 512) {
-    const int ww = e / (16 * NJ), jj = (e / 16) % NJ, rr = e % 16;
-    int t = idx[(size_t)b * v.D + rho * v.Dr + ww * 16 * NJ + 16 * jj + rr];
-    t = t < 0 ? 0 : (t >= v.N ? v.N - 1 : t);
-    boff[ww][jj][rr] = t * v.C;
-  }
-  __syncthreads();
 
   // what this lane fetches of a 1 KiB chunk (8 rows x 128 bytes): row lane / 8, and the packet that
   // the swizzle places at position lane % 8 of that row
   const int l_row = lane >> 3;
   const int l_pkt = ((lane & 7) ^ (l_row & 7)) * EPP;
+  // Element offsets (inside the sample) of the packets this lane fetches of its wave's destination
+  // rows, one per (stage of a K step, chunk): the same for every K step, so they stay in registers.
+  int roff[SPS][LPS];
+#pragma unroll
+  for (int q = 0; q < SPS; q++)
+#pragma unroll
+    for (int ch = 0; ch < LPS; ch++) {
+      int t = idx[(size_t)b * v.D + rho * v.Dr + w * 16 * NJ + 16 * (q * JS + (ch >> 1)) + 8 * (ch & 1) + l_row];
+      t = t < 0 ? 0 : (t >= v.N ? v.N - 1 : t);
+      roff[q][ch] = t * v.C + l_pkt;
+    }
   // source rows: wave w < 4 fetches rows 8 w .. 8 w + 7 of every step
   const T *a_src = Xb + (size_t)v.token(rho, m0 + 8 * (w & 3) + l_row) * v.C + l_pkt;
   const int nsteps = v.C / EPS, U = nsteps * SPS;
-  auto issue_a = [&](int s) { load_to_lds16(a_src + s * EPS, As[s & 1] + (w & 3) * (1024 / ES)); };
-  auto issue_b = [&](int u) {
-    const int s = u / SPS, q = u - s * SPS;
-    T *dst = Bs[w][u & (RS - 1)];
+  // LDS byte addresses (scalar registers) of this wave's ring and of its part of the source rows
+  const uint32_t w_s = (uint32_t)__builtin_amdgcn_readfirstlane(w);
+  const uint32_t bs_lds = lds_addr_of(&Bs[0][0][0]) + w_s * (RS * 2 * 16 * EPS * ES);
+  const uint32_t as_lds = lds_addr_of(&As[0][0]) + (w_s & 3) * 1024;
+  auto issue_a = [&](int s) { load_to_lds16_at(a_src + s * EPS, as_lds + (uint32_t)(s & 1) * (32 * EPS * ES)); };
+  // stage u = s * SPS + q of the ring (q is a compile-time constant at every call)
+  auto issue_b = [&](int s, int q) {
+    const uint32_t dst = bs_lds + (uint32_t)((s * SPS + q) & (RS - 1)) * (2 * 16 * EPS * ES);
+    const T *src = Xb + s * EPS;
 #pragma unroll
-    for (int ch = 0; ch < LPS; ch++) {
-      const int row_off = boff[w][q * JS + (ch >> 1)][8 * (ch & 1) + l_row];
-      load_to_lds16(Xb + row_off + s * EPS + l_pkt, dst + ch * (1024 / ES));
-    }
+    for (int ch = 0; ch < LPS; ch++) load_to_lds16_at(src + roff[q][ch], dst + ch * 1024);
   };
   auto fence = [&]() { asm volatile("" ::: "memory"); };
 
@@ -248,13 +253,13 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
 #pragma unroll
     for (int j = 0; j < NJ; j++) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // the offset reads above are LDS reads: they must have returned before M0-based loads reuse the
-  // registers (the compiler's own waits cover them); from here on vmcnt counts only ring loads
+  // the index loads above have returned (their values were used): from here on vmcnt counts
+  // only ring loads
   wait_vmcnt<0>();
   if (w < 4) issue_a(0);
 #pragma unroll
   for (int u = 0; u < RS - 1; u++)
-    if (u < U) issue_b(u);
+    if (u < U) issue_b(u / SPS, u % SPS);
   wait_vmcnt<0>();
   fence();
   __builtin_amdgcn_s_barrier();
@@ -270,7 +275,7 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
 #pragma unroll
     for (int q = 0; q < SPS; q++) {
       const int u = s * SPS + q;
-      if (u + RS - 1 < U) issue_b(u + RS - 1);
+      if (u + RS - 1 < U) issue_b(s + (q + RS - 1) / SPS, (q + RS - 1) % SPS);
       // this wave's loads of stage u are the oldest outstanding ones
       const int younger = min(U - 1 - u, RS - 1);
       if (younger >= 3) wait_vmcnt<3 * LPS>();
