@@ -216,6 +216,38 @@ def test_attention_shapes_and_output_projection(oracle, dtype, heads, C, L, T):
     _check_stage("O Wo", O2, oracle.attend(_f64(Xm), Xe, *Wts, heads=heads, Wo=_f64(Wo)), tg.TOL[dtype])
 
 
+@pytest.mark.parametrize("dtype,head_dim,order", [("bf16", 64, "up"), ("bf16", 64, "down"), ("bf16", 128, "up"),
+                                                  ("f32", 64, "up")])
+def test_attention_with_drifting_maxima(oracle, dtype, head_dim, order):
+    """Scores whose row maxima keep growing along the keys, slowly for some queries and fast for
+    others of the same wave (or are largest at the first keys): the streaming softmax has to move
+    its reference point per row and rescale what it has accumulated, over 16 key tiles."""
+    print(f"[attend drift] {dtype} head_dim={head_dim} {order}", flush=True)
+    rng = np.random.default_rng(9)
+    C, D, T = head_dim, 256, 768
+    w = synth.scaled(W["tiny"], name="drift", dtype=dtype, B=1, H=16, W=16, C=C, tile_h=16, tile_w=16,
+                     keep=1.0, heads=1, T_extra=T, index=14)
+    assert w.D == D
+    inp = synth.make_inputs(w)
+    dv = tg.Device(w, inp, 1)
+    L = D + T
+    # token j = a_j e_0 + noise with a_j rising from 1 to about 45: with W_q = W_k = I the score of
+    # (i, j) is about a_i a_j, so the maximum of row i grows by about 2.8 a_i per tile of 64 keys
+    a = 1.0 + 0.043 * np.arange(L)
+    if order == "down":
+        a = a[::-1].copy()
+    U = 0.05 * rng.standard_normal((1, L, C))
+    U[0, :, 0] += a
+    U = synth.quantize(w, U.astype(np.float32))
+    eye = np.eye(C, dtype=np.float32)
+    Wv = synth.quantize(w, (rng.standard_normal((C, C)) / np.sqrt(C)).astype(np.float32))
+    dv.Wq.copy_(tg.dev(eye, dtype)); dv.Wk.copy_(tg.dev(eye, dtype)); dv.Wv.copy_(tg.dev(Wv, dtype))
+    dv.Xe.copy_(tg.dev(U[:, D:], dtype))
+    O = dv.attend(Xm=U[:, :D])
+    ref = oracle.attend(_f64(U[:, :D]), _f64(U[:, D:]), _f64(eye), _f64(eye), _f64(Wv), heads=1)
+    _check_stage("O", O, ref, tg.TOL[dtype])
+
+
 @pytest.mark.parametrize("dtype,rows,C,hidden", [("f32", 200, 64, 256), ("bf16", 1000, 128, 512),
                                                   ("bf16", 333, 96, 160), ("bf16", 2 * 2048, 640, 2560)])
 def test_mlp_module(oracle, dtype, rows, C, hidden):
