@@ -389,6 +389,10 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   // fixed offsets off a few per-lane bases instead of being recomputed every step.  (The
   // 256 x 256 tile has no registers to spare for per-stage bases and keeps a rolled loop.)
   constexpr bool kUnroll = BM * BN <= 256 * 128;
+  // Reading the fragments one sub-step ahead needs a second set of fragment registers.  The largest
+  // tile cannot afford them when exactly one operand is k-major (measured: the spills cost more than
+  // the exposed LDS latency, which the SIMD's other wave covers).
+  constexpr bool kPipelineFrags = kUnroll || Pol::A_KS == Pol::B_KS;
   const uint32_t w_s = (uint32_t)__builtin_amdgcn_readfirstlane(w);
   const uint32_t a_lds = lds_addr_of(&As[0][0]) + w_s * (NIA * 1024);
   const uint32_t b_lds = lds_addr_of(&Bs[0][0]) + w_s * (NIB * 1024);
@@ -472,7 +476,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   for (int s = 0; s < STAGES - 1; s++)
     if (s < nk) issue(s, s);
 
-  if constexpr (G::KSUB == 2) {
+  if constexpr (G::KSUB == 2 && kPipelineFrags) {
     Frag<T> fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     wait_stage(0);
     meet();

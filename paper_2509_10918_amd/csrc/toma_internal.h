@@ -46,7 +46,7 @@ inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, b
                                 int epi) {
   static const int bm[5] = {256, 256, 128, 128, 64}, bn[5] = {256, 128, 128, 64, 64};
   static const int step[3][5] = {{3230, 2200, 1230, 1000, 560},   // both operands k-contiguous
-                                 {5350, 1900, 1300, 810, 560},    // one k-major
+                                 {3700, 1900, 1300, 810, 560},    // one k-major
                                  {3400, 2100, 1220, 750, 560}};   // both k-major
   static const int per_cu[5] = {1, 1, 1, 2, 2};
   const int kind = (a_ks ? 1 : 0) + (b_ks ? 1 : 0);
