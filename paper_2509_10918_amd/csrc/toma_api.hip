@@ -49,7 +49,7 @@ void plan_workspace(const Shape &s, Workspace *w) {
   auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
   // row strides of the partial-result arrays: one entry per wave slice of the weights product
   // (sources x destinations x C), whose block tile is planned here exactly as at launch
-  if (weights_fused_fits(s.Nr, s.Dr, s.C, (int)es)) {
+  if (weights_single_pass(s.Nr, s.Dr, s.C, s.B * s.R, (int)es)) {
     w->stat_parts = 1;           // (unused by the single-pass kernel)
     w->z_parts = s.Nr / 32;      // one partial row sum per 32-source workgroup
   } else if (gemm_async_fits(s.Nr, s.Dr, s.C, (int)es)) {

@@ -34,7 +34,7 @@ inline bool gemm_async_fits(int M, int N, int K, int elem_size) {
   const int bk = 128 / elem_size, epp = 16 / elem_size;
   return K % bk == 0 && M >= epp && N >= epp;
 }
-struct GemmPlan { int bm, bn, nsplit; };
+struct GemmPlan { int bm, bn, nsplit; double cost; };  // cost: estimated shader clocks
 // Cost model in shader clocks, fitted to measurements of the kernel on MI355X (sweeps of every tile
 // and split on the SDXL-sized products): a K step of a workgroup costs about step[][] (it depends on
 // which operands are k-major: their fragment reads go through the LDS transpose path), a workgroup
@@ -51,7 +51,7 @@ inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, b
   static const int per_cu[5] = {1, 1, 1, 2, 2};
   const int kind = (a_ks ? 1 : 0) + (b_ks ? 1 : 0);
   const int nk = K / (128 / elem_size);
-  GemmPlan best{128, 128, 1};
+  GemmPlan best{128, 128, 1, 0.0};
   double best_cost = -1.0;
   for (int i = 0; i < 5; i++) {
     const long long tiles = (long long)((M + bm[i] - 1) / bm[i]) * ((N + bn[i] - 1) / bn[i]) * batch;
@@ -63,7 +63,7 @@ inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, b
       const long long share = std::min<long long>(per_cu[i], (blocks + 255) / 256);  // workgroups sharing a CU
       double cost = rounds * (((nk + ns - 1) / ns) * (double)step[kind][i] * share + fixed);
       if (ns > 1) cost += 8000.0 + (4.0 * ns + elem_size) * (double)M * N * batch / 1500.0;
-      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = GemmPlan{bm[i], bn[i], ns}; }
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = GemmPlan{bm[i], bn[i], ns, cost}; }
     }
   }
   return best;
@@ -76,6 +76,22 @@ inline bool weights_fused_fits(int Nr, int Dr, int C, int elem_size) {
   const int nj = Dr / 128;
   return Dr % 128 == 0 && (nj == 1 || nj == 2 || nj == 4 || nj == 8 || nj == 16) && Nr % 32 == 0 &&
          (C * elem_size) % 128 == 0;
+}
+
+// Single pass or two passes for the merge weights?  The single-pass kernel streams every destination
+// row through each of its workgroups: about 4 clocks per destination row and K step (measured: it is
+// bound by what one CU can pull in), in rounds of one workgroup per CU, plus a fixed part.  The two
+// passes cost two planned products plus the small kernel between them.  Few, long rows (a Flux
+// block: 1024 destinations, 48 K steps, 128 workgroups) favour the two passes; many destinations
+// with a short K favour the single pass.
+inline bool weights_single_pass(int Nr, int Dr, int C, int batch, int elem_size) {
+  if (!weights_fused_fits(Nr, Dr, C, elem_size)) return false;
+  if (!gemm_async_fits(Nr, Dr, C, elem_size)) return true;
+  const long long wgs = (long long)(Nr / 32) * batch;
+  const double rounds = (double)((wgs + 255) / 256);
+  const double single = 19000.0 + rounds * (C * elem_size / 128) * Dr * 4.0;
+  const double two = 2.0 * plan_gemm_async(Nr, Dr, C, batch, elem_size, false, false, false, 3).cost + 14000.0;
+  return single <= two;
 }
 
 int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s);

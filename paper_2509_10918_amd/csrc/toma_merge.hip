@@ -492,7 +492,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   int batch = s.B * s.R;
   const int zr = s.B * s.D;
   float *zpart = reinterpret_cast<float *>(ws + w.zpart);
-  if (weights_fused_fits(s.Nr, s.Dr, s.C, (int)sizeof(T))) {
+  if (weights_single_pass(s.Nr, s.Dr, s.C, batch, (int)sizeof(T))) {
     const RegionView<T> v = make_view<T>(s, X);
     const dim3 grid(s.Nr / 32, batch);
     {

@@ -117,22 +117,24 @@ def test_stages_isolated(oracle, cases, name, tile_local):
     _check_stage("Y (oracle weights)", Y, Y_ref2, tol)
 
 
-@pytest.mark.parametrize("dtype,grid,tile,keep,C", [
-    ("bf16", (16, 16), (8, 8), 0.5, 64),      # 128 destinations: one 128-wide slice per workgroup
-    ("f32", (32, 16), (8, 8), 0.5, 32),       # 256 destinations
-    ("bf16", (32, 32), (8, 8), 0.5, 128),     # 512 destinations
-    ("bf16", (32, 64), (16, 16), 0.5, 64),    # 1024 destinations
-    ("f32", (64, 64), (16, 16), 0.5, 32),     # 2048 destinations: the largest single-pass case
-    ("bf16", (32, 48), (8, 8), 0.5, 64),      # 768 destinations: not a single-pass size, two-pass path
-    ("bf16", (16, 16), (8, 8), 0.25, 64),     # 64 destinations: two-pass path
+@pytest.mark.parametrize("dtype,grid,tile,keep,C,passes", [
+    ("bf16", (16, 16), (8, 8), 0.5, 64, 1),      # 128 destinations: one 128-wide slice per workgroup
+    ("f32", (32, 16), (8, 8), 0.5, 32, 1),       # 256 destinations
+    ("bf16", (32, 32), (8, 8), 0.5, 128, 1),     # 512 destinations
+    ("bf16", (32, 64), (16, 16), 0.5, 64, 1),    # 1024 destinations
+    ("f32", (64, 64), (16, 16), 0.5, 32, 1),     # 2048 destinations: the largest single-pass case
+    ("bf16", (32, 48), (8, 8), 0.5, 64, 2),      # 768 destinations: not a single-pass size
+    ("bf16", (16, 16), (8, 8), 0.25, 64, 2),     # 64 destinations: not a single-pass size
+    ("bf16", (32, 64), (16, 16), 0.5, 1024, 2),  # 1024 destinations, 16 K steps, 128 workgroups: two passes are cheaper
 ])
-def test_merge_weights_region_sizes(oracle, dtype, grid, tile, keep, C):
-    """Global merge weights over every destination count the single-pass kernel is instantiated for
-    (and sizes it does not take), against the oracle's A / Z, Z and merged tokens."""
+def test_merge_weights_region_sizes(oracle, dtype, grid, tile, keep, C, passes):
+    """Global merge weights over every destination count the single-pass kernel is instantiated for,
+    sizes it does not take and a shape where two passes are cheaper, against the oracle's A / Z, Z
+    and merged tokens; the profiling aid says which path ran."""
     H, Wd = grid
     th, tw = tile
     w = synth.scaled(W["tiny"], name="wsize", dtype=dtype, B=2, H=H, W=Wd, C=C, tile_h=th, tile_w=tw, keep=keep,
-                     heads=1, index=13)
+                     heads=max(1, C // 128), index=13)
     print(f"[weights sizes] {dtype} grid {H}x{Wd} tile {th}x{tw} D={w.D} C={C}", flush=True)
     inp = synth.make_inputs(w)
     tol = tg.TOL[dtype]
@@ -142,7 +144,14 @@ def test_merge_weights_region_sizes(oracle, dtype, grid, tile, keep, C):
     A_ref, Z_ref, _ = oracle.merge_weights(d, X, idx)
     Xm_ref = oracle.merge(d, X, A_ref, Z_ref)
     dv = tg.Device(w, inp, 1)
-    A, Z, Xm = dv.merge(idx=idx)
+    tb.toma_profile_enable(True)
+    try:
+        tb.toma_profile_read("weights_stats")
+        A, Z, Xm = dv.merge(idx=idx)
+        stats_launches, _ = tb.toma_profile_read("weights_stats")
+    finally:
+        tb.toma_profile_enable(False)
+    assert stats_launches == (1 if passes == 2 else 0)
     At_ref = A_ref / np.maximum(Z_ref, 1e-20).reshape(w.B, 1, -1, 1)
     At = A / np.maximum(Z, 1e-20).reshape(w.B, 1, -1, 1)
     _check_stage("A~", At, At_ref, tol)
