@@ -48,6 +48,7 @@ def kernel_work(w, R, esize):
         "copy_extra": ("hbm", 2 * w.B * w.T_extra * w.C * esize),
         # second pass of a K-split merge / unmerge product: at least two fp32 partials in, one tile out
         "split_finish": ("hbm", w.B * w.D * w.C * (2 * 4 + esize)),
+        "occupancy": ("hbm", a_bytes),   # one read of the stored weights
         "_a_bytes": ("hbm", a_bytes),
     }
 
@@ -178,6 +179,10 @@ def main():
         "gram": "achieved counts the full N_loc x N_loc product; the kernel executes the blocks on and above the "
                 "diagonal only (53% of it at N_loc = 256); a bare fp64 MFMA loop measures 43-47 TFLOP/s on this part",
     }
+    if "occupancy" in per_kernel:
+        sparse = ("achieved counts the dense product; K steps whose blocks of the stored weights are all zero (the "
+                  "occupancy map) are skipped, so the figure can exceed what the matrix cores could do densely")
+        notes["merge"] = notes["unmerge"] = sparse
     for name, rec in per_kernel.items():
         if name in notes:
             rec["note"] = notes[name]

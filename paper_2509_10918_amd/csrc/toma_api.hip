@@ -80,6 +80,14 @@ void plan_workspace(const Shape &s, Workspace *w) {
     if (pu.nsplit > 1) part = std::max(part, (size_t)pu.nsplit * s.B * s.N * s.C * sizeof(float));
   }
   w->split = take(part);
+  if (occupancy_pays(s.Nr, s.Dr, s.C, (int)es)) {
+    w->occ_db = (s.Dr + kOccDest - 1) / kOccDest;
+    w->occ_sb = s.Nr / kOccSrc;
+    w->occ = take((size_t)s.B * s.R * w->occ_db * w->occ_sb);
+  } else {
+    w->occ_db = w->occ_sb = 0;
+    w->occ = off;
+  }
   w->total = off;
 }
 
@@ -154,6 +162,8 @@ TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void 
   if (rc != TOMA_OK) return rc;
   if (!X || !A || !Z || !Xm) return TOMA_ERR_NULL;
   if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Xm, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
+  rc = launch_occupancy(s, A, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+  if (rc != TOMA_OK) return rc;
   return launch_merge(s, X, A, Z, Xm, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
 }
 
@@ -181,6 +191,8 @@ TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, 
   if (!A || !Z || !O || !Y) return TOMA_ERR_NULL;
   if (o_rows < s.D) return TOMA_ERR_SHAPE;
   if (misaligned(A, 16) || misaligned(O, 16) || misaligned(Y, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
+  rc = launch_occupancy(s, A, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+  if (rc != TOMA_OK) return rc;
   return launch_unmerge(s, A, Z, O, o_rows, false, Y, static_cast<char *>(ws), w,
                         static_cast<hipStream_t>(stream));
 }
@@ -214,8 +226,12 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
   }
   if (!reuse_a) {
     rc = launch_weights(s, X, idx, A, Z, wsb, w, st);
-    if (rc != TOMA_OK) return rc;
+  } else {
+    // the occupancy map of a cached A is rebuilt in every call: the workspace is scratch, only
+    // idx, A and Z persist
+    rc = launch_occupancy(s, A, wsb, w, st);
   }
+  if (rc != TOMA_OK) return rc;
   rc = launch_merge(s, X, A, Z, Xm, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   // inside the layer the attention writes its merged rows already divided by Z (the unmerge's

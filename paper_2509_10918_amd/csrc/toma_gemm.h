@@ -40,12 +40,19 @@
 // The policy itself is never written to, so it stays in the kernel-argument segment.
 // Extents along a packet's direction must be multiples of the packet length (8 bf16 / 4 fp32).
 #pragma once
+#include <type_traits>
+
 #include "toma_common.h"
 #include "toma_internal.h"
 
 namespace toma {
 
 struct GemmCtx { int M, N, K, b, rho, z, split; };
+
+// A policy may declare SPARSE_K = true and supply k_list() / k_active(): the kernel then runs only
+// the K steps the policy calls active (see k_gemm_async).
+template <typename P, typename = void> struct PolSparseK { static constexpr bool value = false; };
+template <typename P> struct PolSparseK<P, std::void_t<decltype(P::SPARSE_K)>> { static constexpr bool value = P::SPARSE_K; };
 
 template <typename T, int BM, int BN> struct GemmTile {
   static constexpr int ES = (int)sizeof(T);
@@ -339,7 +346,52 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   // this workgroup's share of the K steps
   const int nk_all = ctx.K / G::BK;
   const int kt0 = (int)((long long)nk_all * split / nsplit), kt1 = (int)((long long)nk_all * (split + 1) / nsplit);
-  const int nk = kt1 - kt0, kbase = kt0 * G::BK;
+  int nk = kt1 - kt0;
+  const int kbase = kt0 * G::BK;
+
+  // Sparse K: wave 0 asks the policy about every K step of this workgroup's range and compacts the
+  // active ones into a list; the pipeline below then walks the list instead of the range.  Each
+  // wave keeps the current 64 entries of the list in one register (entry i in lane i % 64).
+  constexpr bool kSparse = PolSparseK<Pol>::value;
+  constexpr int kMaxList = kSparse ? 1024 : 1;
+  __shared__ uint16_t klist[kMaxList];
+  __shared__ int klist_n;
+  bool listed = false;
+  if constexpr (kSparse) {
+    if (pol.k_list() && nk <= kMaxList) {
+      if (w == 0) {
+        int count = 0;
+        for (int c0 = 0; c0 < nk; c0 += 64) {
+          const int kt = c0 + lane;
+          const bool act = kt < nk && pol.k_active(ctx, m0, BM, kbase + kt * G::BK, G::BK);
+          const uint64_t mask = __ballot(act);
+          if (act) klist[count + __popcll(mask & ((1ull << lane) - 1ull))] = (uint16_t)kt;
+          count += __popcll(mask);
+        }
+        if (lane == 0) klist_n = count;
+      }
+      __syncthreads();
+      nk = klist_n;
+      listed = true;
+    }
+  }
+  uint32_t kreg = 0;  // list entries 64 c + lane of the chunk c the issue index is in
+  auto list_chunk = [&](int j) {
+    if constexpr (kSparse) {
+      if (listed) { const int e = (j & ~63) + lane; kreg = e < nk ? klist[e] : 0; }
+    }
+  };
+  // K step that issue index j stands for
+  auto step_of = [&](int j) -> int {
+    if constexpr (kSparse) {
+      if (listed) {
+        if ((j & 63) == 0 && j > 0) list_chunk(j);
+        return __builtin_amdgcn_readlane((int)kreg, j & 63);
+      }
+    }
+    return j;
+  };
+  list_chunk(0);
 
   // what this lane fetches for chunk `ch` (1 KiB = 64 packets) of a tile: tile coordinates
   int a_i[NIA], a_k[NIA], b_i[NIB], b_k[NIB];
@@ -396,7 +448,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   const uint32_t w_s = (uint32_t)__builtin_amdgcn_readfirstlane(w);
   const uint32_t a_lds = lds_addr_of(&As[0][0]) + w_s * (NIA * 1024);
   const uint32_t b_lds = lds_addr_of(&Bs[0][0]) + w_s * (NIB * 1024);
-  auto issue = [&](int st, int kt) {
+  auto issue = [&](int st, int j) {
+    const int kt = step_of(j);
     const int k0 = kbase + kt * G::BK;
     const uint32_t a_st = a_lds + (uint32_t)st * (A_ELEMS * G::ES), b_st = b_lds + (uint32_t)st * (B_ELEMS * G::ES);
 #pragma unroll
@@ -600,7 +653,13 @@ template <typename T, typename Pol>
 inline GemmShape launch_gemm(int kernel_id, const Pol &pol, int M, int N, int K, int batch, hipStream_t st) {
   if (gemm_async_fits(M, N, K, (int)sizeof(T))) {
     // load-to-LDS pipeline
-    const GemmPlan pl = plan_gemm_async(M, N, K, batch, (int)sizeof(T), Pol::SPLIT_K, Pol::A_KS, Pol::B_KS, Pol::EPI);
+    // With a K list the work per workgroup is not known here: splitting K then mostly splits the
+    // empty steps, so K stays whole unless the tiles alone cannot occupy the chip.
+    bool may_split = Pol::SPLIT_K;
+    if constexpr (PolSparseK<Pol>::value) {
+      if (pol.k_list() && (long long)((M + 127) / 128) * ((N + 127) / 128) * batch >= 128) may_split = false;
+    }
+    const GemmPlan pl = plan_gemm_async(M, N, K, batch, (int)sizeof(T), may_split, Pol::A_KS, Pol::B_KS, Pol::EPI);
     const GemmShape g{pl.bm, pl.bn, 4, 2, (M + pl.bm - 1) / pl.bm, (N + pl.bn - 1) / pl.bn, pl.nsplit};
     const dim3 grid(g.tiles_m * g.tiles_n * batch * g.nsplit);
     {

@@ -21,9 +21,24 @@ struct Shape {
 
 // Offsets (bytes) of the scratch sections inside the caller's workspace.
 struct Workspace {
-  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, total;
+  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, occ, total;
   int stat_parts, z_parts;
+  int occ_db, occ_sb;  // occupancy map of A: blocks of kOccDest destinations x kOccSrc sources (0: not used)
 };
+
+// Occupancy map of the stored merge weights.  With a small temperature almost every source token
+// puts all of its weight on one or two destinations and the rest of its column of A rounds to an
+// exact zero: the merge and unmerge products then multiply blocks of zeros.  A byte per
+// (kOccDest destinations x kOccSrc sources) block of A says whether the block holds any nonzero
+// value; the two products skip the K steps whose blocks are all empty, which changes no result
+// (finite inputs) and costs one read of A.  Worth it when the products are long enough.
+constexpr int kOccDest = 128, kOccSrc = 32;
+inline bool occupancy_pays(int Nr, int Dr, int C, int elem_size) {
+  // long products only (the map costs a kernel of its own unless the single-pass weights kernel
+  // writes it); a K list holds at most 1024 steps
+  return Nr >= 2048 && Dr >= 1024 && Nr % kOccSrc == 0 && Dr % kOccDest == 0 && (C * elem_size) % 128 == 0 &&
+         Nr / (128 / elem_size) <= 1024 && Dr / (128 / elem_size) <= 1024;
+}
 
 constexpr int kGemmMinSlice = 16;  // narrowest wave slice of a GEMM block tile (rows or columns)
 
@@ -100,8 +115,12 @@ void plan_workspace(const Shape &s, Workspace *w);
 // stage launchers (each returns a toma_status)
 int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, char *ws, const Workspace &w,
                   hipStream_t st);
+// (also leaves the occupancy map of the new A in the workspace, see launch_occupancy)
 int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, char *ws,
                    const Workspace &w, hipStream_t st);
+// fills the occupancy map of A in the workspace (no-op when the shape does not use one); this or
+// launch_weights must run, in the same call, before launch_merge / launch_unmerge
+int launch_occupancy(const Shape &s, const void *A, char *ws, const Workspace &w, hipStream_t st);
 int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, char *ws,
                  const Workspace &w, hipStream_t st);
 // Zs (optional): divide the merged rows of O by max(Z, 1e-20) on the way out (the unmerge input)
@@ -118,7 +137,7 @@ int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const voi
 
 // Kernel identifiers of the profiling aid (toma_profile_*): one per kernel of the path.
 enum KernelId { K_GRAM = 0, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
-                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_COUNT };
+                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_COUNT };
 
 // Brackets one launch with HIP events on its stream while profiling is enabled; free otherwise.
 struct KernelTimer {

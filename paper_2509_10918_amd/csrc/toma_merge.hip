@@ -44,6 +44,8 @@ template <typename T, bool WRITE> struct WeightsPol {
   int lda;
   float *zpart;      // pass 2 out: [B*R][Dr][zparts]
   int zparts;
+  uint8_t *occ;      // pass 2 out (optional): occupancy map of A, zeroed before the launch
+  int occ_db, occ_sb;
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Nr, v.Dr, v.C, bz / v.R, bz % v.R, bz};
   }
@@ -90,6 +92,12 @@ template <typename T, bool WRITE> struct WeightsPol {
       float colsum[TN];
 #pragma unroll
       for (int j = 0; j < TN; j++) colsum[j] = 0.f;
+      // occupancy: a wave's tile lies inside one block of destinations and covers one or two
+      // blocks of sources
+      constexpr int kSrcBlocks = 16 * TM > kOccSrc ? 16 * TM / kOccSrc : 1;
+      bool nonzero[kSrcBlocks];
+#pragma unroll
+      for (int h = 0; h < kSrcBlocks; h++) nonzero[h] = false;
 #pragma unroll
       for (int i = 0; i < TM; i++) {
         int mb = m_w + 16 * i + 4 * g;  // four consecutive sources mb .. mb+3 (M is a multiple of 16)
@@ -105,7 +113,9 @@ template <typename T, bool WRITE> struct WeightsPol {
 #pragma unroll
           for (int r = 0; r < 4; r++) {
             o[r] = from_f32<T>(__expf(acc.t[i][j][r] * scale - l4[r]));
-            colsum[j] += to_f32(o[r]);
+            const float stored = to_f32(o[r]);
+            colsum[j] += stored;
+            nonzero[16 * i / kOccSrc % kSrcBlocks] |= stored != 0.f;
           }
           // straight to memory (8 / 16 bytes per lane), or into this wave's LDS scratch: row = the
           // destination, 16-byte chunk u of a row at position u ^ (row & 7)
@@ -140,6 +150,16 @@ template <typename T, bool WRITE> struct WeightsPol {
           if (n < N && m < M) *reinterpret_cast<u32x4 *>(A + ((size_t)z * N + n) * lda + m) = pk;
         }
       }
+      if (occ) {
+        // every wave that found a nonzero value stores a one (the map starts at zero; several
+        // waves may store the same one)
+#pragma unroll
+        for (int h = 0; h < kSrcBlocks; h++) {
+          const int sblk = m_w / kOccSrc + h, dblk = n_w / kOccDest;
+          if (__any(nonzero[h]) && lane == 0 && sblk < occ_sb && dblk < occ_db)
+            occ[((size_t)z * occ_db + dblk) * occ_sb + sblk] = 1;
+        }
+      }
       const int part = m_w / (16 * TM);
 #pragma unroll
       for (int j = 0; j < TN; j++) {
@@ -155,8 +175,11 @@ template <typename T, bool WRITE> struct WeightsPol {
 
 // lse[row] = M + log(sum_i s_i exp(m_i - M)) over the row's partial (max, sum) pairs.  One 16-lane
 // group per row, partials strided over its lanes; the combination order is fixed.
+// On the side it zeroes `zero_words` 32-bit words at `zero` (the occupancy map the write pass that
+// follows fills with ones), so that this needs no launch of its own.
 __global__ __launch_bounds__(256) void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse, int rows,
-                                            int stride, int parts) {
+                                            int stride, int parts, uint32_t *__restrict__ zero, size_t zero_words) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < zero_words; i += (size_t)gridDim.x * 256) zero[i] = 0;
   int row = (blockIdx.x * 256 + threadIdx.x) >> 4, c = threadIdx.x & 15;
   if (row >= rows) return;
   const float2 *s = stats + (size_t)row * stride;
@@ -196,7 +219,7 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
 template <typename T, int NJ>
 __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, const int32_t *__restrict__ idx, float scale,
                                                      T *__restrict__ A, int lda, float *__restrict__ zpart,
-                                                     int zparts) {
+                                                     int zparts, uint8_t *__restrict__ occ, int occ_db, int occ_sb) {
   constexpr int ES = (int)sizeof(T), EPS = 128 / ES;   // elements per K step
   constexpr int EPP = 16 / ES;
   constexpr int NH = ES == 2 ? 2 : 1;                  // fragments per row per K step
@@ -356,6 +379,12 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
   for (int i = 0; i < 2; i++)
 #pragma unroll
     for (int r = 0; r < 4; r++) l4[i][r] = rowstat[16 * i + 4 * g + r];
+  // occupancy of this wave's block(s) of A (kOccDest destinations x the workgroup's kOccSrc sources):
+  // any stored value that is not zero?  (occ is only passed when a wave's slice is whole blocks)
+  constexpr int kBlocks = 16 * NJ >= kOccDest ? 16 * NJ / kOccDest : 1;
+  bool nonzero[kBlocks];
+#pragma unroll
+  for (int h = 0; h < kBlocks; h++) nonzero[h] = false;
 #pragma unroll
   for (int j = 0; j < NJ; j++) {
     const int n = w * 16 * NJ + 16 * j + c;
@@ -366,7 +395,9 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
 #pragma unroll
       for (int r = 0; r < 4; r++) {
         o[r] = from_f32<T>(__expf(acc[i][j][r] - l4[i][r]));
-        colsum += to_f32(o[r]);
+        const float stored = to_f32(o[r]);
+        colsum += stored;
+        nonzero[16 * j / kOccDest % kBlocks] |= stored != 0.f;
       }
       T *dst = A + ((size_t)z * v.Dr + n) * lda + m0 + 16 * i + 4 * g;
       if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
@@ -376,13 +407,43 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
     colsum += wave_xor_f32(colsum, 32);
     if (g == 0) zpart[((size_t)z * v.Dr + n) * zparts + blockIdx.x] = colsum;
   }
+  if (occ) {
+    static_assert(kOccSrc == 32, "one source block per workgroup");
+#pragma unroll
+    for (int h = 0; h < kBlocks; h++) {
+      const bool any = __any(nonzero[h]);
+      if (lane == 0) occ[((size_t)z * occ_db + w * kBlocks + h) * occ_sb + blockIdx.x] = any ? 1 : 0;
+    }
+  }
 }
 
 // ---- merge -------------------------------------------------------------------------------------
+// Occupancy map of A as the two products read it: [region][destination block][source block] bytes.
+struct OccMap {
+  const uint8_t *map;  // null: every block counts as occupied
+  int db, sb;          // blocks per region
+  // any nonzero block among destinations [j0, j1) x sources [k0, k1) of region z?
+  __device__ __forceinline__ bool any(int z, int j0, int j1, int k0, int k1) const {
+    const int d0 = j0 / kOccDest, d1 = min((j1 - 1) / kOccDest, db - 1);
+    const int s0 = k0 / kOccSrc, s1 = min((k1 - 1) / kOccSrc, sb - 1);
+    const uint8_t *row = map + ((size_t)z * db + d0) * sb;
+    uint32_t acc = 0;
+    for (int d = d0; d <= d1; d++, row += sb)
+      for (int q = s0; q <= s1; q++) acc |= row[q];
+    return acc != 0;
+  }
+};
+
 template <typename T> struct MergePol {
-  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true;
+  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true, SPARSE_K = true;
   static constexpr int EPI = 1;
   static constexpr bool EPI_LDS = false;
+  OccMap occ;
+  __host__ __device__ __forceinline__ bool k_list() const { return occ.map != nullptr; }
+  // K runs over the sources, M over the destinations
+  __device__ __forceinline__ bool k_active(const GemmCtx &x, int m0, int bm, int k0, int bk) const {
+    return occ.any(x.z, m0, min(m0 + bm, x.M), k0, min(k0 + bk, x.K));
+  }
   RegionView<T> v;
   const T *A;  // [B*R][Dr][lda]
   int lda;
@@ -419,9 +480,15 @@ template <typename T> struct MergePol {
 
 // ---- unmerge -----------------------------------------------------------------------------------
 template <typename T> struct UnmergePol {
-  static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true, ACC_T = true;
+  static constexpr bool A_KS = true, B_KS = true, SPLIT_K = true, ACC_T = true, SPARSE_K = true;
   static constexpr int EPI = 1;
   static constexpr bool EPI_LDS = false;
+  OccMap occ;
+  __host__ __device__ __forceinline__ bool k_list() const { return occ.map != nullptr; }
+  // K runs over the destinations, M over the sources
+  __device__ __forceinline__ bool k_active(const GemmCtx &x, int m0, int bm, int k0, int bk) const {
+    return occ.any(x.z, k0, min(k0 + bk, x.K), m0, min(m0 + bm, x.M));
+  }
   RegionView<T> v;
   const T *A;  // [B*R][Dr][lda]
   int lda;
@@ -478,6 +545,58 @@ __global__ void k_copy_extra(const T *__restrict__ O, T *__restrict__ Ye, int D,
   Ye[e] = O[(b * (size_t)(D + T_extra) + D) * C + r];
 }
 
+// Occupancy map of A (see toma_internal.h).  One workgroup per (128 packets = 2 KiB of a row,
+// destination block, region): the rows of the block stream through two at a time, every thread ORs
+// the raw bits of the packets of its column (eight loads in flight), and the columns of one source
+// block are combined through LDS.  (-0 counts as occupied: harmless.)
+template <int ES>
+__global__ __launch_bounds__(256) void k_occupancy(const char *__restrict__ A, uint8_t *__restrict__ occ, int Dr,
+                                                  int Nr, int occ_db, int occ_sb) {
+  constexpr int WIDE = 128;               // packets of a row per workgroup
+  constexpr int PPB = kOccSrc * ES / 16;  // packets per source block
+  constexpr int NB = WIDE / PPB;          // source blocks per workgroup
+  __shared__ uint32_t any[NB];
+  const int tid = threadIdx.x, col = tid % WIDE, r2 = tid / WIDE;
+  const int z = blockIdx.z, dblk = blockIdx.y;
+  const size_t row_bytes = (size_t)Nr * ES;
+  const int pkt = blockIdx.x * WIDE + col;  // packet index inside a row
+  if (tid < NB) any[tid] = 0;
+  __syncthreads();
+  uint32_t acc = 0;
+  if ((size_t)pkt * 16 < row_bytes) {
+    const int j0 = dblk * kOccDest, j1 = min(j0 + kOccDest, Dr);
+    const char *base = A + ((size_t)z * Dr) * row_bytes + (size_t)pkt * 16;
+    for (int j = j0 + r2; j < j1; j += 16) {
+      u32x4 q[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int jj = min(j + 2 * u, j1 - 1);  // (a repeated last row changes nothing)
+        q[u] = *reinterpret_cast<const u32x4 *>(base + (size_t)jj * row_bytes);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) acc |= q[u][0] | q[u][1] | q[u][2] | q[u][3];
+    }
+  }
+  if (acc) atomicOr(&any[col / PPB], 1u);
+  __syncthreads();
+  const int sblk = blockIdx.x * NB + tid;
+  if (tid < NB && sblk < occ_sb) occ[((size_t)z * occ_db + dblk) * occ_sb + sblk] = any[tid] ? 1 : 0;
+}
+
+int launch_occupancy(const Shape &s, const void *A, char *ws, const Workspace &w, hipStream_t st) {
+  if (w.occ_sb == 0) return TOMA_OK;
+  const int es = s.dtype == TOMA_BF16 ? 2 : 4;
+  const int row_packets = s.Nr * es / 16;
+  const dim3 grid((row_packets + 127) / 128, w.occ_db, s.B * s.R);
+  uint8_t *occ = reinterpret_cast<uint8_t *>(ws + w.occ);
+  KernelTimer kt(K_OCC, st);
+  if (es == 2)
+    hipLaunchKernelGGL(k_occupancy<2>, grid, dim3(256), 0, st, static_cast<const char *>(A), occ, s.Dr, s.Nr, w.occ_db, w.occ_sb);
+  else
+    hipLaunchKernelGGL(k_occupancy<4>, grid, dim3(256), 0, st, static_cast<const char *>(A), occ, s.Dr, s.Nr, w.occ_db, w.occ_sb);
+  return launch_status();
+}
+
 template <typename T> static RegionView<T> make_view(const Shape &s, const void *X) {
   RegionView<T> v;
   v.X = static_cast<const T *>(X);
@@ -495,13 +614,16 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   if (weights_single_pass(s.Nr, s.Dr, s.C, batch, (int)sizeof(T))) {
     const RegionView<T> v = make_view<T>(s, X);
     const dim3 grid(s.Nr / 32, batch);
+    // the kernel fills the occupancy map itself when a wave's slice of destinations is whole blocks
+    const bool own_map = w.occ_sb != 0 && (s.Dr / 8) % kOccDest == 0;
+    uint8_t *occ = own_map ? reinterpret_cast<uint8_t *>(ws + w.occ) : nullptr;
     {
       KernelTimer kt(K_WWRITE, st);
       switch (s.Dr / 128) {
 #define TOMA_WF_CASE(NJ)                                                                                       \
   case NJ:                                                                                                     \
     hipLaunchKernelGGL((k_weights_fused<T, NJ>), grid, dim3(512), 0, st, v, idx, s.scale, static_cast<T *>(A), \
-                       s.Nr, zpart, w.z_parts);                                                                \
+                       s.Nr, zpart, w.z_parts, occ, w.occ_db, w.occ_sb);                                       \
     break;
         TOMA_WF_CASE(1)
         TOMA_WF_CASE(2)
@@ -512,9 +634,12 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
         default: return TOMA_ERR_UNSUPPORTED;
       }
     }
-    KernelTimer kt(K_ZSUM, st);
-    hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, zpart, Z, zr, w.z_parts, s.Nr / 32);
-    return launch_status();
+    {
+      KernelTimer kt(K_ZSUM, st);
+      hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, zpart, Z, zr, w.z_parts, s.Nr / 32);
+    }
+    if (launch_status() != TOMA_OK) return TOMA_ERR_LAUNCH;
+    return own_map ? TOMA_OK : launch_occupancy(s, A, ws, w, st);
   }
   WeightsPol<T, false> p1{};
   p1.v = make_view<T>(s, X);
@@ -523,12 +648,19 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   const GemmShape gs = launch_gemm<T>(K_WSTATS, p1, s.Nr, s.Dr, s.C, batch, st);
   float *lse = reinterpret_cast<float *>(ws + w.lse);
   int rows = batch * s.Nr;
+  // the write pass fills the occupancy map too (every wave tile lies inside one block of
+  // destinations: the wave slices of the planner's tiles divide kOccDest); k_lse zeroes it first
+  const bool own_map = w.occ_sb != 0;
+  uint8_t *occ = own_map ? reinterpret_cast<uint8_t *>(ws + w.occ) : nullptr;
+  const size_t occ_words = own_map ? ((size_t)batch * w.occ_db * w.occ_sb + 3) / 4 : 0;
   { KernelTimer kt(K_LSE, st);
-    hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n); }
+    hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n,
+                       reinterpret_cast<uint32_t *>(occ), occ_words); }
   WeightsPol<T, true> p2{};
   p2.v = p1.v; p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
   p2.A = static_cast<T *>(A); p2.lda = s.Nr;
   p2.zpart = zpart; p2.zparts = w.z_parts;
+  p2.occ = occ; p2.occ_db = w.occ_db; p2.occ_sb = w.occ_sb;
   const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
   { KernelTimer kt(K_ZSUM, st);
     hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
@@ -547,6 +679,7 @@ static int merge_typed(const Shape &s, const void *X, const void *A, const float
   MergePol<T> p{};
   p.v = make_view<T>(s, X);
   p.A = static_cast<const T *>(A); p.lda = s.Nr; p.Z = Z; p.Xm = static_cast<T *>(Xm);
+  p.occ = OccMap{w.occ_sb ? reinterpret_cast<const uint8_t *>(ws + w.occ) : nullptr, w.occ_db, w.occ_sb};
   p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_MERGE, p, s.Dr, s.C, s.Nr, s.B * s.R, st);
   return launch_status();
@@ -574,6 +707,7 @@ static int unmerge_typed(const Shape &s, const void *A, const float *Z, const vo
   }
   p.v = make_view<T>(s, nullptr);
   p.A = static_cast<const T *>(A); p.lda = s.Nr; p.Y = static_cast<T *>(Y);
+  p.occ = OccMap{w.occ_sb ? reinterpret_cast<const uint8_t *>(ws + w.occ) : nullptr, w.occ_db, w.occ_sb};
   p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_UNMERGE, p, s.Nr, s.C, s.Dr, s.B * s.R, st);
   return launch_status();
