@@ -23,6 +23,10 @@
  *     token: p = (r / tile_h) * (W / tile_w) + (c / tile_w), l = (r % tile_h) * tile_w + c % tile_w
  *     (tile-shaped regions, Sec. 4.3.1; tile_w == W gives stripe-shaped regions).
  *     P = regions per sample, N_loc = tile_h * tile_w, D = P * d_loc destinations per sample.
+ *   - Values are expected to be finite.  The merge and unmerge products skip blocks of the stored
+ *     weights that are entirely zero (with a small tau most of A is): a zero weight then contributes
+ *     nothing even where 0 * inf or 0 * NaN would have contributed a NaN.  For finite inputs the
+ *     results are those of the full products.
  *   - Limits: C % 32 == 0; N_loc % 16 == 0 and N_loc <= 256; 1 <= d_loc <= N_loc;
  *     merge_regions is 1 or P; head_dim is 32, 64 or 128.
  *     Anything else returns TOMA_ERR_UNSUPPORTED or TOMA_ERR_SHAPE.
