@@ -51,6 +51,10 @@ struct GemmCtx { int M, N, K, b, rho, z, split; };
 
 // A policy may declare SPARSE_K = true and supply k_list() / k_active(): the kernel then runs only
 // the K steps the policy calls active (see k_gemm_async).
+// A policy may also declare EMPTY_TILES = true and supply tile_is_empty() / write_empty_tile(): a
+// workgroup whose whole output tile the policy can prove empty writes it without the product.
+template <typename P, typename = void> struct PolEmptyTiles { static constexpr bool value = false; };
+template <typename P> struct PolEmptyTiles<P, std::void_t<decltype(P::EMPTY_TILES)>> { static constexpr bool value = P::EMPTY_TILES; };
 template <typename P, typename = void> struct PolSparseK { static constexpr bool value = false; };
 template <typename P> struct PolSparseK<P, std::void_t<decltype(P::SPARSE_K)>> { static constexpr bool value = P::SPARSE_K; };
 
@@ -343,6 +347,13 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   ctx.split = split;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w / WGN, wn = w % WGN;
   const int g = lane >> 4, c = lane & 15;
+  if constexpr (PolEmptyTiles<Pol>::value) {
+    // every thread checks its share of the evidence; all must agree
+    if (__syncthreads_and(pol.tile_is_empty(ctx, m0, n0, BM, BN, tid, 64 * WAVES) ? 1 : 0)) {
+      pol.write_empty_tile(ctx, m0, n0, BM, BN, BM / WGM, tid, 64 * WAVES);
+      return;
+    }
+  }
   // this workgroup's share of the K steps
   const int nk_all = ctx.K / G::BK;
   const int kt0 = (int)((long long)nk_all * split / nsplit), kt1 = (int)((long long)nk_all * (split + 1) / nsplit);

@@ -46,6 +46,46 @@ template <typename T, bool WRITE> struct WeightsPol {
   int zparts;
   uint8_t *occ;      // pass 2 out (optional): occupancy map of A, zeroed before the launch
   int occ_db, occ_sb;
+  // Pass 2 may skip the product of a tile that pass 1's statistics prove empty: pass 1 left, per
+  // source row and slice of `slice` destinations, the largest logit of the slice; where every such
+  // maximum of a tile lies more than kEmptyGap below its row's log-sum-exp, every weight of the tile
+  // is below exp(-kEmptyGap), which rounds to zero in bf16 and in fp32 alike, and the tile is
+  // written as zeros.  (With a small temperature that is all but the tiles around a token's own
+  // region.)
+  static constexpr bool EMPTY_TILES = WRITE;
+  static constexpr float kEmptyGap = 110.0f;
+  const float2 *seen;  // pass 1's statistics (null: no skipping)
+  int seen_parts, slice;
+  __device__ __forceinline__ bool tile_is_empty(const GemmCtx &x, int m0, int n0, int bm, int bn, int tid,
+                                                int nthreads) const {
+    if (!WRITE || !seen) return false;
+    const int p0 = n0 / slice, p1 = min((min(n0 + bn, x.N) - 1) / slice, seen_parts - 1);
+    for (int t = tid; t < bm; t += nthreads) {
+      const int m = m0 + t;
+      if (m >= x.M) break;
+      const float l = lse[(size_t)x.z * x.M + m];
+      const float2 *row = seen + ((size_t)x.z * x.M + m) * seen_parts;
+      for (int q = p0; q <= p1; q++)
+        if (!(row[q].x - l < -kEmptyGap)) return false;
+    }
+    return true;
+  }
+  __device__ __forceinline__ void write_empty_tile(const GemmCtx &x, int m0, int n0, int bm, int bn, int wave_rows,
+                                                   int tid, int nthreads) const {
+    constexpr int EPC = 16 / (int)sizeof(T);
+    const int m1 = min(m0 + bm, x.M), n1 = min(n0 + bn, x.N);
+    const int cpr = (m1 - m0) / EPC;  // 16-byte chunks per destination row (M is a multiple of 16)
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (int e = tid; e < (n1 - n0) * cpr; e += nthreads) {
+      const int n = n0 + e / cpr, m = m0 + (e % cpr) * EPC;
+      *reinterpret_cast<u32x4 *>(A + ((size_t)x.z * x.N + n) * lda + m) = zero;
+    }
+    // the partial row sums of all of this tile's wave slices (also those past a ragged end: the
+    // row-sum kernel adds up every slice of every tile)
+    const int parts = bm / wave_rows, part0 = m0 / wave_rows;
+    for (int e = tid; e < (n1 - n0) * parts; e += nthreads)
+      zpart[((size_t)x.z * x.N + n0 + e / parts) * zparts + part0 + e % parts] = 0.f;
+  }
   __device__ __forceinline__ GemmCtx setup(int bz) const {
     return GemmCtx{v.Nr, v.Dr, v.C, bz / v.R, bz % v.R, bz};
   }
@@ -661,6 +701,8 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   p2.A = static_cast<T *>(A); p2.lda = s.Nr;
   p2.zpart = zpart; p2.zparts = w.z_parts;
   p2.occ = occ; p2.occ_db = w.occ_db; p2.occ_sb = w.occ_sb;
+  // (pass 1 wrote one statistic per wave slice of its tiles: slices of bn / wgn destinations)
+  p2.seen = p1.stats; p2.seen_parts = w.stat_parts; p2.slice = gs.bn / gs.wgn;
   const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
   { KernelTimer kt(K_ZSUM, st);
     hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
