@@ -100,7 +100,10 @@ int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_
  *   Z_j  = sum_s A_js,   Xm_j = (1 / Z_j) * sum_s A_js x_s          (A~ = A / Z, Xm = A~ X)
  * Z_j is clamped below at 1e-20.  A is stored in dtype; Z sums the stored values of A.
  *   idx  in   [B, P, d_loc]             destinations (from toma_select or a cache)
- *   A    out  [B, R, D/R, N/R] dtype    R = merge_regions; sources of a region in local order
+ *   A    out  [B, R, D/R, N/R] dtype    R = merge_regions; sources in region order: source s of a
+ *                                       merge region is token l = s % N_loc of its selection region
+ *                                       s / N_loc (with R = P: of the region itself), so the tokens
+ *                                       of one selection region are N_loc consecutive columns
  *   Z    out  [B, D] float
  *   Xm   out  [B, D, C] dtype           merged tokens, rows in idx order
  * (A, Z) is the cache that toma_merge_cached / toma_unmerge take; treat it as opaque.

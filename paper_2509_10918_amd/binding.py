@@ -91,6 +91,18 @@ def make_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, dtype, logi
     return toma_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, logit_scale, code)
 
 
+def source_tokens(desc):
+    """Grid index (r * W + c) of every column of A: int64 [merge_regions, N / merge_regions].  Sources are
+    stored region by region, in local order inside a selection region (see toma_merge in toma.h)."""
+    import numpy as np
+    pw = desc.W // desc.tile_w
+    P = (desc.H // desc.tile_h) * pw
+    n_loc = desc.tile_h * desc.tile_w
+    p, l = np.divmod(np.arange(P * n_loc), n_loc)
+    tok = ((p // pw) * desc.tile_h + l // desc.tile_w) * desc.W + (p % pw) * desc.tile_w + l % desc.tile_w
+    return tok.reshape(desc.merge_regions, -1)
+
+
 def torch_dtype(desc):
     return torch.bfloat16 if desc.dtype == TOMA_BF16 else torch.float32
 

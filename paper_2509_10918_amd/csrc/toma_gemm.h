@@ -55,6 +55,10 @@ struct GemmCtx { int M, N, K, b, rho, z, split; };
 // workgroup whose whole output tile the policy can prove empty writes it without the product.
 template <typename P, typename = void> struct PolEmptyTiles { static constexpr bool value = false; };
 template <typename P> struct PolEmptyTiles<P, std::void_t<decltype(P::EMPTY_TILES)>> { static constexpr bool value = P::EMPTY_TILES; };
+// B_STEP_OFFSET = true with b_step_uniform() / b_step_offset(): a B operand that is not linear in k
+// but moves as a whole from one K step to the next.
+template <typename P, typename = void> struct PolStepB { static constexpr bool value = false; };
+template <typename P> struct PolStepB<P, std::void_t<decltype(P::B_STEP_OFFSET)>> { static constexpr bool value = P::B_STEP_OFFSET; };
 template <typename P, typename = void> struct PolSparseK { static constexpr bool value = false; };
 template <typename P> struct PolSparseK<P, std::void_t<decltype(P::SPARSE_K)>> { static constexpr bool value = P::SPARSE_K; };
 
@@ -446,6 +450,15 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   // the per-step delta of a linear operand is the same for every packet: keep it in a scalar register
   const int da = lin_a ? __builtin_amdgcn_readfirstlane((int)(pol.a_ptr(ctx, m0 + a_i[0], kbase + a_k[0] + G::BK) - pa[0])) : 0;
   const int db = lin_b ? __builtin_amdgcn_readfirstlane((int)(pol.b_ptr(ctx, n0 + b_i[0], kbase + b_k[0] + G::BK) - pb[0])) : 0;
+  // (a B operand that moves as a whole per step: one wave-uniform offset per step instead of an
+  // address computation per packet)
+  bool step_b = false;
+  ptrdiff_t step_b0 = 0;
+  if constexpr (PolStepB<Pol>::value) {
+    step_b = !lin_b && pol.b_step_uniform(G::BK);
+    if (step_b) step_b0 = pol.b_step_offset(ctx, kbase);
+  }
+  const bool b_fast = lin_b || step_b;
   // Ring positions are passed down as plain integers.  For all but the largest tile the K loop
   // below is unrolled by the number of stages, which makes them constants after inlining: the LDS
   // addresses of the loads are then scalar constants off one base, and the fragment reads use
@@ -468,9 +481,14 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
       const T *src = lin_a ? pa[t] + (ptrdiff_t)kt * da : pol.a_ptr(ctx, m0 + a_i[t], k0 + a_k[t]);
       load_to_lds16_at(src, a_st + (uint32_t)(t * 1024));
     }
+    // one wave-uniform offset per step covers the linear and the step-uniform case alike
+    ptrdiff_t b_off = (ptrdiff_t)kt * db;
+    if constexpr (PolStepB<Pol>::value) {
+      if (step_b) b_off = pol.b_step_offset(ctx, k0) - step_b0;
+    }
 #pragma unroll
     for (int t = 0; t < NIB; t++) {
-      const T *src = lin_b ? pb[t] + (ptrdiff_t)kt * db : pol.b_ptr(ctx, n0 + b_i[t], k0 + b_k[t]);
+      const T *src = b_fast ? pb[t] + b_off : pol.b_ptr(ctx, n0 + b_i[t], k0 + b_k[t]);
       load_to_lds16_at(src, b_st + (uint32_t)(t * 1024));
     }
   };

@@ -24,9 +24,31 @@ template <typename T> struct RegionView {
   const T *X;
   RegionMap map;
   int N, C, D, R, Nr, Dr;
-  __device__ __forceinline__ int token(int rho, int s) const { return R == 1 ? s : map.token(rho, s); }
-  // token(rho, s + step) - token(rho, s) does not depend on s
-  __device__ __forceinline__ bool token_linear(int step) const { return R == 1 || step % map.tile_w == 0; }
+  // Sources are enumerated region by region in both merge modes (local order inside a region), so
+  // that the columns of A that a region's destinations actually weigh - its own tokens and a few
+  // neighbours - are contiguous: with one merge region per sample, source s is token s % N_loc of
+  // selection region s / N_loc.
+  int sh_nloc, sh_tw, sh_pw;  // log2 of N_loc, tile_w and regions per grid row when all are powers of two, else -1
+  __device__ __forceinline__ int token(int rho, int s) const {
+    if (R != 1) return map.token(rho, s);
+    if (sh_nloc >= 0) {  // the usual shapes: no divisions
+      const int p = s >> sh_nloc, l = s & ((1 << sh_nloc) - 1);
+      const int r = (p >> sh_pw) * map.tile_h + (l >> sh_tw), c = ((p & (map.pw - 1)) << sh_tw) + (l & (map.tile_w - 1));
+      return r * map.W + c;
+    }
+    const int n_loc = map.tile_h * map.tile_w;
+    return map.token(s / n_loc, s % n_loc);
+  }
+  // token(rho, s + step) - token(rho, s) does not depend on s (inside one selection region)
+  __device__ __forceinline__ bool token_linear(int step) const {
+    if (R == 1) return map.tile_w == map.W && map.tile_h * map.tile_w >= N;  // a single region: raster order
+    return step % map.tile_w == 0;
+  }
+  // token(rho, s + i) - token(rho, s) does not depend on s for s a multiple of step and i < step:
+  // steps start on a region row and stay inside one selection region
+  __device__ __forceinline__ bool token_step_uniform(int step) const {
+    return step % map.tile_w == 0 && (map.tile_h * map.tile_w) % step == 0;
+  }
 };
 
 // ---- pass 1 and pass 2 of the weights ----------------------------------------------------------
@@ -500,6 +522,13 @@ template <typename T> struct MergePol {
   }
   __device__ __forceinline__ bool a_linear(int) const { return true; }
   __device__ __forceinline__ bool b_linear(int step) const { return v.token_linear(step); }
+  // where B is not linear in k it may still move as a whole from step to step: every packet of the
+  // step starting at source k sits b_step_offset(k) elements past its place in the step at source 0
+  static constexpr bool B_STEP_OFFSET = true;
+  __device__ __forceinline__ bool b_step_uniform(int step) const { return v.token_step_uniform(step); }
+  __device__ __forceinline__ ptrdiff_t b_step_offset(const GemmCtx &x, int k) const {
+    return (ptrdiff_t)(v.token(x.rho, k) - v.token(x.rho, 0)) * v.C;
+  }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &x, int m, int k) const {
     return A + ((size_t)x.z * x.M + m) * lda + k;
   }
@@ -642,6 +671,9 @@ template <typename T> static RegionView<T> make_view(const Shape &s, const void 
   v.X = static_cast<const T *>(X);
   v.map = RegionMap{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
   v.N = s.N; v.C = s.C; v.D = s.D; v.R = s.R; v.Nr = s.Nr; v.Dr = s.Dr;
+  auto log2_exact = [](int x) { int sh = 0; while ((1 << sh) < x) sh++; return (1 << sh) == x ? sh : -1; };
+  v.sh_nloc = log2_exact(s.n_loc); v.sh_tw = log2_exact(s.tile_w); v.sh_pw = log2_exact(v.map.pw);
+  if (v.sh_nloc < 0 || v.sh_tw < 0 || v.sh_pw < 0) v.sh_nloc = v.sh_tw = v.sh_pw = -1;
   return v;
 }
 

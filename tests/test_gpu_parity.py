@@ -198,7 +198,7 @@ def test_merge_unmerge_skip_only_empty_blocks(oracle, dtype, tau, C, passes):
     # cached pattern: the oracle's weights (rounded to the dtype) go to the device, the map comes
     # from the scan of that A
     A_in = _f64(synth.quantize(w, A_ref.astype(np.float32)))
-    dv.A.copy_(tg.dev(A_in, dtype).reshape(dv.A.shape))
+    dv.A.copy_(tg.dev(tg.a_in_stored_order(dv.desc, A_in), dtype).reshape(dv.A.shape))
     dv.Z.copy_(torch.from_numpy(Z_ref.astype(np.float32)).reshape(dv.Z.shape))
     _check_stage("Xm (cached A)", dv.merge_cached(), oracle.merge(d, X, A_in, Z_ref), tol)
     O = synth.quantize(w, rng.standard_normal((w.B, w.D, w.C)).astype(np.float32))

@@ -34,6 +34,23 @@ def oracle_desc(oracle, w, merge_regions):
     return oracle.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, merge_regions, w.tau)
 
 
+def a_in_oracle_order(desc, A):
+    """The stored weights [B, R, Dr, Nr] with the source axis as the oracle has it: grid (row-major)
+    order in global mode, local order per region in tile mode."""
+    if desc.merge_regions != 1:
+        return A
+    out = np.empty_like(A)
+    out[..., tb.source_tokens(desc)[0]] = A
+    return out
+
+
+def a_in_stored_order(desc, A):
+    """Inverse of a_in_oracle_order: an oracle-layout A as the library stores it."""
+    if desc.merge_regions != 1:
+        return A
+    return np.ascontiguousarray(A[..., tb.source_tokens(desc)[0]])
+
+
 class Device:
     """Device copies of one workload's tensors plus output buffers and workspace."""
 
@@ -63,7 +80,7 @@ class Device:
             self.idx.copy_(torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)))
         tb.toma_merge(self.desc, self.X, self.idx, self.A, self.Z, self.Xm, self.ws)
         torch.cuda.synchronize()
-        return host(self.A), host(self.Z), host(self.Xm)
+        return a_in_oracle_order(self.desc, host(self.A)), host(self.Z), host(self.Xm)
 
     def merge_cached(self):
         tb.toma_merge_cached(self.desc, self.X, self.A, self.Z, self.Xm, self.ws)
