@@ -41,7 +41,7 @@ template <typename T> struct RegionView {
   }
   // token(rho, s + step) - token(rho, s) does not depend on s (inside one selection region)
   __device__ __forceinline__ bool token_linear(int step) const {
-    if (R == 1) return map.tile_w == map.W && map.tile_h * map.tile_w >= N;  // a single region: raster order
+    if (R == 1) return map.tile_w == map.W;  // full-width regions: region order is grid order
     return step % map.tile_w == 0;
   }
   // token(rho, s + i) - token(rho, s) does not depend on s for s a multiple of step and i < step:
