@@ -89,3 +89,21 @@ def test_binding_raises_with_status():
     with pytest.raises(tb.TomaError) as e:
         tb._check(4, "toma_select")
     assert e.value.status == 4 and "workspace" in str(e.value)
+
+
+@pytest.mark.parametrize("H,W,th,tw,R", [(8, 12, 4, 4, 1), (8, 12, 4, 4, 6), (6, 8, 3, 8, 1), (16, 16, 16, 16, 1)])
+def test_source_tokens_enumerates_regions_in_local_order(H, W, th, tw, R):
+    """Column s of A: with one merge region, token s % N_loc of selection region s / N_loc; with one
+    merge region per selection region, token s of that region (Sec. 4.3.1's region / local index)."""
+    d = tb.make_desc(1, H, W, 32, th, tw, 1, R, 0.1, "f32")
+    got = tb.source_tokens(d)
+    pw, n_loc = W // tw, th * tw
+    P = (H // th) * pw
+    want = []
+    for p in range(P):
+        for l in range(n_loc):
+            r, c = (p // pw) * th + l // tw, (p % pw) * tw + l % tw
+            want.append(r * W + c)
+    assert got.shape == (R, H * W // R)
+    assert got.reshape(-1).tolist() == want
+    assert sorted(want) == list(range(H * W))        # every token exactly once
