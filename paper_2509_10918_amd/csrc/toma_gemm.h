@@ -37,6 +37,13 @@
 //   static constexpr bool SPLIT_K         K may be split between workgroups; then also
 //   float* split_buffer()                 fp32 partial tiles [split][batch][M][N], and
 //   void finish(ctx, m, n, f32x4 v)       output step for four consecutive columns of a summed row
+// and optionally (detected by the traits below)
+//   static constexpr bool SPARSE_K        with k_list() / k_active(ctx, m0, bm, k0, bk): only the K
+//                                         steps the policy calls active are run
+//   static constexpr bool EMPTY_TILES     with tile_is_empty() / write_empty_tile(): output tiles the
+//                                         policy can prove empty are written without their product
+//   static constexpr bool B_STEP_OFFSET   with b_step_uniform() / b_step_offset(ctx, k): a B operand
+//                                         that is not affine in k but moves as a whole per K step
 // The policy itself is never written to, so it stays in the kernel-argument segment.
 // Extents along a packet's direction must be multiples of the packet length (8 bf16 / 4 fp32).
 #pragma once
