@@ -451,19 +451,32 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
   for (int j = 0; j < NJ; j++) {
     const int n = w * 16 * NJ + 16 * j + c;
     float colsum = 0.f;
+    alignas(16) T o[2][4];
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      alignas(16) T o[4];
+    for (int i = 0; i < 2; i++)
 #pragma unroll
       for (int r = 0; r < 4; r++) {
-        o[r] = from_f32<T>(__expf(acc[i][j][r] - l4[i][r]));
-        const float stored = to_f32(o[r]);
+        o[i][r] = from_f32<T>(__expf(acc[i][j][r] - l4[i][r]));
+        const float stored = to_f32(o[i][r]);
         colsum += stored;
         nonzero[16 * j / kOccDest % kBlocks] |= stored != 0.f;
       }
-      T *dst = A + ((size_t)z * v.Dr + n) * lda + m0 + 16 * i + 4 * g;
-      if (sizeof(T) == 2) *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<u32x2 *>(o);
-      else *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<u32x4 *>(o);
+    T *row = A + ((size_t)z * v.Dr + n) * lda + m0;
+    if constexpr (sizeof(T) == 2) {
+      // A lane holds 8 bytes of each source tile (four sources); lanes g and g ^ 1 trade halves so
+      // that each stores one 16-byte packet and the four lanes of a destination a whole 64-byte run
+      // (even g: sources 4 g .. 4 g + 7 of tile 0, odd g: sources 4 (g - 1) .. 4 g + 3 of tile 1)
+      const u32x2 own0 = *reinterpret_cast<u32x2 *>(o[0]), own1 = *reinterpret_cast<u32x2 *>(o[1]);
+      const bool odd = g & 1;
+      const u32x2 give = odd ? own0 : own1;
+      u32x2 got;
+      got[0] = (uint32_t)__shfl_xor((int)give[0], 16, 64);
+      got[1] = (uint32_t)__shfl_xor((int)give[1], 16, 64);
+      const u32x4 pk = odd ? (u32x4){got[0], got[1], own1[0], own1[1]} : (u32x4){own0[0], own0[1], got[0], got[1]};
+      *reinterpret_cast<u32x4 *>(row + (odd ? 16 + 4 * (g - 1) : 4 * g)) = pk;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; i++) *reinterpret_cast<u32x4 *>(row + 16 * i + 4 * g) = *reinterpret_cast<u32x4 *>(o[i]);
     }
     colsum += wave_xor_f32(colsum, 16);
     colsum += wave_xor_f32(colsum, 32);
