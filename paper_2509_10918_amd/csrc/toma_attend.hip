@@ -325,16 +325,22 @@ __device__ __forceinline__ float rows4_sum_f32(float v) {
 // softmax of tile t, so that the matrix cores work on them while the vector ALU does the maxima,
 // exponentials and packing of tile t (a wave executes in order; with one or two waves per SIMD
 // nothing else would overlap the two).
-template <typename T, int DH, int QT>
-__global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn_async(const T *__restrict__ Q, const T *__restrict__ Kx,
-                                                                     const T *__restrict__ V, T *__restrict__ O, int L,
-                                                                     int H, float scale_log2,
-                                                                     const float *__restrict__ Zs, int D) {
+// NW waves per workgroup, 16 QT queries each.  The default is eight waves with one query tile each:
+// the same 128 queries per workgroup as four waves with two tiles, but twice the waves per SIMD, and
+// a wave alone overlaps its matrix and vector work poorly (the ring of a 128-wide head leaves room
+// for one workgroup per CU only, which then runs two waves per SIMD instead of one: 86 -> 71 us on
+// the Flux block; with 64-wide heads two workgroups share a CU and the gain is 5 %).
+template <typename T, int DH, int QT, int NW = 4>
+__global__ __launch_bounds__(64 * NW, DH >= 128 ? 1 : (NW > 4 ? 2 : (QT == 1 ? 3 : 2))) void k_attn_async(
+    const T *__restrict__ Q, const T *__restrict__ Kx, const T *__restrict__ V, T *__restrict__ O, int L, int H,
+    float scale_log2, const float *__restrict__ Zs, int D) {
   constexpr int ES = (int)sizeof(T), EPP = 16 / ES;
   constexpr int PPR = DH / EPP;       // 16-byte packets per K / V row
   constexpr int KK = DH / 32, DT = DH / 16, STAGES = 4;  // QT: query tiles (of 16) per wave
   constexpr int CH = PPR;             // 1 KiB chunks per 64-row tile
-  constexpr int NI = CH / 4;          // load instructions per wave per tile, for K and for V
+  constexpr int NI = CH / NW;         // load instructions per wave per tile, for K and for V
+  static_assert(CH % NW == 0, "the tile's chunks divide among the waves");
+  constexpr int QB = NW * 16 * QT;    // queries per workgroup
   constexpr int TILE = 64 * DH;
   __shared__ __align__(1024) T Ks[STAGES][TILE];
   __shared__ __align__(1024) T Vs[STAGES][TILE];
@@ -342,12 +348,12 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
   // one-dimensional grid over (sample, head, query block), remapped so that the blocks an XCD
   // receives are neighbours: the query blocks of a head then share that head's K and V in one L2
-  const int nq = (L + 64 * QT - 1) / (64 * QT);
+  const int nq = (L + QB - 1) / QB;
   const int work = xcd_remap(blockIdx.x, gridDim.x);
   const int qb = work % nq, h = (work / nq) % H, b = work / (nq * H);
   const size_t head = ((size_t)b * H + h) * L * DH;
   const T *Qh = Q + head, *Kh = Kx + head, *Vh = V + head;
-  const int q_w = qb * (64 * QT) + w * (16 * QT);
+  const int q_w = qb * QB + w * (16 * QT);
   const int nt = (L + 63) / 64;
 
   Frag<T> fq[QT][KK];
@@ -415,22 +421,28 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
   // All K fragments of the tile are requested before the first product (a scheduling fence keeps
   // the compiler from folding each read back in front of its use: it would wait out the LDS
   // latency once per fragment instead of once per tile).
+  // (in batches of KB k-groups: all at once where the registers allow)
   auto scores = [&](f32x4 (&st)[4][QT], const T *kt_) {
-    Frag<T> fk[KK][4];
+    constexpr int KB = (NW > 4 && KK > 2) ? 2 : KK;
 #pragma unroll
-    for (int kk = 0; kk < KK; kk++)
+    for (int k0 = 0; k0 < KK; k0 += KB) {
+      Frag<T> fk[KB][4];
 #pragma unroll
-      for (int kt = 0; kt < 4; kt++) frag_load_kcw_sw<PPR>(fk[kk][kt], kt_, 16 * kt + c, 32 * kk + 8 * g);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int kk = 0; kk < KB; kk++)
 #pragma unroll
-    for (int kk = 0; kk < KK; kk++)
+        for (int kt = 0; kt < 4; kt++) frag_load_kcw_sw<PPR>(fk[kk][kt], kt_, 16 * kt + c, 32 * (k0 + kk) + 8 * g);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kt = 0; kt < 4; kt++)
+      for (int kk = 0; kk < KB; kk++)
 #pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-          if (kk == 0) st[kt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-          mma16(st[kt][qt], fk[kk][kt], fq[qt][kk]);
-        }
+        for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+          for (int qt = 0; qt < QT; qt++) {
+            if (k0 + kk == 0) st[kt][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            mma16(st[kt][qt], fk[kk][kt], fq[qt][k0 + kk]);
+          }
+      if (k0 + KB < KK) __builtin_amdgcn_sched_barrier(0);
+    }
   };
   // online softmax of one tile's scores and O^T += V^T P^T
   auto softmax_pv = [&](f32x4 (&st)[4][QT], const T *vt_, int key0) {
@@ -551,7 +563,7 @@ __global__ __launch_bounds__(256, DH >= 128 ? 1 : (QT == 1 ? 3 : 2)) void k_attn
 }
 
 #ifndef TOMA_ATTN_QT
-#define TOMA_ATTN_QT 2
+#define TOMA_ATTN_QT 8   // 8: eight waves with one query tile each; 1, 2: four waves with that many tiles
 #endif
 template <typename T, int DH>
 static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, const float *Zs, hipStream_t st,
@@ -561,7 +573,10 @@ static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O
   // load-to-LDS pipeline when a row is at least eight packets and the ring of four tiles fits the LDS
   constexpr int kRowPackets = DH * (int)sizeof(T) / 16;
   if constexpr (kRowPackets >= 8 && 4 * 2 * 64 * DH * (int)sizeof(T) <= 160 * 1024 - 4096) {
-    if (qt == 1) {
+    if (qt == 8) {  // eight waves, one query tile each
+      dim3 grid((s.L + 127) / 128 * s.heads * s.B);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 1, 8>), grid, dim3(512), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+    } else if (qt == 1) {
       dim3 grid((s.L + 63) / 64 * s.heads * s.B);
       hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
     } else {
