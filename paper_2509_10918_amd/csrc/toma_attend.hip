@@ -325,22 +325,24 @@ __device__ __forceinline__ float rows4_sum_f32(float v) {
 // softmax of tile t, so that the matrix cores work on them while the vector ALU does the maxima,
 // exponentials and packing of tile t (a wave executes in order; with one or two waves per SIMD
 // nothing else would overlap the two).
-// NW waves per workgroup, 16 QT queries each.  The default is eight waves with one query tile each:
-// the same 128 queries per workgroup as four waves with two tiles, but twice the waves per SIMD, and
-// a wave alone overlaps its matrix and vector work poorly (the ring of a 128-wide head leaves room
-// for one workgroup per CU only, which then runs two waves per SIMD instead of one: 86 -> 71 us on
-// the Flux block; with 64-wide heads two workgroups share a CU and the gain is 5 %).
-template <typename T, int DH, int QT, int NW = 4>
-__global__ __launch_bounds__(64 * NW, DH >= 128 ? 1 : (NW > 4 ? 2 : (QT == 1 ? 3 : 2))) void k_attn_async(
+// The number of waves per workgroup is the launch's choice (blockDim.x / 64, four to twelve), 16 QT
+// queries each: with one query tile per wave it sets how many queries a workgroup takes and with
+// that how evenly the grid fills the SIMDs (launch_attn picks it per shape).  Many waves with one
+// tile each beat few waves with two: a wave alone overlaps its matrix and vector work poorly, and
+// the ring of a 128-wide head leaves room for one workgroup per CU only.  The first four waves
+// fetch the K / V tiles (the first eight where a row is 256 bytes or more: such launches have at
+// least eight).
+template <typename T, int DH, int QT>
+__global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 256 ? 3 : 4) : (DH * sizeof(T) >= 256 ? 1 : 2)) void k_attn_async(
     const T *__restrict__ Q, const T *__restrict__ Kx, const T *__restrict__ V, T *__restrict__ O, int L, int H,
     float scale_log2, const float *__restrict__ Zs, int D) {
   constexpr int ES = (int)sizeof(T), EPP = 16 / ES;
   constexpr int PPR = DH / EPP;       // 16-byte packets per K / V row
   constexpr int KK = DH / 32, DT = DH / 16, STAGES = 4;  // QT: query tiles (of 16) per wave
   constexpr int CH = PPR;             // 1 KiB chunks per 64-row tile
-  constexpr int NI = CH / NW;         // load instructions per wave per tile, for K and for V
-  static_assert(CH % NW == 0, "the tile's chunks divide among the waves");
-  constexpr int QB = NW * 16 * QT;    // queries per workgroup
+  constexpr int LW = QT == 1 && DH * ES >= 256 ? 8 : 4;  // waves that fetch the K / V tiles (the first LW)
+  constexpr int NI = CH / LW;         // load instructions per loading wave per tile, for K and for V
+  const int QB = (int)(blockDim.x >> 6) * 16 * QT;  // queries per workgroup
   constexpr int TILE = 64 * DH;
   __shared__ __align__(1024) T Ks[STAGES][TILE];
   __shared__ __align__(1024) T Vs[STAGES][TILE];
@@ -376,32 +378,36 @@ __global__ __launch_bounds__(64 * NW, DH >= 128 ? 1 : (NW > 4 ? 2 : (QT == 1 ? 3
   }
 
   // what this lane fetches for its chunks: tile row and element offset inside the row
-  int k_row[NI];
-  const T *kp[NI], *vp[NI];
+  // (element offsets from the head's first row: the tile's base stays in scalar registers)
+  int k_row[NI], k_off[NI], v_off[NI];
+  const bool loader = w < LW;
+  const int wl = w & (LW - 1);
 #pragma unroll
   for (int t = 0; t < NI; t++) {
-    const int ch = w * NI + t, row = ch * (64 / PPR) + lane / PPR, pos = lane % PPR;
+    const int ch = wl * NI + t, row = ch * (64 / PPR) + lane / PPR, pos = lane % PPR;
     k_row[t] = row;
-    kp[t] = Kh + (size_t)row * DH + ((pos & ~7) | ((pos ^ row) & 7)) * EPP;
-    vp[t] = Vh + (size_t)row * DH + SwzTile<T>::template ks_slot<PPR>(row, pos) * EPP;
+    k_off[t] = row * DH + ((pos & ~7) | ((pos ^ row) & 7)) * EPP;
+    v_off[t] = row * DH + SwzTile<T>::template ks_slot<PPR>(row, pos) * EPP;
   }
   // LDS byte addresses of this wave's first chunk in stage 0 (scalar registers)
-  const uint32_t ks_addr = lds_addr_of(&Ks[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(w) * (NI * 1024);
-  const uint32_t vs_addr = lds_addr_of(&Vs[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(w) * (NI * 1024);
+  const uint32_t ks_addr = lds_addr_of(&Ks[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(wl) * (NI * 1024);
+  const uint32_t vs_addr = lds_addr_of(&Vs[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(wl) * (NI * 1024);
   auto issue = [&](int st, int it) {
+    if (!loader) return;  // (a wave without loads passes every vmcnt wait below at once)
     const ptrdiff_t adv = (ptrdiff_t)it * 64 * DH;
     if ((it + 1) * 64 <= L) {  // uniform: only the last tile can reach past the end
+      const T *kb = Kh + adv, *vb = Vh + adv;
 #pragma unroll
       for (int t = 0; t < NI; t++) {
-        load_to_lds16_at(kp[t] + adv, ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
-        load_to_lds16_at(vp[t] + adv, vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_at(kb + k_off[t], ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_at(vb + v_off[t], vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
       }
     } else {  // rows past the end repeat row L - 1 and are masked below
 #pragma unroll
       for (int t = 0; t < NI; t++) {
         const ptrdiff_t a = it * 64 + k_row[t] >= L ? (ptrdiff_t)(L - 1 - k_row[t]) * DH : adv;
-        load_to_lds16_at(kp[t] + a, ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
-        load_to_lds16_at(vp[t] + a, vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_at(Kh + (a + k_off[t]), ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_at(Vh + (a + v_off[t]), vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
       }
     }
   };
@@ -423,7 +429,7 @@ __global__ __launch_bounds__(64 * NW, DH >= 128 ? 1 : (NW > 4 ? 2 : (QT == 1 ? 3
   // latency once per fragment instead of once per tile).
   // (in batches of KB k-groups: all at once where the registers allow)
   auto scores = [&](f32x4 (&st)[4][QT], const T *kt_) {
-    constexpr int KB = (NW > 4 && KK > 2) ? 2 : KK;
+    constexpr int KB = (QT == 1 && KK > 2) ? 2 : KK;
 #pragma unroll
     for (int k0 = 0; k0 < KK; k0 += KB) {
       Frag<T> fk[KB][4];
@@ -562,23 +568,48 @@ __global__ __launch_bounds__(64 * NW, DH >= 128 ? 1 : (NW > 4 ? 2 : (QT == 1 ? 3
   }
 }
 
+// Waves per workgroup for k_attn_async with one query tile per wave.  Model (fitted to sweeps of
+// the wave count over sequence lengths 512 .. 8192): workgroups are placed `cap` to a CU (LDS ring
+// and register file) in rounds over the 256 CUs; the busiest SIMD of a CU then holds
+// k = cap * ceil(nw / 4) waves (a second workgroup lands on the SIMDs like the first), and a round
+// costs max(kAlone, k) units per key tile: several waves on a SIMD are bound by their vector-ALU
+// work, one or two by their own dependent chain (kAlone: about 2 for rows under 256 bytes, 2.3
+// above).  The choice with the least total wins, eight waves unless another is at least 3% better.
+static int attn_waves(int L, int heads_x_batch, int ring_bytes, int waves_per_cu, int min_waves, float kAlone) {
+  int best = 8;
+  float best_cost = 0.f;
+  for (int pass = 0; pass < 2; pass++)
+    for (int nw = pass == 0 ? 8 : min_waves; nw <= (pass == 0 ? 8 : 12); nw++) {
+      const int cap = std::min((160 * 1024) / ring_bytes, waves_per_cu / nw);
+      if (cap < 1) continue;
+      const long wgs = (long)((L + 16 * nw - 1) / (16 * nw)) * heads_x_batch;
+      const long slots = 256L * cap, full = wgs / slots, rem = wgs % slots;
+      const int per_simd = (nw + 3) / 4;
+      float cost = (float)full * std::max(kAlone, (float)(cap * per_simd));
+      if (rem) cost += std::max(kAlone, (float)((int)((rem + 255) / 256) * per_simd));
+      if (pass == 0 || cost < best_cost * 0.97f) { best = nw; best_cost = cost; }
+    }
+  return best;
+}
+
 #ifndef TOMA_ATTN_QT
-#define TOMA_ATTN_QT 8   // 8: eight waves with one query tile each; 1, 2: four waves with that many tiles
+#define TOMA_ATTN_QT 1   // query tiles per wave: 1 (any number of waves) or 2 (four waves)
 #endif
+// nw: waves per workgroup, 0 = chosen by attn_waves
 template <typename T, int DH>
 static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, const float *Zs, hipStream_t st,
-                        int qt = TOMA_ATTN_QT) {
+                        int nw = 0) {
   float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   KernelTimer kt(K_ATTN, st);
   // load-to-LDS pipeline when a row is at least eight packets and the ring of four tiles fits the LDS
   constexpr int kRowPackets = DH * (int)sizeof(T) / 16;
-  if constexpr (kRowPackets >= 8 && 4 * 2 * 64 * DH * (int)sizeof(T) <= 160 * 1024 - 4096) {
-    if (qt == 8) {  // eight waves, one query tile each
-      dim3 grid((s.L + 127) / 128 * s.heads * s.B);
-      hipLaunchKernelGGL((k_attn_async<T, DH, 1, 8>), grid, dim3(512), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
-    } else if (qt == 1) {
-      dim3 grid((s.L + 63) / 64 * s.heads * s.B);
-      hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+  constexpr int kRing = 4 * 2 * 64 * DH * (int)sizeof(T);
+  if constexpr (kRowPackets >= 8 && kRing <= 160 * 1024 - 4096) {
+    if (TOMA_ATTN_QT == 1) {
+      constexpr bool kWide = DH * sizeof(T) >= 256;  // three waves per SIMD fit the registers, else four
+      if (nw < (kWide ? 8 : 4) || nw > 12) nw = attn_waves(s.L, s.heads * s.B, kRing, kWide ? 12 : 16, kWide ? 8 : 4, kWide ? 2.3f : 2.0f);
+      dim3 grid((s.L + 16 * nw - 1) / (16 * nw) * s.heads * s.B);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(64 * nw), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
     } else {
       dim3 grid((s.L + 127) / 128 * s.heads * s.B);
       hipLaunchKernelGGL((k_attn_async<T, DH, 2>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);

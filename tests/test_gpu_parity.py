@@ -247,9 +247,12 @@ def test_layer_chained_and_reuse(oracle, cases, name, tile_local):
 
 
 @pytest.mark.parametrize("dtype,heads,C,L,T", [("bf16", 2, 256, 200, 0), ("bf16", 1, 32, 77, 5),
-                                               ("f32", 2, 128, 130, 0), ("f32", 1, 128, 64, 3)])
+                                               ("f32", 2, 128, 130, 0), ("f32", 1, 128, 64, 3),
+                                               ("bf16", 10, 640, 256, 1744), ("bf16", 12, 1536, 256, 1244)])
 def test_attention_shapes_and_output_projection(oracle, dtype, heads, C, L, T):
-    """Head widths 32 / 64 / 128, ragged lengths, extra tokens and the optional W_o."""
+    """Head widths 32 / 64 / 128, ragged lengths, extra tokens and the optional W_o.  The two long
+    cases (2000 and 1500 tokens over 20 and 24 heads) are sized so that the launch takes workgroups
+    of eleven and ten waves, the last one of each head reaching past the end."""
     print(f"[attend] {dtype} heads={heads} C={C} D={L} T={T}", flush=True)
     rng = np.random.default_rng(5)
     # a descriptor whose D equals L: one region of 16 x 16 tokens per 'row', d_loc chosen to fit
