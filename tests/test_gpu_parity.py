@@ -206,6 +206,71 @@ def test_merge_unmerge_skip_only_empty_blocks(oracle, dtype, tau, C, passes):
     _check_stage("Y", Y, oracle.unmerge(d, A_in, np.maximum(Z_ref, 1e-20), _f64(O)), tol)
 
 
+def _crafted_weights(rng, B, D, N, case):
+    """Sparse weights [B, D, N] with the sources in the order the library stores them: one to three
+    destinations per source, all inside the source's own 128-destination block, plus what the case
+    plants."""
+    A = np.zeros((B, D, N), dtype=np.float32)
+    per_block = N // (D // 128)            # sources whose destinations lie in one block
+    for b in range(B):
+        for i in range(N):
+            blk = i // per_block
+            for j in rng.choice(128, size=int(rng.integers(1, 4)), replace=False):
+                A[b, blk * 128 + j, i] = rng.uniform(0.1, 1.0)
+    if case == "long row":                 # 65 weights in one destination's row
+        A[1, 300, :] = 0.0
+        A[1, 300, rng.choice(N, size=65, replace=False)] = 0.5
+    elif case == "many source blocks":     # 65 occupied blocks of 32 sources in one destination block
+        A[0, 128:256, :] = 0.0
+        for k in range(65):
+            A[0, 128 + k, 32 * (k + 3) + 5] = 0.25
+    elif case == "many destination blocks":  # a block of 32 sources with weights in 9 destination blocks
+        A[0, :, 64:96] = 0.0
+        for k in range(9):
+            A[0, 128 * k + 7, 64 + k] = 0.75
+    elif case == "long column":            # 17 weights for one source, in one destination block
+        A[1, :, 1000] = 0.0
+        A[1, 512 + 3 * np.arange(17), 1000] = 0.125
+    elif case == "crowded rows":           # 16 rows x 32 sources with 80 weights
+        A[0, 256:272, 512:544] = 0.0
+        for r in range(16):
+            A[0, 256 + r, 512 + rng.choice(32, size=5, replace=False)] = 0.375
+    elif case == "empty":                  # a destination nobody chooses and a source with no weight at all
+        A[0, 40, :] = 0.0
+        A[1, :, 77] = 0.0
+    return A
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("case", ["plain", "empty", "long row", "many source blocks", "many destination blocks",
+                                  "long column", "crowded rows"])
+def test_merge_unmerge_of_planted_weights(oracle, dtype, case):
+    """Merge and unmerge of a cached, planted A on a shape long enough for the occupancy map: very
+    sparse weights around the block diagonal plus rows, columns and blocks that are far denser or
+    far more scattered than the rest.  Whatever blocks the products skip, the result is the dense
+    definition; then the same through the layer call with the cached pattern."""
+    print(f"[planted] {dtype} {case}", flush=True)
+    w = synth.scaled(W["tiny"], name="planted", dtype=dtype, B=2, H=64, W=64, C=128, tile_h=16, tile_w=16,
+                     keep=0.5, heads=2, index=16)
+    inp = synth.make_inputs(w)
+    tol = tg.TOL[dtype]
+    rng = np.random.default_rng(21)
+    d = tg.oracle_desc(oracle, w, 1)
+    dv = tg.Device(w, inp, 1)
+    A_in = tg.a_in_oracle_order(dv.desc, _f64(synth.quantize(w, _crafted_weights(rng, w.B, w.D, w.N, case))))
+    Z = A_in.sum(axis=2)
+    X = _f64(inp["X"])
+    dv.A.copy_(tg.dev(tg.a_in_stored_order(dv.desc, A_in), dtype).reshape(dv.A.shape))
+    dv.Z.copy_(torch.from_numpy(Z.astype(np.float32)).reshape(dv.Z.shape))
+    _check_stage("Xm", dv.merge_cached(), oracle.merge(d, X, A_in, Z), tol)
+    O = synth.quantize(w, rng.standard_normal((w.B, w.D, w.C)).astype(np.float32))
+    _check_stage("Y", dv.unmerge(O=O), oracle.unmerge(d, A_in, np.maximum(Z, 1e-20), _f64(O)), tol)
+    Yl, _ = dv.layer(tb.TOMA_REUSE_A)
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    ref = oracle.layer(d, X, *Wts, heads=w.heads, idx=np.zeros((w.B, w.P, w.d_loc), dtype=np.int64), AZ=(A_in, Z))
+    _check_stage("Y (layer, cached A)", Yl, ref["Y"], tol)
+
+
 @pytest.mark.parametrize("tile_local", [False, True])
 @pytest.mark.parametrize("name", list(CASES))
 def test_layer_chained_and_reuse(oracle, cases, name, tile_local):
