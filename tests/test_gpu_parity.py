@@ -65,6 +65,19 @@ def test_select_region_sizes(oracle, n_loc_shape, d_loc):
     assert not bad
 
 
+@pytest.mark.parametrize("dtype,C", [("bf16", 128), ("bf16", 256), ("f32", 64)])
+def test_select_many_regions(oracle, dtype, C):
+    """64 regions of 256 tokens: enough 32 x 32 blocks of the similarity matrices for the kernel that
+    takes them whole, with K in one slice (few channels) and in two; the picks must be the oracle's."""
+    w = synth.scaled(W["tiny"], name="many", dtype=dtype, B=1, H=128, W=128, C=C, tile_h=16, tile_w=16,
+                     keep=0.25, heads=max(1, C // 64), index=17)
+    print(f"[select many regions] {dtype} C={C} regions={w.P}", flush=True)
+    inp = synth.make_inputs(w)
+    dv = tg.Device(w, inp, 1)
+    bad, near, forced = tg.compare_picks(oracle, w, _f64(inp["X"]), dv.select())
+    assert not bad
+
+
 def test_select_all_identical_tokens_picks_in_index_order(oracle):
     w = synth.scaled(W["tiny"], name="const", B=1, H=8, W=8, C=32, tile_h=4, tile_w=4, keep=1.0, index=12)
     inp = synth.make_inputs(w)
