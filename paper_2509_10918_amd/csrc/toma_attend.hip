@@ -387,7 +387,7 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
     const int ch = wl * NI + t, row = ch * (64 / PPR) + lane / PPR, pos = lane % PPR;
     k_row[t] = row;
     k_off[t] = row * DH + ((pos & ~7) | ((pos ^ row) & 7)) * EPP;
-    v_off[t] = row * DH + SwzTile<T>::template ks_slot<PPR>(row, pos) * EPP;
+    v_off[t] = row * DH + SwzTile<T>::template ks_slot<PPR, true>(row, pos) * EPP;
   }
   // LDS byte addresses of this wave's first chunk in stage 0 (scalar registers)
   const uint32_t ks_addr = lds_addr_of(&Ks[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(wl) * (NI * 1024);
@@ -510,7 +510,7 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
 #pragma unroll
       for (int dt = 0; dt < DT; dt++) {
         Frag<T> fv;
-        frag_load_ks_sw<PPR>(fv, vt_, 32 * u + 4 * g, 32 * u + 16 + 4 * g, 16 * dt, lane);
+        frag_load_ks_sw<PPR, true>(fv, vt_, 32 * u + 4 * g, 32 * u + 16 + 4 * g, 16 * dt, lane);
 #pragma unroll
         for (int qt = 0; qt < QT; qt++) mma16(oacc[dt][qt], fv, fp[qt][u]);
       }

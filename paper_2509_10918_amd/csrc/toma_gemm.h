@@ -250,36 +250,43 @@ template <typename T> struct SwzTile {
   // read touches, per 16 lanes, four consecutive k-rows x 32 bytes: the low bits of k spread them
   // over one 128-byte bank group; bit 3 of k (the second 16 lanes of each half wave sit eight rows
   // further) selects the other 128-byte group when a row is long enough to have one.
-  template <int PPR> __device__ static __forceinline__ int ks_slot(int k, int pi) {
+  // G4: the second 16 lanes sit FOUR rows further (the attention kernel's key order).  A long row
+  // again has its other 128-byte group for them; with 128-byte rows, where odd and even rows already
+  // alternate between the two groups, they take the 32-byte pieces that the first 16 lanes leave free.
+  template <int PPR, bool G4 = false> __device__ static __forceinline__ int ks_slot(int k, int pi) {
+    if constexpr (G4) {
+      if (PPR >= 16) return pi ^ ((k & 3) << 1) ^ (((k >> 2) & 1) << 3);
+      return pi ^ (((k & 3) ^ ((k >> 2) & 1)) << 1);
+    }
     int s = pi ^ ((k & 3) << 1);
     if (PPR >= 16) s ^= ((k >> 3) & 1) << 3;
     return s;
   }
-  template <int PPR> __device__ static __forceinline__ int ks(int k, int pi) {
-    return (k * PPR + ks_slot<PPR>(k, pi)) * EPP;
+  template <int PPR, bool G4 = false> __device__ static __forceinline__ int ks(int k, int pi) {
+    return (k * PPR + ks_slot<PPR, G4>(k, pi)) * EPP;
   }
 };
 
-template <int PPR>
+template <int PPR, bool G4 = false>
 __device__ __forceinline__ void frag_load_ks_sw(Frag<bf16_t> &f, const bf16_t *tile, int ka, int kb, int nb, int lane) {
   typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
   typedef short s16x8 __attribute__((ext_vector_type(8)));
   const int j = lane & 15, col = nb + 4 * (j & 3);
   const int ra = ka + (j >> 2), rb = kb + (j >> 2);
-  const bf16_t *pa = tile + SwzTile<bf16_t>::ks<PPR>(ra, col >> 3) + (col & 7);
-  const bf16_t *pb = tile + SwzTile<bf16_t>::ks<PPR>(rb, col >> 3) + (col & 7);
+  const bf16_t *pa = tile + SwzTile<bf16_t>::ks<PPR, G4>(ra, col >> 3) + (col & 7);
+  const bf16_t *pb = tile + SwzTile<bf16_t>::ks<PPR, G4>(rb, col >> 3) + (col & 7);
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pa));
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pb));
   s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   f.v = __builtin_bit_cast(bf16x8, both);
 }
-template <int PPR>
+template <int PPR, bool G4 = false>
 __device__ __forceinline__ void frag_load_ks_sw(Frag<float> &f, const float *tile, int ka, int kb, int nb, int lane) {
   const int col = nb + (lane & 15);
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    f.v[i] = tile[SwzTile<float>::ks<PPR>(ka + i, col >> 2) + (col & 3)];
-    f.v[4 + i] = tile[SwzTile<float>::ks<PPR>(kb + i, col >> 2) + (col & 3)];
+    f.v[i] = tile[SwzTile<float>::ks<PPR, G4>(ka + i, col >> 2) + (col & 3)];
+    f.v[4 + i] = tile[SwzTile<float>::ks<PPR, G4>(kb + i, col >> 2) + (col & 3)];
   }
 }
 // eight consecutive k starting at element kf of row `row` of a swizzled k-contiguous tile
