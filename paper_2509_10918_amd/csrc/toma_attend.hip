@@ -25,7 +25,7 @@ template <typename T> struct QkvPol {
   const T *Xm, *Xe;
   const T *W[3];
   T *out[3];
-  int B, D, Tx, L, C, H, dh;
+  int B, D, Tx, L, C, H, dh, dh_sh;  // dh_sh = log2(dh), or -1 if dh is not a power of two
   __device__ __forceinline__ GemmCtx setup(int bz) const { return GemmCtx{B * L, C, C, 0, 0, bz}; }
   __device__ __forceinline__ bool a_linear(int) const { return true; }
   __device__ __forceinline__ bool b_linear(int) const { return true; }
@@ -40,11 +40,19 @@ template <typename T> struct QkvPol {
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
                                            int lane, void *wave_lds) const {
     // head-major output [B][H][L][dh]: a row's part and a column's part of the offset add up
+    // (divisions are dear here: the head width is a power of two, and the sample of a row follows
+    // from the sample of the wave tile's first row, which is the same for all lanes)
     T *o = out[x.z];
-    const int L_ = L, H_ = H, dh_ = dh;
+    const int L_ = L, H_ = H, dh_ = dh, sh = dh_sh;
+    const int b0 = m_w / L_, l0 = m_w - b0 * L_;
     store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
-                  [=](int m) { const int b = m / L_, l = m - b * L_; return o + ((size_t)b * H_ * L_ + l) * dh_; },
-                  [=](int n) { const int h = n / dh_; return (size_t)h * L_ * dh_ + (n - h * dh_); },
+                  [=](int m) {
+                    int b = b0, l = l0 + (m - m_w);
+                    if (L_ >= 16 * TM) { if (l >= L_) { l -= L_; b++; } }  // a tile of 16 TM rows crosses one boundary at most
+                    else { b = m / L_; l = m - b * L_; }
+                    return o + ((size_t)b * H_ * L_ + l) * dh_;
+                  },
+                  [=](int n) { const int h = sh >= 0 ? n >> sh : n / dh_; return (size_t)h * L_ * dh_ + (n - h * dh_); },
                   [](int) { return 1.0f; });
   }
 };
@@ -630,6 +638,8 @@ static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const vo
   p.W[0] = static_cast<const T *>(Wq); p.W[1] = static_cast<const T *>(Wk); p.W[2] = static_cast<const T *>(Wv);
   p.out[0] = Q; p.out[1] = K; p.out[2] = V;
   p.B = s.B; p.D = s.D; p.Tx = s.T; p.L = s.L; p.C = s.C; p.H = s.heads; p.dh = s.head_dim;
+  p.dh_sh = -1;
+  for (int sh = 0; sh < 16; sh++) if ((1 << sh) == s.head_dim) p.dh_sh = sh;
   launch_gemm<T>(K_QKV, p, s.B * s.L, s.C, s.C, 3, st);
   T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
   switch (s.head_dim) {

@@ -644,6 +644,11 @@ template <typename T, int TM, int TN, typename RowFn, typename ColFn, typename R
 __device__ __forceinline__ void store_rows(const WaveAccT<TM, TN> &acc, int m_w, int n_w, int lane, int M, int N,
                                            RowFn row, ColFn col, RowScaleFn row_scale, ElemFn elem = ElemFn()) {
   const int g = lane >> 4, c = lane & 15;
+  // the column parts once, outside the rows' conditional code (left inside, each row's copy of a
+  // column offset that needs a division is computed again)
+  decltype(col(0)) coff[TN];
+#pragma unroll
+  for (int j = 0; j < TN; j++) coff[j] = col(n_w + 16 * j + 4 * g);
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     const int m = m_w + 16 * i + c;
@@ -653,7 +658,7 @@ __device__ __forceinline__ void store_rows(const WaveAccT<TM, TN> &acc, int m_w,
 #pragma unroll
     for (int j = 0; j < TN; j++) {
       const int n = n_w + 16 * j + 4 * g;
-      if (n < N) store4<T>(base + col(n), elem(acc.t[i][j] * sc));
+      if (n < N) store4<T>(base + coff[j], elem(acc.t[i][j] * sc));
     }
   }
 }
