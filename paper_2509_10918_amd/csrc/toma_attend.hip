@@ -3,8 +3,10 @@
 //
 //   k_gemm<QkvPol>   Q, K, V = U W  (one launch, blockIdx.z picks the weight), written head-major
 //                    [B][heads][L][head_dim] so that every head is a dense matrix.
-//   k_attn           flash-style attention: 128 queries per workgroup (32 per wave), 64 keys per
-//                    step through LDS, online softmax, nothing of size L x L ever stored.
+//   k_attn_async     flash-style attention: 16 queries per wave, four to twelve waves per workgroup
+//                    (chosen per launch), 64 keys per step through a ring of K / V tiles in LDS,
+//                    online softmax, nothing of size L x L ever stored.  (k_attn: the same with
+//                    register-staged tiles, for head widths whose ring does not fit.)
 //                    The score tile is computed TRANSPOSED (keys x queries): its accumulator
 //                    layout (lane = query, registers = 4 consecutive keys) is then already the
 //                    B-operand layout of the second product O^T += V^T P^T, so probabilities go
