@@ -584,22 +584,33 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
 // k = cap * ceil(nw / 4) waves (a second workgroup lands on the SIMDs like the first), and a round
 // costs max(kAlone, k) units per key tile: several waves on a SIMD are bound by their vector-ALU
 // work, one or two by their own dependent chain (kAlone: about 2 for rows under 256 bytes, 2.3
-// above).  The choice with the least total wins, eight waves unless another is at least 3% better.
+// above).  The choice with the least total wins; how ties go is said in the function.
 static int attn_waves(int L, int heads_x_batch, int ring_bytes, int waves_per_cu, int min_waves, float kAlone) {
-  int best = 8;
-  float best_cost = 0.f;
-  for (int pass = 0; pass < 2; pass++)
-    for (int nw = pass == 0 ? 8 : min_waves; nw <= (pass == 0 ? 8 : 12); nw++) {
-      const int cap = std::min((160 * 1024) / ring_bytes, waves_per_cu / nw);
-      if (cap < 1) continue;
-      const long wgs = (long)((L + 16 * nw - 1) / (16 * nw)) * heads_x_batch;
-      const long slots = 256L * cap, full = wgs / slots, rem = wgs % slots;
-      const int per_simd = (nw + 3) / 4;
-      float cost = (float)full * std::max(kAlone, (float)(cap * per_simd));
-      if (rem) cost += std::max(kAlone, (float)((int)((rem + 255) / 256) * per_simd));
-      if (pass == 0 || cost < best_cost * 0.97f) { best = nw; best_cost = cost; }
-    }
-  return best;
+  float cost[13];
+  long wgs_of[13];
+  float least = 0.f;
+  for (int nw = min_waves; nw <= 12; nw++) {
+    cost[nw] = -1.f;
+    const int cap = std::min((160 * 1024) / ring_bytes, waves_per_cu / nw);
+    if (cap < 1) continue;
+    const long wgs = (long)((L + 16 * nw - 1) / (16 * nw)) * heads_x_batch;
+    const long slots = 256L * cap, full = wgs / slots, rem = wgs % slots;
+    const int per_simd = (nw + 3) / 4;
+    float c = (float)full * std::max(kAlone, (float)(cap * per_simd));
+    if (rem) c += std::max(kAlone, (float)((int)((rem + 255) / 256) * per_simd));
+    cost[nw] = c;
+    wgs_of[nw] = wgs;
+    if (least == 0.f || c < least) least = c;
+  }
+  // among the choices within 3% of the least: the one that spreads one workgroup per CU over the
+  // most CUs (measured 5-8% ahead of its equals), else eight waves, else the first
+  int best = -1;
+  for (int nw = min_waves; nw <= 12; nw++) {
+    if (cost[nw] < 0.f || cost[nw] > least * 1.03f) continue;
+    if (wgs_of[nw] <= 256 && (best < 0 || wgs_of[best] > 256 || wgs_of[nw] > wgs_of[best])) best = nw;
+    else if (best < 0 || (nw == 8 && wgs_of[best] > 256)) best = nw;
+  }
+  return best < 0 ? 8 : best;
 }
 
 #ifndef TOMA_ATTN_QT
