@@ -627,14 +627,15 @@ __global__ void k_copy_extra(const T *__restrict__ O, T *__restrict__ Ye, int D,
   Ye[e] = O[(b * (size_t)(D + T_extra) + D) * C + r];
 }
 
-// Occupancy map of A (see toma_internal.h).  One workgroup per (128 packets = 2 KiB of a row,
-// destination block, region): the rows of the block stream through two at a time, every thread ORs
-// the raw bits of the packets of its column (eight loads in flight), and the columns of one source
-// block are combined through LDS.  (-0 counts as occupied: harmless.)
-template <int ES>
+// Occupancy map of A (see toma_internal.h).  One workgroup per (WIDE packets of a row, destination
+// block, region): the rows of the block stream through 256 / WIDE at a time, every thread ORs the
+// raw bits of the packets of its column (eight loads in flight), and the columns of one source
+// block are combined through LDS.  (-0 counts as occupied: harmless.)  Narrow pieces of the rows
+// and many workgroups suit this read best: 512 bytes per row and workgroup here.
+template <int ES, int WIDE>  // WIDE: packets of a row per workgroup
 __global__ __launch_bounds__(256) void k_occupancy(const char *__restrict__ A, uint8_t *__restrict__ occ, int Dr,
                                                   int Nr, int occ_db, int occ_sb) {
-  constexpr int WIDE = 128;               // packets of a row per workgroup
+  constexpr int RG = 256 / WIDE;          // row groups: rows of the block in flight side by side
   constexpr int PPB = kOccSrc * ES / 16;  // packets per source block
   constexpr int NB = WIDE / PPB;          // source blocks per workgroup
   __shared__ uint32_t any[NB];
@@ -648,11 +649,11 @@ __global__ __launch_bounds__(256) void k_occupancy(const char *__restrict__ A, u
   if ((size_t)pkt * 16 < row_bytes) {
     const int j0 = dblk * kOccDest, j1 = min(j0 + kOccDest, Dr);
     const char *base = A + ((size_t)z * Dr) * row_bytes + (size_t)pkt * 16;
-    for (int j = j0 + r2; j < j1; j += 16) {
+    for (int j = j0 + r2; j < j1; j += 8 * RG) {
       u32x4 q[8];
 #pragma unroll
       for (int u = 0; u < 8; u++) {
-        const int jj = min(j + 2 * u, j1 - 1);  // (a repeated last row changes nothing)
+        const int jj = min(j + RG * u, j1 - 1);  // (a repeated last row changes nothing)
         q[u] = *reinterpret_cast<const u32x4 *>(base + (size_t)jj * row_bytes);
       }
 #pragma unroll
@@ -669,13 +670,15 @@ int launch_occupancy(const Shape &s, const void *A, char *ws, const Workspace &w
   if (w.occ_sb == 0) return TOMA_OK;
   const int es = s.dtype == TOMA_BF16 ? 2 : 4;
   const int row_packets = s.Nr * es / 16;
-  const dim3 grid((row_packets + 127) / 128, w.occ_db, s.B * s.R);
+  constexpr int wide = 32;  // packets of a row per workgroup (128, 64 and 16 measured slower)
+  const dim3 grid((row_packets + wide - 1) / wide, w.occ_db, s.B * s.R);
   uint8_t *occ = reinterpret_cast<uint8_t *>(ws + w.occ);
   KernelTimer kt(K_OCC, st);
+  const char *Ab = static_cast<const char *>(A);
   if (es == 2)
-    hipLaunchKernelGGL(k_occupancy<2>, grid, dim3(256), 0, st, static_cast<const char *>(A), occ, s.Dr, s.Nr, w.occ_db, w.occ_sb);
+    hipLaunchKernelGGL((k_occupancy<2, wide>), grid, dim3(256), 0, st, Ab, occ, s.Dr, s.Nr, w.occ_db, w.occ_sb);
   else
-    hipLaunchKernelGGL(k_occupancy<4>, grid, dim3(256), 0, st, static_cast<const char *>(A), occ, s.Dr, s.Nr, w.occ_db, w.occ_sb);
+    hipLaunchKernelGGL((k_occupancy<4, wide>), grid, dim3(256), 0, st, Ab, occ, s.Dr, s.Nr, w.occ_db, w.occ_sb);
   return launch_status();
 }
 
