@@ -175,7 +175,8 @@ def main():
     notes = {
         "greedy": "achieved = bytes a per-round rescan of S (Alg. 2) would stream / duration; S stays in registers and "
                   "the values are updated incrementally, so the figure can exceed the HBM peak: the binding limit is "
-                  "the per-round dependency chain (LDS exchange, two barriers), not HBM",
+                  "each round's dependent chain (the exchange through LDS, then the columns whose coverage the "
+                  "pick raises, one after the other), not HBM",
         "gram": "achieved counts the full N_loc x N_loc product; the kernel executes the blocks on and above the "
                 "diagonal only (53% of it at N_loc = 256); a bare fp64 MFMA loop measures 43-47 TFLOP/s on this part",
     }
