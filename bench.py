@@ -101,7 +101,7 @@ def main():
     Xe = dev(inp["X_extra"]) if inp["X_extra"] is not None else None
     Wq, Wk, Wv = dev(inp["Wq"]), dev(inp["Wk"]), dev(inp["Wv"])
     ws = tb.alloc_workspace(desc, attn)
-    idx, A, Z = tb.alloc_cache(desc)
+    idx, A, Z, amap = tb.alloc_cache(desc)
     Y = torch.empty((w.B, w.N, w.C), dtype=tdt, device="cuda")
     Ye = torch.empty((w.B, w.T_extra, w.C), dtype=tdt, device="cuda") if w.T_extra else None
 
@@ -114,7 +114,7 @@ def main():
                 for sel, rew in synth.reuse_schedule(w)]
 
     def call(flags, x=None):
-        tb.toma_layer(desc, attn, flags, X if x is None else x, Xe, idx, A, Z, Wq, Wk, Wv, None, Y, Ye, ws)
+        tb.toma_layer(desc, attn, flags, X if x is None else x, Xe, idx, A, Z, amap, Wq, Wk, Wv, None, Y, Ye, ws)
 
     def timed(flags, steps):
         torch.cuda.synchronize()

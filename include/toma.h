@@ -84,14 +84,18 @@ const char *toma_status_string(int status);
  * row sum; every later pick maximises sum_j max(0, S_ij - m_j) over tokens not yet picked, with
  * m_j the largest similarity of token j to the picks so far.  Ties go to the lowest index.
  * Similarities are evaluated in double precision from the stored token values and rounded once
- * to the nearest multiple of 2^-22; the sums and comparisons over them are exact, so the picks
- * do not depend on any summation order and exact ties are decided by index alone.
+ * to the nearest multiple of 2^-30; the sums and comparisons over them are exact (64-bit integers),
+ * so the picks do not depend on any summation order and mathematically tied candidates (frequent:
+ * two tokens that only improve each other's coverage) are exact ties, decided by index alone.
  *   X        in   [B, N, C]         tokens (dtype)
  *   idx      out  [B, P, d_loc]     int32 grid index of each pick, in pick order
- *   gain_opt out  [B, P, d_loc]     float value of each winning candidate, or NULL
+ *   gain_opt out  [B, P, d_loc]     float value of each winning candidate (the first: its row sum), or NULL
+ *   gap_opt  out  [B, P, d_loc]     float lead of each winner over the best other candidate (0 = an
+ *                                   exact tie, decided by index; +inf = no other candidate was left),
+ *                                   or NULL.  gap / gain below 1e-6 marks a near tie.
  */
-int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt, void *ws,
-                size_t ws_bytes, void *stream);
+int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt, float *gap_opt,
+                void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Merge weights and merge (Sec. 4.2.1; Alg. 3 step 2).  Inside each merge region (all tokens
@@ -105,16 +109,34 @@ int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_
  *                                       s / N_loc (with R = P: of the region itself), so the tokens
  *                                       of one selection region are N_loc consecutive columns
  *   Z    out  [B, D] float
+ *   amap out  toma_map_bytes(desc) bytes   block map of A (below); NULL iff toma_map_bytes(desc) == 0
  *   Xm   out  [B, D, C] dtype           merged tokens, rows in idx order
- * (A, Z) is the cache that toma_merge_cached / toma_unmerge take; treat it as opaque.
+ * (A, Z, amap) is the cache that toma_merge_cached / toma_unmerge / toma_layer take: the three
+ * belong together and are only valid with the descriptor they were written under; treat them as opaque.
  */
-int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx, void *A, float *Z,
+int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx, void *A, float *Z, void *amap,
                void *Xm, void *ws, size_t ws_bytes, void *stream);
 
-/* Merge with cached weights (Sec. 4.3.2): Xm = (A / Z) X for the CURRENT X and an (A, Z) computed
- * earlier by toma_merge with the same descriptor. */
+/*
+ * The block map of a stored A (part of the pattern cache of Sec. 4.3.2).  With a small temperature
+ * nearly every source token gives all of its weight to one or two destinations and the rest of its
+ * column of A is stored as exact zeros; the map says, per block of 128 destinations x 32 sources of
+ * every merge region, whether the block holds any nonzero value, and the merge and unmerge products
+ * skip the blocks that do not.  Whoever writes A writes the map (toma_merge, toma_layer); it is
+ * caller-owned device memory that lives as long as (A, Z) and must never outlive or be mixed with
+ * another A: a map that marks an occupied block as empty silently drops that block's weights.
+ *   toma_map_bytes   size of the map for this descriptor; 0 when the shape uses none (short
+ *                    products), in which case every amap argument may be NULL
+ *   toma_map_build   recomputes the map from an A that did not come out of this library's weight
+ *                    kernels (restored from elsewhere, edited by the caller): one read of A
+ */
+size_t toma_map_bytes(const toma_desc *desc);
+int toma_map_build(const toma_desc *desc, const void *A, void *amap, void *stream);
+
+/* Merge with cached weights (Sec. 4.3.2): Xm = (A / Z) X for the CURRENT X and an (A, Z, amap)
+ * computed earlier by toma_merge / toma_layer with the same descriptor. */
 int toma_merge_cached(const toma_desc *desc, const void *X, const void *A, const float *Z,
-                      void *Xm, void *ws, size_t ws_bytes, void *stream);
+                      const void *amap, void *Xm, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Attention on the merged tokens (Eq. 1 with tau = 1; Alg. 3 "computational layer").
@@ -135,21 +157,21 @@ int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *X
  *   O  in   [B, o_rows, C]   o_rows >= D; only rows [0, D) of each sample are read
  *   Y  out  [B, N, C]
  */
-int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *O,
+int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *amap, const void *O,
                  int32_t o_rows, void *Y, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * One whole layer with pattern reuse (Alg. 3 + Sec. 4.3.2).  reuse_flags says what is taken from
  * the caller's cache instead of being recomputed from X:
- *   0                  select, weights, merge, attention, unmerge; idx, A, Z are written
- *   TOMA_REUSE_IDX     idx is read; weights are recomputed; A, Z are written
- *   TOMA_REUSE_A       idx is ignored, A and Z are read (implies TOMA_REUSE_IDX)
+ *   0                  select, weights, merge, attention, unmerge; idx, A, Z, amap are written
+ *   TOMA_REUSE_IDX     idx is read; weights are recomputed; A, Z, amap are written
+ *   TOMA_REUSE_A       idx is ignored, A, Z and amap are read (implies TOMA_REUSE_IDX)
  *   Y            out  [B, N, C]
  *   Y_extra_opt  out  [B, t_extra, C]  rows of O that belong to the extra tokens (NULL iff none)
  */
 enum { TOMA_REUSE_IDX = 1, TOMA_REUSE_A = 2 };
 int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse_flags,
-               const void *X, const void *X_extra_opt, int32_t *idx, void *A, float *Z,
+               const void *X, const void *X_extra_opt, int32_t *idx, void *A, float *Z, void *amap,
                const void *Wq, const void *Wk, const void *Wv, const void *Wo_opt, void *Y,
                void *Y_extra_opt, void *ws, size_t ws_bytes, void *stream);
 
@@ -178,7 +200,9 @@ int toma_mlp(int32_t dtype, int32_t rows, int32_t C, int32_t hidden, const void 
  * pool until the process ends).  toma_profile_read waits for the recorded events of all kernels,
  * then returns and clears the launch count and summed duration (ms) of the named kernel.
  * toma_profile_kernel_name(i) enumerates the names (NULL past the last).  Enabling or disabling
- * clears all totals.  Not meant to be enabled under HIP graph capture.
+ * clears all totals.  Not meant to be enabled under HIP graph capture.  The three calls may come from
+ * any thread; a launch in flight on another thread while totals are read or cleared is counted
+ * whole, either before or after.
  */
 int toma_profile_enable(int on);
 const char *toma_profile_kernel_name(int i);

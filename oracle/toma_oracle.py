@@ -47,7 +47,7 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
-SIM_BITS = 22  # similarities are decided on a 2^-22 grid (see toma_oracle.c)
+SIM_BITS = 30  # similarities are decided on a 2^-30 grid (see toma_oracle.c)
 
 
 def make_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, sim_bits=SIM_BITS, scale=None):

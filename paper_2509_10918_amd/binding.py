@@ -14,8 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libtoma.so")
 
 TOMA_F32, TOMA_BF16 = 0, 1
 TOMA_REUSE_IDX, TOMA_REUSE_A = 1, 2
-EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_merge",
-           "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer", "toma_mlp", "toma_profile_enable",
+EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_merge", "toma_map_bytes",
+           "toma_map_build", "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer", "toma_mlp", "toma_profile_enable",
            "toma_profile_kernel_name", "toma_profile_read")
 
 
@@ -64,15 +64,18 @@ def lib():
         L.toma_status_string.restype = ctypes.c_char_p
         L.toma_status_string.argtypes = [ctypes.c_int]
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
-        L.toma_select.argtypes = [vp, vp, vp, vp, vp, sz, vp]
-        L.toma_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
-        L.toma_merge_cached.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_select.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_map_bytes.restype = ctypes.c_size_t
+        L.toma_map_bytes.argtypes = [vp]
+        L.toma_map_build.argtypes = [vp, vp, vp, vp]
+        L.toma_merge_cached.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_attend.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-        L.toma_unmerge.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
-        L.toma_layer.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_unmerge.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
+        L.toma_layer.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_mlp.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
-        for name in ("toma_select", "toma_merge", "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer",
-                     "toma_mlp"):
+        for name in ("toma_select", "toma_merge", "toma_map_build", "toma_merge_cached", "toma_attend", "toma_unmerge",
+                     "toma_layer", "toma_mlp"):
             getattr(L, name).restype = ctypes.c_int
         L.toma_profile_enable.argtypes = [ctypes.c_int]
         L.toma_profile_kernel_name.restype = ctypes.c_char_p
@@ -89,18 +92,6 @@ def status_string(status):
 def make_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, dtype, logit_scale=0.0):
     code = {torch.float32: TOMA_F32, torch.bfloat16: TOMA_BF16, "f32": TOMA_F32, "bf16": TOMA_BF16}[dtype]
     return toma_desc(B, H, W, C, tile_h, tile_w, d_loc, merge_regions, tau, logit_scale, code)
-
-
-def source_tokens(desc):
-    """Grid index (r * W + c) of every column of A: int64 [merge_regions, N / merge_regions].  Sources are
-    stored region by region, in local order inside a selection region (see toma_merge in toma.h)."""
-    import numpy as np
-    pw = desc.W // desc.tile_w
-    P = (desc.H // desc.tile_h) * pw
-    n_loc = desc.tile_h * desc.tile_w
-    p, l = np.divmod(np.arange(P * n_loc), n_loc)
-    tok = ((p // pw) * desc.tile_h + l // desc.tile_w) * desc.W + (p % pw) * desc.tile_w + l % desc.tile_w
-    return tok.reshape(desc.merge_regions, -1)
 
 
 def torch_dtype(desc):
@@ -139,19 +130,27 @@ def alloc_workspace(desc, attn=None, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def toma_select(desc, X, idx, gain, ws):
-    _check(lib().toma_select(_ref(desc), _ptr(X), _ptr(idx), _ptr(gain), _ptr(ws), ws.numel(), _stream()),
-           "toma_select")
+def toma_select(desc, X, idx, gain, gap, ws):
+    _check(lib().toma_select(_ref(desc), _ptr(X), _ptr(idx), _ptr(gain), _ptr(gap), _ptr(ws), ws.numel(),
+                             _stream()), "toma_select")
 
 
-def toma_merge(desc, X, idx, A, Z, Xm, ws):
-    _check(lib().toma_merge(_ref(desc), _ptr(X), _ptr(idx), _ptr(A), _ptr(Z), _ptr(Xm), _ptr(ws), ws.numel(),
-                            _stream()), "toma_merge")
+def toma_merge(desc, X, idx, A, Z, amap, Xm, ws):
+    _check(lib().toma_merge(_ref(desc), _ptr(X), _ptr(idx), _ptr(A), _ptr(Z), _ptr(amap), _ptr(Xm), _ptr(ws),
+                            ws.numel(), _stream()), "toma_merge")
 
 
-def toma_merge_cached(desc, X, A, Z, Xm, ws):
-    _check(lib().toma_merge_cached(_ref(desc), _ptr(X), _ptr(A), _ptr(Z), _ptr(Xm), _ptr(ws), ws.numel(),
-                                   _stream()), "toma_merge_cached")
+def toma_map_bytes(desc):
+    return lib().toma_map_bytes(_ref(desc))
+
+
+def toma_map_build(desc, A, amap):
+    _check(lib().toma_map_build(_ref(desc), _ptr(A), _ptr(amap), _stream()), "toma_map_build")
+
+
+def toma_merge_cached(desc, X, A, Z, amap, Xm, ws):
+    _check(lib().toma_merge_cached(_ref(desc), _ptr(X), _ptr(A), _ptr(Z), _ptr(amap), _ptr(Xm), _ptr(ws),
+                                   ws.numel(), _stream()), "toma_merge_cached")
 
 
 def toma_attend(desc, attn, Xm, X_extra, Wq, Wk, Wv, Wo, O, ws):
@@ -159,15 +158,15 @@ def toma_attend(desc, attn, Xm, X_extra, Wq, Wk, Wv, Wo, O, ws):
                              _ptr(Wo), _ptr(O), _ptr(ws), ws.numel(), _stream()), "toma_attend")
 
 
-def toma_unmerge(desc, A, Z, O, Y, ws):
-    _check(lib().toma_unmerge(_ref(desc), _ptr(A), _ptr(Z), _ptr(O), O.shape[1], _ptr(Y), _ptr(ws), ws.numel(),
-                              _stream()), "toma_unmerge")
+def toma_unmerge(desc, A, Z, amap, O, Y, ws):
+    _check(lib().toma_unmerge(_ref(desc), _ptr(A), _ptr(Z), _ptr(amap), _ptr(O), O.shape[1], _ptr(Y), _ptr(ws),
+                              ws.numel(), _stream()), "toma_unmerge")
 
 
-def toma_layer(desc, attn, reuse_flags, X, X_extra, idx, A, Z, Wq, Wk, Wv, Wo, Y, Y_extra, ws):
+def toma_layer(desc, attn, reuse_flags, X, X_extra, idx, A, Z, amap, Wq, Wk, Wv, Wo, Y, Y_extra, ws):
     _check(lib().toma_layer(_ref(desc), _ref(attn), int(reuse_flags), _ptr(X), _ptr(X_extra), _ptr(idx), _ptr(A),
-                            _ptr(Z), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo), _ptr(Y), _ptr(Y_extra), _ptr(ws),
-                            ws.numel(), _stream()), "toma_layer")
+                            _ptr(Z), _ptr(amap), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo), _ptr(Y), _ptr(Y_extra),
+                            _ptr(ws), ws.numel(), _stream()), "toma_layer")
 
 
 def toma_mlp(In, W1, W2, Hbuf, Out):
@@ -201,10 +200,13 @@ def toma_profile_read(kernel):
 
 
 def alloc_cache(desc, device="cuda"):
-    """Caller-owned pattern cache (idx, A, Z) of one layer."""
+    """Caller-owned pattern cache (idx, A, Z, amap) of one layer; amap is None when the shape uses no
+    block map."""
     dt = torch_dtype(desc)
     R = desc.merge_regions
     idx = torch.empty((desc.B, desc.P, desc.d_loc), dtype=torch.int32, device=device)
     A = torch.empty((desc.B, R, desc.D // R, desc.N // R), dtype=dt, device=device)
     Z = torch.empty((desc.B, desc.D), dtype=torch.float32, device=device)
-    return idx, A, Z
+    n = toma_map_bytes(desc)
+    amap = torch.empty(n, dtype=torch.uint8, device=device) if n else None
+    return idx, A, Z, amap

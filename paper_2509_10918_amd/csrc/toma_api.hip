@@ -26,7 +26,9 @@ int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s) {
   if (d->merge_regions != 1 && d->merge_regions != s->P) return TOMA_ERR_SHAPE;
   if (d->C % 32) return TOMA_ERR_UNSUPPORTED;
   if (s->n_loc % 16 || s->n_loc > 256) return TOMA_ERR_UNSUPPORTED;
-  if ((long long)d->B * s->N * d->C >= (1ll << 40)) return TOMA_ERR_UNSUPPORTED;
+  // kernels index inside one sample with 32-bit element offsets and launch one thread per element
+  // of a tensor in places: a sample's tokens must stay below 2^31 elements, the batch below 2^38
+  if ((long long)s->N * d->C >= (1ll << 31) || (long long)d->B * s->N * d->C >= (1ll << 38)) return TOMA_ERR_UNSUPPORTED;
   s->R = d->merge_regions;
   s->D = s->P * d->d_loc;
   s->Nr = s->N / s->R;
@@ -39,6 +41,7 @@ int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s) {
     if ((long long)a->heads * a->head_dim != d->C) return TOMA_ERR_SHAPE;
     if (a->head_dim != 32 && a->head_dim != 64 && a->head_dim != 128) return TOMA_ERR_UNSUPPORTED;
     s->heads = a->heads; s->head_dim = a->head_dim; s->T = a->t_extra; s->L = s->D + a->t_extra;
+    if ((long long)s->L * d->C >= (1ll << 31) || (long long)d->B * s->L * d->C >= (1ll << 38)) return TOMA_ERR_UNSUPPORTED;
   }
   return TOMA_OK;
 }
@@ -80,13 +83,14 @@ void plan_workspace(const Shape &s, Workspace *w) {
     if (pu.nsplit > 1) part = std::max(part, (size_t)pu.nsplit * s.B * s.N * s.C * sizeof(float));
   }
   w->split = take(part);
+  // the occupancy map of A is not scratch: it belongs to the caller's cache, next to (A, Z)
   if (occupancy_pays(s.Nr, s.Dr, s.C, (int)es)) {
     w->occ_db = (s.Dr + kOccDest - 1) / kOccDest;
     w->occ_sb = s.Nr / kOccSrc;
-    w->occ = take((size_t)s.B * s.R * w->occ_db * w->occ_sb);
+    w->occ_bytes = up256((size_t)s.B * s.R * w->occ_db * w->occ_sb);
   } else {
     w->occ_db = w->occ_sb = 0;
-    w->occ = off;
+    w->occ_bytes = 0;
   }
   w->total = off;
 }
@@ -131,40 +135,73 @@ TOMA_API const char *toma_status_string(int status) {
   }
 }
 
-TOMA_API int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt, void *ws,
-                         size_t ws_bytes, void *stream) {
+TOMA_API int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt, float *gap_opt,
+                         void *ws, size_t ws_bytes, void *stream) {
   Shape s; Workspace w;
   int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
   if (rc != TOMA_OK) return rc;
   if (!X || !idx) return TOMA_ERR_NULL;
-  if (misaligned(X, 16) || misaligned(idx, 4) || (gain_opt && misaligned(gain_opt, 4))) return TOMA_ERR_ALIGN;
-  return launch_select(s, X, idx, gain_opt, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+  if (misaligned(X, 16) || misaligned(idx, 4) || (gain_opt && misaligned(gain_opt, 4)) ||
+      (gap_opt && misaligned(gap_opt, 4)))
+    return TOMA_ERR_ALIGN;
+  return launch_select(s, X, idx, gain_opt, gap_opt, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
 }
 
-TOMA_API int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx, void *A, float *Z, void *Xm,
-                        void *ws, size_t ws_bytes, void *stream) {
+// The block map travels with (A, Z): required exactly when the shape uses one.
+static int check_map(const Workspace &w, const void *amap) {
+  if (w.occ_bytes != 0 && !amap) return TOMA_ERR_NULL;
+  if (amap && misaligned(amap, 16)) return TOMA_ERR_ALIGN;
+  return TOMA_OK;
+}
+
+TOMA_API size_t toma_map_bytes(const toma_desc *desc) {
+  Shape s;
+  Workspace w;
+  if (make_shape(desc, nullptr, &s) != TOMA_OK) return 0;
+  plan_workspace(s, &w);
+  return w.occ_bytes;
+}
+
+TOMA_API int toma_map_build(const toma_desc *desc, const void *A, void *amap, void *stream) {
+  Shape s; Workspace w;
+  int rc = make_shape(desc, nullptr, &s);
+  if (rc != TOMA_OK) return rc;
+  plan_workspace(s, &w);
+  if (!A) return TOMA_ERR_NULL;
+  if (misaligned(A, 16)) return TOMA_ERR_ALIGN;
+  rc = check_map(w, amap);
+  if (rc != TOMA_OK) return rc;
+  return launch_occupancy(s, A, static_cast<uint8_t *>(amap), w, static_cast<hipStream_t>(stream));
+}
+
+TOMA_API int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx, void *A, float *Z, void *amap,
+                        void *Xm, void *ws, size_t ws_bytes, void *stream) {
   Shape s; Workspace w;
   int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
   if (rc != TOMA_OK) return rc;
   if (!X || !idx || !A || !Z || !Xm) return TOMA_ERR_NULL;
   if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Xm, 16) || misaligned(Z, 4) || misaligned(idx, 4))
     return TOMA_ERR_ALIGN;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  rc = launch_weights(s, X, idx, A, Z, static_cast<char *>(ws), w, st);
+  rc = check_map(w, amap);
   if (rc != TOMA_OK) return rc;
-  return launch_merge(s, X, A, Z, Xm, static_cast<char *>(ws), w, st);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t *occ = static_cast<uint8_t *>(amap);
+  rc = launch_weights(s, X, idx, A, Z, occ, static_cast<char *>(ws), w, st);
+  if (rc != TOMA_OK) return rc;
+  return launch_merge(s, X, A, Z, occ, Xm, static_cast<char *>(ws), w, st);
 }
 
-TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void *A, const float *Z, void *Xm,
-                               void *ws, size_t ws_bytes, void *stream) {
+TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void *A, const float *Z,
+                               const void *amap, void *Xm, void *ws, size_t ws_bytes, void *stream) {
   Shape s; Workspace w;
   int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
   if (rc != TOMA_OK) return rc;
   if (!X || !A || !Z || !Xm) return TOMA_ERR_NULL;
   if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Xm, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
-  rc = launch_occupancy(s, A, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+  rc = check_map(w, amap);
   if (rc != TOMA_OK) return rc;
-  return launch_merge(s, X, A, Z, Xm, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+  return launch_merge(s, X, A, Z, static_cast<const uint8_t *>(amap), Xm, static_cast<char *>(ws), w,
+                      static_cast<hipStream_t>(stream));
 }
 
 TOMA_API int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *Xm,
@@ -183,22 +220,22 @@ TOMA_API int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, cons
                        static_cast<hipStream_t>(stream));
 }
 
-TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *O, int32_t o_rows,
-                          void *Y, void *ws, size_t ws_bytes, void *stream) {
+TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *amap, const void *O,
+                          int32_t o_rows, void *Y, void *ws, size_t ws_bytes, void *stream) {
   Shape s; Workspace w;
   int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
   if (rc != TOMA_OK) return rc;
   if (!A || !Z || !O || !Y) return TOMA_ERR_NULL;
   if (o_rows < s.D) return TOMA_ERR_SHAPE;
   if (misaligned(A, 16) || misaligned(O, 16) || misaligned(Y, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
-  rc = launch_occupancy(s, A, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream));
+  rc = check_map(w, amap);
   if (rc != TOMA_OK) return rc;
-  return launch_unmerge(s, A, Z, O, o_rows, false, Y, static_cast<char *>(ws), w,
+  return launch_unmerge(s, A, Z, static_cast<const uint8_t *>(amap), O, o_rows, false, Y, static_cast<char *>(ws), w,
                         static_cast<hipStream_t>(stream));
 }
 
 TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse_flags, const void *X,
-                        const void *X_extra_opt, int32_t *idx, void *A, float *Z, const void *Wq,
+                        const void *X_extra_opt, int32_t *idx, void *A, float *Z, void *amap, const void *Wq,
                         const void *Wk, const void *Wv, const void *Wo_opt, void *Y, void *Y_extra_opt,
                         void *ws, size_t ws_bytes, void *stream) {
   if (!attn) return TOMA_ERR_NULL;
@@ -216,29 +253,28 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
       (X_extra_opt && misaligned(X_extra_opt, 16)) || (Y_extra_opt && misaligned(Y_extra_opt, 16)) ||
       (Wo_opt && misaligned(Wo_opt, 16)))
     return TOMA_ERR_ALIGN;
+  rc = check_map(w, amap);
+  if (rc != TOMA_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char *wsb = static_cast<char *>(ws);
+  uint8_t *occ = static_cast<uint8_t *>(amap);
   // Xm and O are internal to the layer and live in their own workspace sections.
   void *Xm = wsb + w.xm, *O = wsb + w.o;
   if (!reuse_idx) {
-    rc = launch_select(s, X, idx, nullptr, wsb, w, st);
+    rc = launch_select(s, X, idx, nullptr, nullptr, wsb, w, st);
     if (rc != TOMA_OK) return rc;
   }
-  if (!reuse_a) {
-    rc = launch_weights(s, X, idx, A, Z, wsb, w, st);
-  } else {
-    // the occupancy map of a cached A is rebuilt in every call: the workspace is scratch, only
-    // idx, A and Z persist
-    rc = launch_occupancy(s, A, wsb, w, st);
+  if (!reuse_a) {  // (a cached A comes with its map)
+    rc = launch_weights(s, X, idx, A, Z, occ, wsb, w, st);
+    if (rc != TOMA_OK) return rc;
   }
-  if (rc != TOMA_OK) return rc;
-  rc = launch_merge(s, X, A, Z, Xm, wsb, w, st);
+  rc = launch_merge(s, X, A, Z, occ, Xm, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   // inside the layer the attention writes its merged rows already divided by Z (the unmerge's
   // input), so no separate scaling pass runs; the extra-token rows stay as they are
   rc = launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, Z, wsb, w, st);
   if (rc != TOMA_OK) return rc;
-  rc = launch_unmerge(s, A, Z, O, s.L, true, Y, wsb, w, st);
+  rc = launch_unmerge(s, A, Z, occ, O, s.L, true, Y, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   if (s.T > 0) rc = launch_copy_extra(s, O, Y_extra_opt, st);
   return rc;

@@ -300,9 +300,6 @@ __device__ __forceinline__ void frag_load_kc_sw(Frag<float> &f, const float *til
   for (int i = 0; i < 4; i++) { f.v[i] = a[i]; f.v[4 + i] = b[i]; }
 }
 
-// One load-to-LDS instruction: lane l's 16 bytes at gptr land at lds_chunk + 16 l.  Issued as
-// assembly so that the pipeline's own s_waitcnt vmcnt(n) (below) decides when a tile is complete;
-// the compiler's model would otherwise drain every outstanding load before each LDS read.
 // eight consecutive k starting at element kf of a row of PPR packets
 template <int PPR> __device__ __forceinline__ void frag_load_kcw_sw(Frag<bf16_t> &f, const bf16_t *tile, int row, int kf) {
   f.v = *reinterpret_cast<const bf16x8 *>(tile + SwzTile<bf16_t>::kcw<PPR>(row, kf >> 3));
@@ -314,6 +311,9 @@ template <int PPR> __device__ __forceinline__ void frag_load_kcw_sw(Frag<float> 
   for (int i = 0; i < 4; i++) { f.v[i] = a[i]; f.v[4 + i] = b[i]; }
 }
 
+// One load-to-LDS instruction: lane l's 16 bytes at gptr land at lds_chunk + 16 l.  Issued as
+// assembly so that the pipeline's own s_waitcnt vmcnt(n) (below) decides when a tile is complete;
+// the compiler's model would otherwise drain every outstanding load before each LDS read.
 template <typename T>
 __device__ __forceinline__ void load_to_lds16(const T *gptr, T *lds_chunk) {
   uint32_t lds_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds_chunk;

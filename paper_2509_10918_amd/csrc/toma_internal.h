@@ -21,9 +21,12 @@ struct Shape {
 
 // Offsets (bytes) of the scratch sections inside the caller's workspace.
 struct Workspace {
-  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, occ, total;
+  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, total;
   int stat_parts, z_parts;
-  int occ_db, occ_sb;  // occupancy map of A: blocks of kOccDest destinations x kOccSrc sources (0: not used)
+  // occupancy map of A, kept by the caller next to (A, Z): blocks of kOccDest destinations x kOccSrc
+  // sources per merge region (0: this shape uses none)
+  int occ_db, occ_sb;
+  size_t occ_bytes;
 };
 
 // Occupancy map of the stored merge weights.  With a small temperature almost every source token
@@ -113,23 +116,24 @@ int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s);
 void plan_workspace(const Shape &s, Workspace *w);
 
 // stage launchers (each returns a toma_status)
-int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, char *ws, const Workspace &w,
-                  hipStream_t st);
-// (also leaves the occupancy map of the new A in the workspace, see launch_occupancy)
-int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, char *ws,
+// gain, gap: optional outputs (null: not wanted)
+int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, float *gap, char *ws,
+                  const Workspace &w, hipStream_t st);
+// occ: the occupancy map that travels with (A, Z), w.occ_bytes bytes (null iff the shape uses none).
+// launch_weights writes it along with A and Z; launch_occupancy rebuilds it from a stored A;
+// launch_merge / launch_unmerge read it.
+int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, uint8_t *occ, char *ws,
                    const Workspace &w, hipStream_t st);
-// fills the occupancy map of A in the workspace (no-op when the shape does not use one); this or
-// launch_weights must run, in the same call, before launch_merge / launch_unmerge
-int launch_occupancy(const Shape &s, const void *A, char *ws, const Workspace &w, hipStream_t st);
-int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, char *ws,
-                 const Workspace &w, hipStream_t st);
+int launch_occupancy(const Shape &s, const void *A, uint8_t *occ, const Workspace &w, hipStream_t st);
+int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, const uint8_t *occ, void *Xm,
+                 char *ws, const Workspace &w, hipStream_t st);
 // Zs (optional): divide the merged rows of O by max(Z, 1e-20) on the way out (the unmerge input)
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
                   const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
                   hipStream_t st);
 // prescaled: the merged rows of O were already divided by Z (see launch_attend)
-int launch_unmerge(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, bool prescaled,
-                   void *Y, char *ws, const Workspace &w, hipStream_t st);
+int launch_unmerge(const Shape &s, const void *A, const float *Z, const uint8_t *occ, const void *O, int o_rows,
+                   bool prescaled, void *Y, char *ws, const Workspace &w, hipStream_t st);
 int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t st);
 // Out = gelu(In W1) W2 on `rows` rows; Hbuf is [rows, hidden] scratch of the same dtype
 int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const void *W1, const void *W2, void *Hbuf,
@@ -143,7 +147,10 @@ enum KernelId { K_GRAM = 0, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE
 struct KernelTimer {
   KernelTimer(int id, hipStream_t st);
   ~KernelTimer();
-  int slot;
+  KernelTimer(const KernelTimer &) = delete;
+  KernelTimer &operator=(const KernelTimer &) = delete;
+  int id;           // -1: profiling was off at construction
+  hipEvent_t a, b;
   hipStream_t st;
 };
 

@@ -666,13 +666,12 @@ __global__ __launch_bounds__(256) void k_occupancy(const char *__restrict__ A, u
   if (tid < NB && sblk < occ_sb) occ[((size_t)z * occ_db + dblk) * occ_sb + sblk] = any[tid] ? 1 : 0;
 }
 
-int launch_occupancy(const Shape &s, const void *A, char *ws, const Workspace &w, hipStream_t st) {
+int launch_occupancy(const Shape &s, const void *A, uint8_t *occ, const Workspace &w, hipStream_t st) {
   if (w.occ_sb == 0) return TOMA_OK;
   const int es = s.dtype == TOMA_BF16 ? 2 : 4;
   const int row_packets = s.Nr * es / 16;
   constexpr int wide = 32;  // packets of a row per workgroup (128, 64 and 16 measured slower)
   const dim3 grid((row_packets + wide - 1) / wide, w.occ_db, s.B * s.R);
-  uint8_t *occ = reinterpret_cast<uint8_t *>(ws + w.occ);
   KernelTimer kt(K_OCC, st);
   const char *Ab = static_cast<const char *>(A);
   if (es == 2)
@@ -694,8 +693,8 @@ template <typename T> static RegionView<T> make_view(const Shape &s, const void 
 }
 
 template <typename T>
-static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, char *ws,
-                         const Workspace &w, hipStream_t st) {
+static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, uint8_t *occ_out,
+                         char *ws, const Workspace &w, hipStream_t st) {
   int batch = s.B * s.R;
   const int zr = s.B * s.D;
   float *zpart = reinterpret_cast<float *>(ws + w.zpart);
@@ -704,7 +703,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
     const dim3 grid(s.Nr / 32, batch);
     // the kernel fills the occupancy map itself when a wave's slice of destinations is whole blocks
     const bool own_map = w.occ_sb != 0 && (s.Dr / 8) % kOccDest == 0;
-    uint8_t *occ = own_map ? reinterpret_cast<uint8_t *>(ws + w.occ) : nullptr;
+    uint8_t *occ = own_map ? occ_out : nullptr;
     {
       KernelTimer kt(K_WWRITE, st);
       switch (s.Dr / 128) {
@@ -727,7 +726,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
       hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, zpart, Z, zr, w.z_parts, s.Nr / 32);
     }
     if (launch_status() != TOMA_OK) return TOMA_ERR_LAUNCH;
-    return own_map ? TOMA_OK : launch_occupancy(s, A, ws, w, st);
+    return own_map ? TOMA_OK : launch_occupancy(s, A, occ_out, w, st);
   }
   WeightsPol<T, false> p1{};
   p1.v = make_view<T>(s, X);
@@ -739,7 +738,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   // the write pass fills the occupancy map too (every wave tile lies inside one block of
   // destinations: the wave slices of the planner's tiles divide kOccDest); k_lse zeroes it first
   const bool own_map = w.occ_sb != 0;
-  uint8_t *occ = own_map ? reinterpret_cast<uint8_t *>(ws + w.occ) : nullptr;
+  uint8_t *occ = own_map ? occ_out : nullptr;
   const size_t occ_words = own_map ? ((size_t)batch * w.occ_db * w.occ_sb + 3) / 4 : 0;
   { KernelTimer kt(K_LSE, st);
     hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n,
@@ -757,33 +756,33 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   return launch_status();
 }
 
-int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, char *ws,
+int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, uint8_t *occ, char *ws,
                    const Workspace &w, hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? weights_typed<bf16_t>(s, X, idx, A, Z, ws, w, st)
-                              : weights_typed<float>(s, X, idx, A, Z, ws, w, st);
+  return s.dtype == TOMA_BF16 ? weights_typed<bf16_t>(s, X, idx, A, Z, occ, ws, w, st)
+                              : weights_typed<float>(s, X, idx, A, Z, occ, ws, w, st);
 }
 
 template <typename T>
-static int merge_typed(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, char *ws,
-                       const Workspace &w, hipStream_t st) {
+static int merge_typed(const Shape &s, const void *X, const void *A, const float *Z, const uint8_t *occ, void *Xm,
+                       char *ws, const Workspace &w, hipStream_t st) {
   MergePol<T> p{};
   p.v = make_view<T>(s, X);
   p.A = static_cast<const T *>(A); p.lda = s.Nr; p.Z = Z; p.Xm = static_cast<T *>(Xm);
-  p.occ = OccMap{w.occ_sb ? reinterpret_cast<const uint8_t *>(ws + w.occ) : nullptr, w.occ_db, w.occ_sb};
+  p.occ = OccMap{w.occ_sb ? occ : nullptr, w.occ_db, w.occ_sb};
   p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_MERGE, p, s.Dr, s.C, s.Nr, s.B * s.R, st);
   return launch_status();
 }
 
-int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, void *Xm, char *ws,
-                 const Workspace &w, hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? merge_typed<bf16_t>(s, X, A, Z, Xm, ws, w, st)
-                              : merge_typed<float>(s, X, A, Z, Xm, ws, w, st);
+int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, const uint8_t *occ, void *Xm,
+                 char *ws, const Workspace &w, hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? merge_typed<bf16_t>(s, X, A, Z, occ, Xm, ws, w, st)
+                              : merge_typed<float>(s, X, A, Z, occ, Xm, ws, w, st);
 }
 
 template <typename T>
-static int unmerge_typed(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, bool prescaled,
-                         void *Y, char *ws, const Workspace &w, hipStream_t st) {
+static int unmerge_typed(const Shape &s, const void *A, const float *Z, const uint8_t *occ, const void *O, int o_rows,
+                         bool prescaled, void *Y, char *ws, const Workspace &w, hipStream_t st) {
   UnmergePol<T> p{};
   if (prescaled) {
     p.Os = static_cast<const T *>(O); p.os_rows = o_rows;
@@ -797,16 +796,16 @@ static int unmerge_typed(const Shape &s, const void *A, const float *Z, const vo
   }
   p.v = make_view<T>(s, nullptr);
   p.A = static_cast<const T *>(A); p.lda = s.Nr; p.Y = static_cast<T *>(Y);
-  p.occ = OccMap{w.occ_sb ? reinterpret_cast<const uint8_t *>(ws + w.occ) : nullptr, w.occ_db, w.occ_sb};
+  p.occ = OccMap{w.occ_sb ? occ : nullptr, w.occ_db, w.occ_sb};
   p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_UNMERGE, p, s.Nr, s.C, s.Dr, s.B * s.R, st);
   return launch_status();
 }
 
-int launch_unmerge(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, bool prescaled,
-                   void *Y, char *ws, const Workspace &w, hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? unmerge_typed<bf16_t>(s, A, Z, O, o_rows, prescaled, Y, ws, w, st)
-                              : unmerge_typed<float>(s, A, Z, O, o_rows, prescaled, Y, ws, w, st);
+int launch_unmerge(const Shape &s, const void *A, const float *Z, const uint8_t *occ, const void *O, int o_rows,
+                   bool prescaled, void *Y, char *ws, const Workspace &w, hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? unmerge_typed<bf16_t>(s, A, Z, occ, O, o_rows, prescaled, Y, ws, w, st)
+                              : unmerge_typed<float>(s, A, Z, occ, O, o_rows, prescaled, Y, ws, w, st);
 }
 
 int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t st) {

@@ -1,4 +1,5 @@
 // Profiling aid: per-kernel HIP-event timing of the library's own launches (see toma.h).
+#include <atomic>
 #include <mutex>
 #include <string.h>
 #include <vector>
@@ -12,7 +13,7 @@ static const char *const kNames[K_COUNT] = {"gram", "greedy", "weights_stats", "
                                             "unmerge", "copy_extra", "split_finish", "mlp_up", "mlp_down", "occupancy"};
 struct Rec { int id; hipEvent_t a, b; };
 static std::mutex g_mu;
-static bool g_on = false;
+static std::atomic<bool> g_on{false};
 static std::vector<Rec> g_recs;
 static std::vector<hipEvent_t> g_pool;
 static int g_launches[K_COUNT];
@@ -25,20 +26,31 @@ static hipEvent_t take_event() {
   return e;
 }
 
-KernelTimer::KernelTimer(int id, hipStream_t s) : slot(-1), st(s) {
-  if (!g_on) return;
-  std::lock_guard<std::mutex> lk(g_mu);
-  Rec r{id, take_event(), take_event()};
-  if (!r.a || !r.b) return;
-  (void)hipEventRecord(r.a, st);
-  g_recs.push_back(r);
-  slot = (int)g_recs.size() - 1;
+// The timer owns its two events from construction to destruction and hands the finished pair over
+// only then: a toma_profile_read / toma_profile_enable from another thread in between finds either
+// nothing of this launch or all of it.
+KernelTimer::KernelTimer(int id_, hipStream_t s) : id(-1), a(nullptr), b(nullptr), st(s) {
+  if (!g_on.load(std::memory_order_relaxed)) return;
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    a = take_event();
+    b = take_event();
+    if (!a || !b) {
+      if (a) g_pool.push_back(a);
+      if (b) g_pool.push_back(b);
+      a = b = nullptr;
+      return;
+    }
+  }
+  id = id_;
+  (void)hipEventRecord(a, st);
 }
 
 KernelTimer::~KernelTimer() {
-  if (slot < 0) return;
+  if (id < 0) return;
+  (void)hipEventRecord(b, st);
   std::lock_guard<std::mutex> lk(g_mu);
-  if (slot < (int)g_recs.size()) (void)hipEventRecord(g_recs[slot].b, st);
+  g_recs.push_back(Rec{id, a, b});
 }
 
 static void collect() {
@@ -62,7 +74,7 @@ using namespace toma;
 TOMA_API int toma_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_mu);
   collect();
-  g_on = on != 0;
+  g_on.store(on != 0);
   for (int i = 0; i < K_COUNT; i++) { g_launches[i] = 0; g_ms[i] = 0.0; }
   return TOMA_OK;
 }

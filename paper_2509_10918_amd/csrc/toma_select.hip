@@ -4,7 +4,7 @@
 // Two kernels:
 //   k_gram    S = cos(x_i, x_j) per region with the fp64 matrix cores (v_mfma_f64_16x16x4_f64):
 //             products of stored bf16 / fp32 values are exact in double, so S is the similarity
-//             to ~1e-16 before it is rounded once to the nearest multiple of 2^-22 and stored as
+//             to ~1e-16 before it is rounded once to the nearest multiple of 2^-30 and stored as
 //             a 32-bit integer.  From there on every sum and comparison of the greedy loop is
 //             exact integer arithmetic: the picks do not depend on any summation order, and
 //             mathematically tied candidates (common: two tokens that only improve each other's
@@ -17,9 +17,12 @@
 
 namespace toma {
 
-// Similarities are decided on a grid of 2^-22: |S| <= 1, so a 256-term sum of differences
-// max(0, S_ij - m_j) <= 2^23 stays below 2^31 and is exact in a 32-bit integer.
-constexpr double kSimScale = 4194304.0;
+// Similarities are decided on a grid of 2^-30: |S| <= 1 fits a 32-bit integer, a difference
+// max(0, S_ij - m_j) <= 2^31 an unsigned one, and sums of up to 256 of them are kept in 64 bits.
+// The grid is what makes mathematically tied candidates exact ties; it is fine enough that
+// rounding to it does not decide between candidates that are not tied (a row's value moves by at
+// most 2^-31 per term, below 1e-6 of any value above 2.4e-4 even with all 256 terms adverse).
+constexpr double kSimScale = 1073741824.0;
 
 // ------------------------------------------------------------------------------------------------
 // One wave per 16 x 16 block of one region's similarity matrix.  S is symmetric: only blocks on or
@@ -145,9 +148,10 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
 // ------------------------------------------------------------------------------------------------
 // Greedy facility location, one workgroup per (sample, region): exact, with incremental gains.
 //
-// Arithmetic.  S is on a grid of 2^-22 (kSimScale): a term max(0, S_ij - m_j) is at most 2^23 and a
-// 256-term sum fits an unsigned 32-bit register, so values, sums and comparisons are plain 32-bit
-// integer instructions, independent of any summation order.
+// Arithmetic.  S is on a grid of 2^-30 (kSimScale) and fits a 32-bit register; a term
+// max(0, S_ij - m_j) is at most 2^31 and a 256-term sum at most 2^39, so the rows' values are 64-bit
+// integers: values, sums and comparisons are plain integer instructions, independent of any
+// summation order.
 // Incremental gains.  After a pick t only the columns j with S_tj > m_j change their coverage, and
 // the value of row i drops by exactly  sum over those j of  med(S_ij, m_j, m_j') - m_j  (m' the new
 // coverage).  Because the arithmetic is exact, subtracting these differences keeps every row's value
@@ -163,13 +167,16 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
 // relative to the wave-uniform column number (scalar branches cost far more here than indexing).
 // Exchange, two barriers per round.  The rows' comparison keys (value + 1; 0 = picked or absent)
 // live in LDS.  (1) Every wave reads all keys (RPL per lane) and finds the same argmax t on its own
-// (one DPP reduction and a ballot: lanes are in row order, so the lowest lane among equals holds the
-// lowest index).  By symmetry the owner of column t holds the whole row t, one word per (lane, v):
-// it posts the row to LDS, ordered so that every wave then reads its own columns as one contiguous
-// run.  Barrier.  (2) Each wave subtracts its rows' decreases from the keys with integer LDS
-// atomics (they commute, so the result does not depend on their order).  A picked row's value falls
-// to exactly zero with its own pick's decrease; one more atomic takes away the + 1, which leaves
-// key 0 for good.  Barrier.
+// (the high words first, then the low words of the rows that hold the largest high word: two DPP
+// reductions and a ballot; lanes are in row order, so the lowest lane among equals holds the lowest
+// index).  By symmetry the owner of column t holds the whole row t, one word per (lane, v): it posts
+// the row to LDS, ordered so that every wave then reads its own columns as one contiguous run.
+// Barrier.  (2) Each wave subtracts its rows' decreases from the keys with integer LDS atomics (they
+// commute, so the result does not depend on their order).  A picked row's value falls to exactly
+// zero with its own pick's decrease; one more atomic takes away the + 1, which leaves key 0 for
+// good.  Barrier.
+// GAP: wave 0 also finds the largest key among the rows other than the pick (the runner-up) and
+// records the difference; the other waves skip it.
 // ------------------------------------------------------------------------------------------------
 template <int CTRL, int ROW_MASK = 0xf> __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
@@ -186,20 +193,33 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
   return max(max(a, b), max(c, d));
 }
+// max over the 64 lanes of 64-bit keys: the largest high word, then the largest low word among its
+// holders; the result is uniform
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t k) {
+  const uint32_t hi = (uint32_t)(k >> 32), lo = (uint32_t)k;
+  const uint32_t top_hi = wave_max_u32(hi);
+  const uint32_t top_lo = wave_max_u32(hi == top_hi ? lo : 0u);
+  return ((uint64_t)top_hi << 32) | top_lo;
+}
 
-template <int NT>
+constexpr uint64_t kNoRunnerUp = ~0ull;  // recorded gap when the pick was the last candidate
+
+template <int NT, bool GAP>
 __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *__restrict__ S,
                                                              int32_t *__restrict__ idx,
-                                                             float *__restrict__ gain_out, RegionMap map,
+                                                             float *__restrict__ gain_out,
+                                                             float *__restrict__ gap_out, RegionMap map,
                                                              int P, int d_loc) {
   constexpr int NL = 16 * NT;          // tokens in the region
   constexpr int NW = (NT + 1) / 2;     // waves, up to 32 columns each
   constexpr int RPL = (NL + 63) / 64;  // rows per lane: lane l holds rows RPL l .. RPL l + RPL - 1
-  constexpr int32_t kPad = 1 << 23;    // coverage of a padding column: above every S, so it never changes
-  constexpr int32_t kFloor = -(1 << 22);  // similarity -1: the coverage before the first pick
-  __shared__ uint32_t keys[RPL * 64];     // [64 v + l]: value + 1 of row RPL l + v, 0 once picked
-  __shared__ int32_t rowt[NW * 32];       // row t, column NW c + w at [32 w + c]
-  __shared__ int32_t picks[2][RPL * 64];  // [0] row, [1] value of every pick
+  constexpr int32_t kPad = (1 << 30) + 1;  // coverage of a padding column: above every S, so it never changes
+  constexpr int32_t kFloor = -(1 << 30);   // similarity -1: the coverage before the first pick
+  __shared__ uint64_t keys[RPL * 64];      // [64 v + l]: value + 1 of row RPL l + v, 0 once picked
+  __shared__ int32_t rowt[NW * 32];        // row t, column NW c + w at [32 w + c]
+  __shared__ int32_t pick_row[RPL * 64];   // row of every pick
+  __shared__ uint64_t pick_val[RPL * 64];  // its value
+  __shared__ uint64_t pick_gap[GAP ? RPL * 64 : 1];  // its lead over the runner-up
 
   const int bp = blockIdx.x, p = bp % P;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, cl = lane & 31;
@@ -225,8 +245,10 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
       }
     }
   }
-  const bool col_ok = NW * cl + w < NL;
-  int32_t m = col_ok ? kFloor : kPad;  // coverage of column NW cl + w (lanes l and l + 32 hold the same)
+  // this lane keeps the coverage of column NW cl + w (lanes l and l + 32 hold the same; only the
+  // first 32 report changes, and never for a column past the region's end)
+  const bool col_ok = NW * cl + w < NL, reports = col_ok && lane < 32;
+  int32_t m = col_ok ? kFloor : kPad;
   // where this lane's rows go in rowt (as columns, by symmetry)
   int post_at[RPL];
 #pragma unroll
@@ -236,31 +258,35 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
   }
 
   auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+  auto key_add = [&](int at, uint64_t by) {
+    __hip_atomic_fetch_add(&keys[at], by, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  };
 
-  // keys under the starting coverage: 1 + sum_j (S_ij + 1)
+  // keys under the starting coverage: 1 + sum_j (S_ij + 1); the slots of row t that stand for
+  // columns past the region's end are never posted: they start, and stay, at zero
   for (int i = threadIdx.x; i < RPL * 64; i += 64 * NW) keys[i] = RPL * (i & 63) + (i >> 6) < NL ? 1u : 0u;
+  for (int i = threadIdx.x; i < NW * 32; i += 64 * NW) rowt[i] = 0;
   lds_barrier();
 #pragma unroll
   for (int v = 0; v < RPL; v++) {
-    uint32_t part = 0;
+    uint64_t part = 0;
 #pragma unroll
     for (int c = 0; c < 32; c++)
       if (NW * c + w < NL) part += (uint32_t)(sv[v][c] - kFloor);
-    if (RPL * lane + v < NL)
-      __hip_atomic_fetch_add(&keys[64 * v + lane], part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (RPL * lane + v < NL) key_add(64 * v + lane, part);
   }
   lds_barrier();
 
   for (int step = 0; step < d_loc; step++) {
     // ---- argmax of the keys (lowest index among equals) ----
-    uint32_t bk = 0;
+    uint64_t kv[RPL], bk = 0;
     int bv = 0;
 #pragma unroll
     for (int v = 0; v < RPL; v++) {
-      const uint32_t key = keys[64 * v + lane];
-      if (v == 0 || key > bk) { bk = key; bv = v; }
+      kv[v] = keys[64 * v + lane];
+      if (v == 0 || kv[v] > bk) { bk = kv[v]; bv = v; }
     }
-    const uint32_t top = wave_max_u32(bk);
+    const uint64_t top = wave_max_u64(bk);
     const int tl = __builtin_ctzll(__ballot(bk == top));
     const int tv = __builtin_amdgcn_readlane(bv, tl);
     const int t = RPL * tl + tv;
@@ -272,48 +298,58 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
       for (int v = 0; v < RPL; v++)
         if (post_at[v] >= 0) rowt[post_at[v]] = sv[v][ct];
     }
-    if (threadIdx.x == 0) { picks[0][step] = t; picks[1][step] = (int32_t)(top - 1u); }
+    if (threadIdx.x == 0) { pick_row[step] = t; pick_val[step] = top - 1u; }
+    if constexpr (GAP) {
+      if (w == 0) {  // the largest key among the other rows
+        uint64_t sk = 0;
+#pragma unroll
+        for (int v = 0; v < RPL; v++) {
+          const uint64_t k = (lane == tl && v == tv) ? 0 : kv[v];
+          sk = k > sk ? k : sk;
+        }
+        const uint64_t second = wave_max_u64(sk);
+        if (lane == 0) pick_gap[step] = second ? top - second : kNoRunnerUp;
+      }
+    }
     lds_barrier();  // every wave has read the keys; row t is posted
 
     // ---- new coverage of the own columns; the changed ones lower the rows' values ----
-    if (threadIdx.x == 0)  // t is picked: its key ends at 0
-      __hip_atomic_fetch_add(&keys[64 * tv + tl], 0u - 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (threadIdx.x == 0) key_add(64 * tv + tl, ~0ull);  // t is picked: its key ends at 0
     const int32_t x = rowt[32 * w + cl];
     const int32_t m_old = m;
     m = max(m, x);
-    uint32_t changed = (uint32_t)__ballot(x > m_old && lane < 32);
+    uint32_t changed = (uint32_t)__ballot(reports && x > m_old);
     if (changed) {
-      int32_t dec[RPL];
+      uint64_t dec[RPL];
 #pragma unroll
       for (int v = 0; v < RPL; v++) dec[v] = 0;
-      int32_t sum_a = 0;
       do {
         const int c = __builtin_ctz(changed);
         changed &= changed - 1;
         const int32_t a = __builtin_amdgcn_readlane(m_old, c), b = __builtin_amdgcn_readlane(m, c);
-        sum_a += a;
 #pragma unroll
         for (int v = 0; v < RPL; v++) {
           // clamp to [a, b] (a < b) as one median instruction; at most one operand may be scalar
           int32_t cl3;
           const int32_t bvec = b;
           asm("v_med3_i32 %0, %1, %2, %3" : "=v"(cl3) : "v"(sv[v][c]), "s"(a), "v"(bvec));
-          dec[v] += cl3;
+          dec[v] += (uint32_t)(cl3 - a);
         }
       } while (changed);
 #pragma unroll
       for (int v = 0; v < RPL; v++)
-        if (RPL * lane + v < NL)
-          __hip_atomic_fetch_add(&keys[64 * v + lane], (uint32_t)(sum_a - dec[v]), __ATOMIC_RELAXED,
-                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (RPL * lane + v < NL) key_add(64 * v + lane, 0ull - dec[v]);
     }
     lds_barrier();  // the keys are final for the next round; every wave has read row t
   }
   for (int k = threadIdx.x; k < d_loc; k += 64 * NW) {
-    idx[(size_t)bp * d_loc + k] = map.token(p, picks[0][k]);
+    const size_t at = (size_t)bp * d_loc + k;
+    idx[at] = map.token(p, pick_row[k]);
     // the first value is the row sum shifted by N_loc (coverage -1 everywhere)
-    const double val0 = (double)(uint32_t)picks[1][k] - (k == 0 ? (double)NL * 4194304.0 : 0.0);
-    if (gain_out) gain_out[(size_t)bp * d_loc + k] = (float)(val0 / kSimScale);
+    const double val = (double)pick_val[k] - (k == 0 ? (double)NL * kSimScale : 0.0);
+    if (gain_out) gain_out[at] = (float)(val / kSimScale);
+    if constexpr (GAP)
+      gap_out[at] = pick_gap[k] == kNoRunnerUp ? __builtin_inff() : (float)((double)pick_gap[k] / kSimScale);
   }
 }
 
@@ -328,8 +364,8 @@ static int gram_k_split(const Shape &s) {
 }
 
 template <typename T>
-static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, char *ws, const Workspace &w,
-                        hipStream_t st) {
+static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, float *gap, char *ws,
+                        const Workspace &w, hipStream_t st) {
   int32_t *S = reinterpret_cast<int32_t *>(ws + w.sim);
   RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
   const int tiles = s.n_loc / 16, units = tiles * (tiles + 1) / 2;
@@ -343,10 +379,14 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, c
   int regions = s.B * s.P;
   KernelTimer kt(K_GREEDY, st);
   switch (s.n_loc / 16) {
-#define TOMA_GREEDY_CASE(NT)                                                                              \
-  case NT:                                                                                                \
-    hipLaunchKernelGGL(k_greedy<NT>, dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, map, s.P, \
-                       s.d_loc);                                                                           \
+#define TOMA_GREEDY_CASE(NT)                                                                               \
+  case NT:                                                                                                 \
+    if (gap)                                                                                               \
+      hipLaunchKernelGGL((k_greedy<NT, true>), dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, gap, \
+                         map, s.P, s.d_loc);                                                               \
+    else                                                                                                   \
+      hipLaunchKernelGGL((k_greedy<NT, false>), dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, gap, \
+                         map, s.P, s.d_loc);                                                               \
     break;
     TOMA_GREEDY_CASE(1)
     TOMA_GREEDY_CASE(2)
@@ -371,10 +411,10 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, c
   return launch_status();
 }
 
-int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, char *ws, const Workspace &w,
-                  hipStream_t st) {
-  if (s.dtype == TOMA_BF16) return select_typed<bf16_t>(s, static_cast<const bf16_t *>(X), idx, gain, ws, w, st);
-  return select_typed<float>(s, static_cast<const float *>(X), idx, gain, ws, w, st);
+int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, float *gap, char *ws,
+                  const Workspace &w, hipStream_t st) {
+  if (s.dtype == TOMA_BF16) return select_typed<bf16_t>(s, static_cast<const bf16_t *>(X), idx, gain, gap, ws, w, st);
+  return select_typed<float>(s, static_cast<const float *>(X), idx, gain, gap, ws, w, st);
 }
 
 }  // namespace toma

@@ -59,24 +59,39 @@ def test_argument_errors_are_reported_before_any_launch():
     need = tb.toma_workspace_bytes(d, a)
     ws = 256 * 1024          # fake but aligned addresses: nothing is dereferenced on these paths
     x = 1 << 20
-    assert L.toma_select(None, x, x, None, ws, need, None) == 1
-    assert L.toma_select(dp, None, x, None, ws, need, None) == 1
-    assert L.toma_select(dp, x, x, None, None, need, None) == 1
-    assert L.toma_select(dp, x, x, None, ws + 16, need, None) == 3
-    assert L.toma_select(dp, x + 8, x, None, ws, need, None) == 3
-    assert L.toma_select(dp, x, x, None, ws, tb.toma_workspace_bytes(d, None) - 1, None) == 4
-    assert L.toma_layer(dp, ap, 0, x, None, x, x, x, x, x, x, None, x, None, ws, need - 1, None) == 4
+    assert L.toma_select(None, x, x, None, None, ws, need, None) == 1
+    assert L.toma_select(dp, None, x, None, None, ws, need, None) == 1
+    assert L.toma_select(dp, x, x, None, None, None, need, None) == 1
+    assert L.toma_select(dp, x, x, None, None, ws + 16, need, None) == 3
+    assert L.toma_select(dp, x + 8, x, None, None, ws, need, None) == 3
+    assert L.toma_select(dp, x, x, x, x + 2, ws, need, None) == 3                # misaligned gap output
+    assert L.toma_select(dp, x, x, None, None, ws, tb.toma_workspace_bytes(d, None) - 1, None) == 4
+    assert L.toma_layer(dp, ap, 0, x, None, x, x, x, x, x, x, x, None, x, None, ws, need - 1, None) == 4
     bad = _d(tile_w=48)
-    assert L.toma_select(ctypes.addressof(bad), x, x, None, ws, need, None) == 2
+    assert L.toma_select(ctypes.addressof(bad), x, x, None, None, ws, need, None) == 2
     big = _d(tile_h=32, tile_w=32, d_loc=512)
-    assert L.toma_select(ctypes.addressof(big), x, x, None, ws, need, None) == 5
-    assert L.toma_merge(dp, x, x, None, x, x, ws, need, None) == 1
-    assert L.toma_merge_cached(dp, x, x, x, None, ws, need, None) == 1
+    assert L.toma_select(ctypes.addressof(big), x, x, None, None, ws, need, None) == 5
+    assert L.toma_merge(dp, x, x, None, x, x, x, ws, need, None) == 1
+    assert L.toma_merge_cached(dp, x, x, x, x, None, ws, need, None) == 1
+    # the block map travels with (A, Z): required exactly when the shape uses one (stale-cache misuse
+    # that the host can see: a missing or misaligned map)
+    assert tb.toma_map_bytes(d) > 0 and tb.toma_map_bytes(d) % 256 == 0
+    assert L.toma_merge(dp, x, x, x, x, None, x, ws, need, None) == 1
+    assert L.toma_merge_cached(dp, x, x, x, None, x, ws, need, None) == 1
+    assert L.toma_merge_cached(dp, x, x, x, x + 4, x, ws, need, None) == 3
+    assert L.toma_unmerge(dp, x, x, None, x, 2048, x, ws, need, None) == 1
+    assert L.toma_layer(dp, ap, 2, x, None, x, x, x, None, x, x, x, None, x, None, ws, need, None) == 1
+    assert L.toma_map_build(dp, x, None, None) == 1
+    assert L.toma_map_build(dp, None, x, None) == 1
+    small = _d(H=16, W=16, tile_h=8, tile_w=8, d_loc=32)     # short products: no map, NULL is fine
+    assert tb.toma_map_bytes(small) == 0
+    assert L.toma_merge_cached(ctypes.addressof(small), x, x, x, None, None, ws, need, None) == 1   # (Xm missing)
+    assert tb.toma_map_bytes(None) == 0
     assert L.toma_attend(dp, None, x, None, x, x, x, None, x, ws, need, None) == 1
     assert L.toma_attend(dp, ap, x, x, x, x, x, None, x, ws, need, None) == 1   # extra tokens given, t_extra == 0
-    assert L.toma_unmerge(dp, x, x, x, 100, x, ws, need, None) == 2             # fewer rows than D
-    assert L.toma_layer(dp, ap, 4, x, None, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
-    assert L.toma_layer(dp, ap, 0, x, None, None, x, x, x, x, x, None, x, None, ws, need, None) == 1
+    assert L.toma_unmerge(dp, x, x, x, x, 100, x, ws, need, None) == 2          # fewer rows than D
+    assert L.toma_layer(dp, ap, 4, x, None, x, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
+    assert L.toma_layer(dp, ap, 0, x, None, None, x, x, x, x, x, x, None, x, None, ws, need, None) == 1
     # feed-forward module: dtype, shape, divisibility, null and alignment checks
     assert L.toma_mlp(1, 4096, 640, 2560, x, x, x, x, None, None) == 1
     assert L.toma_mlp(1, 0, 640, 2560, x, x, x, x, x, None) == 2
@@ -92,11 +107,14 @@ def test_binding_raises_with_status():
 
 
 @pytest.mark.parametrize("H,W,th,tw,R", [(8, 12, 4, 4, 1), (8, 12, 4, 4, 6), (6, 8, 3, 8, 1), (16, 16, 16, 16, 1)])
-def test_source_tokens_enumerates_regions_in_local_order(H, W, th, tw, R):
-    """Column s of A: with one merge region, token s % N_loc of selection region s / N_loc; with one
-    merge region per selection region, token s of that region (Sec. 4.3.1's region / local index)."""
+def test_column_order_helper_of_the_gpu_tests(H, W, th, tw, R):
+    """The GPU tests compare the stored A with the oracle's through toma_gpu.source_tokens, which restates
+    the documented column order (toma_merge in toma.h): with one merge region, column s is token
+    s % N_loc of selection region s / N_loc; with one merge region per selection region, token s of
+    that region (Sec. 4.3.1's region / local index).  Checked here against the definition written out."""
+    import toma_gpu as tg
     d = tb.make_desc(1, H, W, 32, th, tw, 1, R, 0.1, "f32")
-    got = tb.source_tokens(d)
+    got = tg.source_tokens(d)
     pw, n_loc = W // tw, th * tw
     P = (H // th) * pw
     want = []

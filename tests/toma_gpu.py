@@ -24,6 +24,14 @@ def max_rel(got, ref):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
 
 
+def elem_excess(got, ref, tol):
+    """Element-wise reading of the same tolerance: the largest |err| / (tol |ref| + tol rms(ref)).
+    At most 1 when every element is within tol of its own reference value, give or take tol of the
+    tensor's typical magnitude (small entries of a tensor cannot hide behind its largest one)."""
+    rms = float(np.sqrt(np.mean(np.square(ref))))
+    return float((np.abs(got - ref) / (tol * np.abs(ref) + tol * max(rms, 1e-300))).max())
+
+
 def descs(w, merge_regions):
     d = tb.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, merge_regions, w.tau, w.dtype)
     a = tb.toma_attn_desc(w.heads, w.head_dim, w.T_extra)
@@ -34,13 +42,25 @@ def oracle_desc(oracle, w, merge_regions):
     return oracle.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, merge_regions, w.tau)
 
 
+def source_tokens(desc):
+    """Grid index (r * W + c) of every column of the stored A: int64 [merge_regions, N / merge_regions].
+    The library stores sources region by region, in local order inside a selection region (see
+    toma_merge in toma.h); this restates that layout for the comparisons with the oracle."""
+    pw = desc.W // desc.tile_w
+    P = (desc.H // desc.tile_h) * pw
+    n_loc = desc.tile_h * desc.tile_w
+    p, l = np.divmod(np.arange(P * n_loc), n_loc)
+    tok = ((p // pw) * desc.tile_h + l // desc.tile_w) * desc.W + (p % pw) * desc.tile_w + l % desc.tile_w
+    return tok.reshape(desc.merge_regions, -1)
+
+
 def a_in_oracle_order(desc, A):
     """The stored weights [B, R, Dr, Nr] with the source axis as the oracle has it: grid (row-major)
     order in global mode, local order per region in tile mode."""
     if desc.merge_regions != 1:
         return A
     out = np.empty_like(A)
-    out[..., tb.source_tokens(desc)[0]] = A
+    out[..., source_tokens(desc)[0]] = A
     return out
 
 
@@ -48,7 +68,7 @@ def a_in_stored_order(desc, A):
     """Inverse of a_in_oracle_order: an oracle-layout A as the library stores it."""
     if desc.merge_regions != 1:
         return A
-    return np.ascontiguousarray(A[..., tb.source_tokens(desc)[0]])
+    return np.ascontiguousarray(A[..., source_tokens(desc)[0]])
 
 
 class Device:
@@ -62,28 +82,37 @@ class Device:
         self.Xe = dev(inputs["X_extra"], dt) if inputs.get("X_extra") is not None else None
         self.Wq, self.Wk, self.Wv = (dev(inputs[k], dt) for k in ("Wq", "Wk", "Wv"))
         self.ws = tb.alloc_workspace(self.desc, self.attn)
-        self.idx, self.A, self.Z = tb.alloc_cache(self.desc)
+        self.idx, self.A, self.Z, self.amap = tb.alloc_cache(self.desc)
         tdt = tb.torch_dtype(self.desc)
         self.gain = torch.empty((w.B, w.P, w.d_loc), dtype=torch.float32, device="cuda")
+        self.gap = torch.empty((w.B, w.P, w.d_loc), dtype=torch.float32, device="cuda")
         self.Xm = torch.empty((w.B, w.D, w.C), dtype=tdt, device="cuda")
         self.O = torch.empty((w.B, w.D + w.T_extra, w.C), dtype=tdt, device="cuda")
         self.Y = torch.empty((w.B, w.N, w.C), dtype=tdt, device="cuda")
         self.Ye = torch.empty((w.B, w.T_extra, w.C), dtype=tdt, device="cuda") if w.T_extra else None
 
-    def select(self):
-        tb.toma_select(self.desc, self.X, self.idx, self.gain, self.ws)
+    def select(self, gap=True):
+        tb.toma_select(self.desc, self.X, self.idx, self.gain, self.gap if gap else None, self.ws)
         torch.cuda.synchronize()
         return self.idx.cpu().numpy()
 
     def merge(self, idx=None):
         if idx is not None:
             self.idx.copy_(torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)))
-        tb.toma_merge(self.desc, self.X, self.idx, self.A, self.Z, self.Xm, self.ws)
+        tb.toma_merge(self.desc, self.X, self.idx, self.A, self.Z, self.amap, self.Xm, self.ws)
         torch.cuda.synchronize()
         return a_in_oracle_order(self.desc, host(self.A)), host(self.Z), host(self.Xm)
 
+    def plant(self, A_oracle_order, Z):
+        """Put weights made elsewhere into the cache: A (oracle column order, values already in the
+        dtype), Z, and the block map rebuilt from that A."""
+        self.A.copy_(dev(a_in_stored_order(self.desc, A_oracle_order), self.w.dtype).reshape(self.A.shape))
+        self.Z.copy_(torch.from_numpy(np.ascontiguousarray(Z, dtype=np.float32)).reshape(self.Z.shape))
+        if self.amap is not None:
+            tb.toma_map_build(self.desc, self.A, self.amap)
+
     def merge_cached(self):
-        tb.toma_merge_cached(self.desc, self.X, self.A, self.Z, self.Xm, self.ws)
+        tb.toma_merge_cached(self.desc, self.X, self.A, self.Z, self.amap, self.Xm, self.ws)
         torch.cuda.synchronize()
         return host(self.Xm)
 
@@ -97,14 +126,14 @@ class Device:
     def unmerge(self, O=None):
         if O is not None:
             self.O.copy_(dev(O, self.w.dtype))
-        tb.toma_unmerge(self.desc, self.A, self.Z, self.O, self.Y, self.ws)
+        tb.toma_unmerge(self.desc, self.A, self.Z, self.amap, self.O, self.Y, self.ws)
         torch.cuda.synchronize()
         return host(self.Y)
 
     def layer(self, flags=0, X=None):
         if X is not None:
             self.X.copy_(dev(X, self.w.dtype))
-        tb.toma_layer(self.desc, self.attn, flags, self.X, self.Xe, self.idx, self.A, self.Z, self.Wq, self.Wk,
+        tb.toma_layer(self.desc, self.attn, flags, self.X, self.Xe, self.idx, self.A, self.Z, self.amap, self.Wq, self.Wk,
                       self.Wv, None, self.Y, self.Ye, self.ws)
         torch.cuda.synchronize()
         return host(self.Y), (host(self.Ye) if self.Ye is not None else None)
