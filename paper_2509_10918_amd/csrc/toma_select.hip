@@ -12,6 +12,8 @@
 //   k_greedy  one workgroup per (sample, region); the region's whole S (up to 256 x 256 words)
 //             lives in the workgroup's vector registers and the rows' values are kept up to date
 //             incrementally (see the comment at the kernel).
+#include <type_traits>
+
 #include "toma_common.h"
 #include "toma_internal.h"
 
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
 // Arithmetic.  S is on a grid of 2^-30 (kSimScale) and fits a 32-bit register; a term
 // max(0, S_ij - m_j) is at most 2^31 and a 256-term sum at most 2^39, so the rows' values are 64-bit
 // integers: values, sums and comparisons are plain integer instructions, independent of any
-// summation order.
+// summation order.  Only the first rounds have values of 4 or more; the rest run on 32-bit words.
 // Incremental gains.  After a pick t only the columns j with S_tj > m_j change their coverage, and
 // the value of row i drops by exactly  sum over those j of  med(S_ij, m_j, m_j') - m_j  (m' the new
 // coverage).  Because the arithmetic is exact, subtracting these differences keeps every row's value
@@ -216,6 +218,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
   constexpr int32_t kPad = (1 << 30) + 1;  // coverage of a padding column: above every S, so it never changes
   constexpr int32_t kFloor = -(1 << 30);   // similarity -1: the coverage before the first pick
   __shared__ uint64_t keys[RPL * 64];      // [64 v + l]: value + 1 of row RPL l + v, 0 once picked
+  __shared__ uint32_t keys32[RPL * 64];    // the same once every key fits 32 bits
   __shared__ int32_t rowt[NW * 32];        // row t, column NW c + w at [32 w + c]
   __shared__ int32_t pick_row[RPL * 64];   // row of every pick
   __shared__ uint64_t pick_val[RPL * 64];  // its value
@@ -258,9 +261,6 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
   }
 
   auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
-  auto key_add = [&](int at, uint64_t by) {
-    __hip_atomic_fetch_add(&keys[at], by, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-  };
 
   // keys under the starting coverage: 1 + sum_j (S_ij + 1); the slots of row t that stand for
   // columns past the region's end are never posted: they start, and stay, at zero
@@ -273,20 +273,40 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
 #pragma unroll
     for (int c = 0; c < 32; c++)
       if (NW * c + w < NL) part += (uint32_t)(sv[v][c] - kFloor);
-    if (RPL * lane + v < NL) key_add(64 * v + lane, part);
+    if (RPL * lane + v < NL)
+      __hip_atomic_fetch_add(&keys[64 * v + lane], part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
   lds_barrier();
 
-  for (int step = 0; step < d_loc; step++) {
+  // One round, with the keys as 64-bit (WIDE) or 32-bit words.  The winning value never grows from
+  // one round to the next (diminishing returns), so once the largest key fits 32 bits every key does
+  // for good, and no row's decrease in a round can exceed 32 bits either: the wide rounds (the first
+  // ten or so of a 256-token region) hand over to the narrow ones, which run on the low words.
+  // A wide round that finds the keys narrow enough returns true before it changes anything.
+  auto round = [&](auto wide_c, int step) -> bool {
+    constexpr bool WIDE = decltype(wide_c)::value;
+    using K = std::conditional_t<WIDE, uint64_t, uint32_t>;
+    auto key_at = [&](int at) -> K * {
+      if constexpr (WIDE) return &keys[at]; else return &keys32[at];
+    };
+    auto key_add = [&](int at, K by) {
+      __hip_atomic_fetch_add(key_at(at), by, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto wave_max = [&](K k) -> K {
+      if constexpr (WIDE) return wave_max_u64(k); else return wave_max_u32(k);
+    };
     // ---- argmax of the keys (lowest index among equals) ----
-    uint64_t kv[RPL], bk = 0;
+    K kv[RPL], bk = 0;
     int bv = 0;
 #pragma unroll
     for (int v = 0; v < RPL; v++) {
-      kv[v] = keys[64 * v + lane];
+      kv[v] = *key_at(64 * v + lane);
       if (v == 0 || kv[v] > bk) { bk = kv[v]; bv = v; }
     }
-    const uint64_t top = wave_max_u64(bk);
+    const K top = wave_max(bk);
+    if constexpr (WIDE) {
+      if ((top >> 32) == 0) return true;
+    }
     const int tl = __builtin_ctzll(__ballot(bk == top));
     const int tv = __builtin_amdgcn_readlane(bv, tl);
     const int t = RPL * tl + tv;
@@ -298,29 +318,29 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
       for (int v = 0; v < RPL; v++)
         if (post_at[v] >= 0) rowt[post_at[v]] = sv[v][ct];
     }
-    if (threadIdx.x == 0) { pick_row[step] = t; pick_val[step] = top - 1u; }
+    if (threadIdx.x == 0) { pick_row[step] = t; pick_val[step] = (uint64_t)top - 1u; }
     if constexpr (GAP) {
       if (w == 0) {  // the largest key among the other rows
-        uint64_t sk = 0;
+        K sk = 0;
 #pragma unroll
         for (int v = 0; v < RPL; v++) {
-          const uint64_t k = (lane == tl && v == tv) ? 0 : kv[v];
+          const K k = (lane == tl && v == tv) ? (K)0 : kv[v];
           sk = k > sk ? k : sk;
         }
-        const uint64_t second = wave_max_u64(sk);
-        if (lane == 0) pick_gap[step] = second ? top - second : kNoRunnerUp;
+        const K second = wave_max(sk);
+        if (lane == 0) pick_gap[step] = second ? (uint64_t)(top - second) : kNoRunnerUp;
       }
     }
     lds_barrier();  // every wave has read the keys; row t is posted
 
     // ---- new coverage of the own columns; the changed ones lower the rows' values ----
-    if (threadIdx.x == 0) key_add(64 * tv + tl, ~0ull);  // t is picked: its key ends at 0
+    if (threadIdx.x == 0) key_add(64 * tv + tl, ~(K)0);  // t is picked: its key ends at 0
     const int32_t x = rowt[32 * w + cl];
     const int32_t m_old = m;
     m = max(m, x);
     uint32_t changed = (uint32_t)__ballot(reports && x > m_old);
     if (changed) {
-      uint64_t dec[RPL];
+      K dec[RPL];
 #pragma unroll
       for (int v = 0; v < RPL; v++) dec[v] = 0;
       do {
@@ -338,9 +358,19 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
       } while (changed);
 #pragma unroll
       for (int v = 0; v < RPL; v++)
-        if (RPL * lane + v < NL) key_add(64 * v + lane, 0ull - dec[v]);
+        if (RPL * lane + v < NL) key_add(64 * v + lane, (K)0 - dec[v]);
     }
     lds_barrier();  // the keys are final for the next round; every wave has read row t
+    return false;
+  };
+
+  int step = 0;
+  for (; step < d_loc; step++)
+    if (round(std::true_type{}, step)) break;
+  if (step < d_loc) {
+    for (int i = threadIdx.x; i < RPL * 64; i += 64 * NW) keys32[i] = (uint32_t)keys[i];
+    lds_barrier();
+    for (; step < d_loc; step++) round(std::false_type{}, step);
   }
   for (int k = threadIdx.x; k < d_loc; k += 64 * NW) {
     const size_t at = (size_t)bp * d_loc + k;
