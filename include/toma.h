@@ -98,6 +98,25 @@ int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_
                 void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * toma_select for callers that cannot hand over or allocate a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid device allocation): the same selection, same
+ * arguments and results, with its scratch (the regions' similarity matrices, B * P * N_loc^2 32-bit
+ * words) in a buffer of TOMA_STATIC_SCRATCH_BYTES that is part of the library's device code and
+ * present once on every GPU.  No device memory is allocated or freed, at any call.
+ *   - Shapes whose similarity matrices exceed the buffer return TOMA_ERR_WORKSPACE (the SDXL-sized
+ *     layers fit: 2 x 16 regions of 256 tokens are 8 MiB; the 128 x 128 grid does not).
+ *   - The GPU the stream belongs to must be the current device of the calling thread.  The buffer's
+ *     address on that GPU is looked up on the first call there (TOMA_ERR_LAUNCH if the runtime
+ *     refuses).
+ *   - All calls on one GPU share the one buffer: calls that may overlap in time on a GPU (different
+ *     streams, different threads) race on it; order them.  Nothing in the buffer needs clearing
+ *     between calls (every similarity that is read was written by the same call).
+ */
+#define TOMA_STATIC_SCRATCH_BYTES (16u << 20)
+int toma_select_static(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt,
+                       float *gap_opt, void *stream);
+
+/*
  * Merge weights and merge (Sec. 4.2.1; Alg. 3 step 2).  Inside each merge region (all tokens
  * of the sample, or one region) with destinations j = rows idx of X and sources s:
  *   A_js = softmax over j of (logit_scale * <x_idx[j], x_s>)   per source s,

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libtoma.so")
 
 TOMA_F32, TOMA_BF16 = 0, 1
 TOMA_REUSE_IDX, TOMA_REUSE_A = 1, 2
-EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_merge", "toma_map_bytes",
+EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_select_static", "toma_merge", "toma_map_bytes",
            "toma_map_build", "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer", "toma_mlp", "toma_profile_enable",
            "toma_profile_kernel_name", "toma_profile_read")
 
@@ -65,6 +65,8 @@ def lib():
         L.toma_status_string.argtypes = [ctypes.c_int]
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
         L.toma_select.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_select_static.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.toma_select_static.restype = ctypes.c_int
         L.toma_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_map_bytes.restype = ctypes.c_size_t
         L.toma_map_bytes.argtypes = [vp]
@@ -133,6 +135,11 @@ def alloc_workspace(desc, attn=None, device="cuda"):
 def toma_select(desc, X, idx, gain, gap, ws):
     _check(lib().toma_select(_ref(desc), _ptr(X), _ptr(idx), _ptr(gain), _ptr(gap), _ptr(ws), ws.numel(),
                              _stream()), "toma_select")
+
+
+def toma_select_static(desc, X, idx, gain, gap):
+    _check(lib().toma_select_static(_ref(desc), _ptr(X), _ptr(idx), _ptr(gain), _ptr(gap), _stream()),
+           "toma_select_static")
 
 
 def toma_merge(desc, X, idx, A, Z, amap, Xm, ws):

@@ -2,6 +2,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "toma_internal.h"
 
@@ -172,6 +173,52 @@ TOMA_API int toma_map_build(const toma_desc *desc, const void *A, void *amap, vo
   rc = check_map(w, amap);
   if (rc != TOMA_OK) return rc;
   return launch_occupancy(s, A, static_cast<uint8_t *>(amap), w, static_cast<hipStream_t>(stream));
+}
+
+// ---- selection without a caller workspace ------------------------------------------------------
+// The selection's scratch (the regions' similarity matrices) in a buffer the library owns: a
+// file-scope device array, present once on every GPU the library's code is loaded on.  In host code
+// the array's name is only a handle; its device address on the current GPU comes from
+// hipGetSymbolAddress, asked once per device and kept.
+static __device__ __align__(256) unsigned char scratch[TOMA_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(char **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TOMA_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return TOMA_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<char *>(g_scratch_ptr[dev]);
+  return TOMA_OK;
+}
+
+TOMA_API int toma_select_static(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt, float *gap_opt,
+                                void *stream) {
+  Shape s; Workspace w;
+  int rc = make_shape(desc, nullptr, &s);
+  if (rc != TOMA_OK) return rc;
+  if (!X || !idx) return TOMA_ERR_NULL;
+  if (misaligned(X, 16) || misaligned(idx, 4) || (gain_opt && misaligned(gain_opt, 4)) ||
+      (gap_opt && misaligned(gap_opt, 4)))
+    return TOMA_ERR_ALIGN;
+  // the selection reads and writes only the similarity section: lay it out at the buffer's start
+  plan_workspace(s, &w);
+  const size_t need = up256((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(int32_t));
+  if (need > (size_t)TOMA_STATIC_SCRATCH_BYTES) return TOMA_ERR_WORKSPACE;
+  w.sim = 0;
+  char *buf = nullptr;
+  rc = static_scratch(&buf);
+  if (rc != TOMA_OK) return rc;
+  return launch_select(s, X, idx, gain_opt, gap_opt, buf, w, static_cast<hipStream_t>(stream));
 }
 
 TOMA_API int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx, void *A, float *Z, void *amap,
