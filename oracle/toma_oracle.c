@@ -469,6 +469,76 @@ ORACLE_API void toma_oracle_attend_rows(int B, int D, int T, int C, int heads, c
   free(U); free(K); free(V);
 }
 
+/* Cross-attention with the merged tokens as queries (Sec. 5.1: in the ToMA_once variant every module
+ * of a transformer block, cross-attention included, runs on the merged tokens between one merge and
+ * one unmerge).  Eq. 1 with tau = 1 and separate token sets: Q = U Wq from the Lq query tokens
+ * (U [B][Lq][C], Wq [C][C]); K = Ctx Wk, V = Ctx Wv from the Tc context tokens (Ctx [B][Tc][Cc],
+ * Wk, Wv [Cc][C]); head h owns channels [h*dh, (h+1)*dh); P = softmax over the context tokens of
+ * Q_h K_h^T / sqrt(dh); O_h = P V_h; heads concatenated; O = O Wo when Wo is given.  O is [B][Lq][C]. */
+ORACLE_API void toma_oracle_cross_attend(int B, int Lq, int Tc, int C, int Cc, int heads, const double *U,
+                                         const double *Ctx, const double *Wq, const double *Wk,
+                                         const double *Wv, const double *Wo, double *O) {
+  int dh = C / heads;
+  double *Q = (double *)malloc(sizeof(double) * (size_t)B * Lq * C);
+  double *K = (double *)malloc(sizeof(double) * (size_t)B * Tc * C);
+  double *V = (double *)malloc(sizeof(double) * (size_t)B * Tc * C);
+  double *Oh = (double *)malloc(sizeof(double) * (size_t)B * Lq * C);
+#pragma omp parallel for schedule(dynamic)
+  for (int r = 0; r < B * Lq; r++) {
+    double *q = Q + (size_t)r * C;
+    for (int n = 0; n < C; n++) q[n] = 0.0;
+    for (int c = 0; c < C; c++)
+      for (int n = 0; n < C; n++) q[n] += U[(size_t)r * C + c] * Wq[(size_t)c * C + n];
+  }
+#pragma omp parallel for schedule(dynamic)
+  for (int r = 0; r < B * Tc; r++) {
+    double *k = K + (size_t)r * C, *v = V + (size_t)r * C;
+    for (int n = 0; n < C; n++) { k[n] = 0.0; v[n] = 0.0; }
+    for (int c = 0; c < Cc; c++) {
+      double x = Ctx[(size_t)r * Cc + c];
+      for (int n = 0; n < C; n++) { k[n] += x * Wk[(size_t)c * C + n]; v[n] += x * Wv[(size_t)c * C + n]; }
+    }
+  }
+  double inv = 1.0 / sqrt((double)dh);
+#pragma omp parallel for schedule(dynamic)
+  for (int r = 0; r < B * Lq; r++) {
+    int b = r / Lq;
+    double *p = (double *)malloc(sizeof(double) * (size_t)Tc);
+    for (int h = 0; h < heads; h++) {
+      const double *q = Q + (size_t)r * C + (size_t)h * dh;
+      double mx = -INFINITY, den = 0.0;
+      for (int j = 0; j < Tc; j++) {
+        const double *k = K + ((size_t)b * Tc + j) * C + (size_t)h * dh;
+        double s = 0.0;
+        for (int c = 0; c < dh; c++) s += q[c] * k[c];
+        p[j] = s * inv;
+        if (p[j] > mx) mx = p[j];
+      }
+      for (int j = 0; j < Tc; j++) { p[j] = exp(p[j] - mx); den += p[j]; }
+      double *o = Oh + (size_t)r * C + (size_t)h * dh;
+      for (int c = 0; c < dh; c++) o[c] = 0.0;
+      for (int j = 0; j < Tc; j++) {
+        double wgt = p[j] / den;
+        const double *v = V + ((size_t)b * Tc + j) * C + (size_t)h * dh;
+        for (int c = 0; c < dh; c++) o[c] += wgt * v[c];
+      }
+    }
+    free(p);
+  }
+  if (Wo) {
+#pragma omp parallel for schedule(dynamic)
+    for (int r = 0; r < B * Lq; r++) {
+      double *o = O + (size_t)r * C;
+      for (int n = 0; n < C; n++) o[n] = 0.0;
+      for (int c = 0; c < C; c++)
+        for (int n = 0; n < C; n++) o[n] += Oh[(size_t)r * C + c] * Wo[(size_t)c * C + n];
+    }
+  } else {
+    memcpy(O, Oh, sizeof(double) * (size_t)B * Lq * C);
+  }
+  free(Q); free(K); free(V); free(Oh);
+}
+
 /* Sec. 4.2.2 (transpose unmerge): X'_unmerged = A~^T X', i.e. for source s of merge region rho
  * Y[token(rho, s)] = sum_{j in rho} A~_js O[j].  O is [B][o_rows][C] and only its first D rows
  * (the merged image tokens) are read; Y is [B][N][C] in grid order. */
@@ -494,7 +564,8 @@ ORACLE_API void toma_oracle_unmerge(const oracle_desc *d, const double *A, const
   free(token_of);
 }
 
-/* Sec. 4.2.2 (Moore-Penrose unmerge, the alternative the paper measures against): not built. */
+/* Sec. 4.2.2 (Moore-Penrose unmerge, the alternative the paper measures against): in toma_oracle.py
+ * (unmerge_pinv), where numpy's SVD-based pseudo-inverse serves as the step. */
 
 /* ---------------------------------------------------------------------------------------------
  * A feed-forward core module (Sec. 4.2: the module between merge and unmerge may be attention

@@ -176,6 +176,20 @@ def attend_rows(Xm, Xe, Wq, Wk, Wv, heads, rows):
     return out
 
 
+def cross_attend(U, Ctx, Wq, Wk, Wv, heads, Wo=None):
+    """Cross-attention: queries from U [B, Lq, C], keys and values from Ctx [B, Tc, Cc]."""
+    U, Ctx = _f64(U), _f64(Ctx)
+    B, Lq, C = U.shape
+    _, Tc, Cc = Ctx.shape
+    Wq, Wk, Wv = _f64(Wq), _f64(Wk), _f64(Wv)
+    assert Wq.shape == (C, C) and Wk.shape == (Cc, C) and Wv.shape == (Cc, C)
+    Wo_p = None if Wo is None else _f64(Wo)
+    O = np.empty((B, Lq, C), np.float64)
+    lib().toma_oracle_cross_attend(B, Lq, Tc, C, Cc, heads, _d(U), _d(Ctx), _d(Wq), _d(Wk), _d(Wv),
+                                   None if Wo_p is None else _d(Wo_p), _d(O))
+    return O
+
+
 def mlp(X, W1, W2):
     """gelu(X W1) W2 on the rows of X (any leading shape)."""
     X, W1, W2 = _f64(X), _f64(W1), _f64(W2)
@@ -192,6 +206,50 @@ def unmerge(d, A, Z, O):
     Y = np.empty((d.B, N, d.C), np.float64)
     lib().toma_oracle_unmerge(ctypes.byref(d), _d(A), _d(Z), _d(O), O.shape[1], _d(Y))
     return Y
+
+
+def _merge_region_tokens(d):
+    """[R, Nr] grid index of source s of merge region rho, in the order the oracle's A has its columns."""
+    N, R = d.H * d.W, d.merge_regions
+    if R == 1:
+        return np.arange(N, dtype=np.int64).reshape(1, N)
+    _, _, token_of = region_map(d.H, d.W, d.tile_h, d.tile_w)
+    return token_of.astype(np.int64)
+
+
+def unmerge_pinv(d, A, Z, O, rcond):
+    """Sec. 4.2.2, first display: X'_unmerged = A~^+ X' with A~^+ the Moore-Penrose pseudo-inverse of the
+    row-normalised merge matrix A~ = A / Z of each merge region (for rows of full rank this is
+    A~^T (A~ A~^T)^-1, the closed form the paper prints).  The pseudo-inverse is numpy's
+    (SVD; singular values <= rcond * largest are treated as zero - the paper does not name a cut-off,
+    so it is an argument).  O is [B, o_rows, C], rows [0, D) are used; Y is [B, N, C] in grid order."""
+    A, Z, O = _f64(A), _f64(Z), _f64(O)
+    R = d.merge_regions
+    D, Dr = A.shape[1] * A.shape[2], A.shape[2]
+    tok = _merge_region_tokens(d)
+    Y = np.zeros((d.B, d.H * d.W, O.shape[2]), np.float64)
+    for b in range(d.B):
+        for rho in range(R):
+            z = np.maximum(Z[b, rho * Dr:(rho + 1) * Dr], 1e-20)
+            At = A[b, rho] / z[:, None]
+            Y[b, tok[rho]] = np.linalg.pinv(At, rcond=rcond) @ O[b, rho * Dr:(rho + 1) * Dr]
+    return Y
+
+
+def merge_matrix_spectrum(d, A, Z):
+    """Per (sample, merge region): singular values of A~ = A / Z, descending (numpy SVD), and the
+    spectral norm of A~ A~^T - I, the quantity Sec. 4.2.2 argues is small."""
+    A, Z = _f64(A), _f64(Z)
+    R, Dr = d.merge_regions, A.shape[2]
+    sv = np.empty((d.B, R, Dr), np.float64)
+    dev = np.empty((d.B, R), np.float64)
+    for b in range(d.B):
+        for rho in range(R):
+            z = np.maximum(Z[b, rho * Dr:(rho + 1) * Dr], 1e-20)
+            At = A[b, rho] / z[:, None]
+            sv[b, rho] = np.linalg.svd(At, compute_uv=False)
+            dev[b, rho] = np.abs(np.linalg.eigvalsh(At @ At.T) - 1.0).max()
+    return sv, dev
 
 
 def layer(d, X, Wq, Wk, Wv, heads, Xe=None, Wo=None, idx=None, AZ=None):

@@ -16,7 +16,7 @@ TOMA_F32, TOMA_BF16 = 0, 1
 TOMA_REUSE_IDX, TOMA_REUSE_A = 1, 2
 EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_select_static", "toma_merge", "toma_map_bytes",
            "toma_map_build", "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer", "toma_mlp", "toma_profile_enable",
-           "toma_profile_kernel_name", "toma_profile_read")
+           "toma_profile_kernel_name", "toma_profile_read", "toma_profile_map_product")
 
 
 class TomaError(RuntimeError):
@@ -83,6 +83,8 @@ def lib():
         L.toma_profile_kernel_name.restype = ctypes.c_char_p
         L.toma_profile_kernel_name.argtypes = [ctypes.c_int]
         L.toma_profile_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
+        L.toma_profile_map_product.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
+        L.toma_profile_map_product.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -204,6 +206,13 @@ def toma_profile_read(kernel):
     n, ms = ctypes.c_int32(0), ctypes.c_float(0.0)
     _check(lib().toma_profile_read(kernel.encode(), ctypes.byref(n), ctypes.byref(ms)), "toma_profile_read")
     return n.value, ms.value
+
+
+def toma_profile_map_product(desc, which):
+    """(rows, columns, K split) of the block tile of the merge (0) / unmerge (1) product, or None."""
+    out = (ctypes.c_int32 * 3)()
+    rc = lib().toma_profile_map_product(_ref(desc), int(which), out)
+    return None if rc != 0 else tuple(out)
 
 
 def alloc_cache(desc, device="cuda"):

@@ -701,13 +701,13 @@ template <typename T, typename Pol>
 inline GemmShape launch_gemm(int kernel_id, const Pol &pol, int M, int N, int K, int batch, hipStream_t st) {
   if (gemm_async_fits(M, N, K, (int)sizeof(T))) {
     // load-to-LDS pipeline
-    // With a K list the work per workgroup is not known here: splitting K then mostly splits the
-    // empty steps, so K stays whole unless the tiles alone cannot occupy the chip.
-    bool may_split = Pol::SPLIT_K;
+    GemmPlan pl;
     if constexpr (PolSparseK<Pol>::value) {
-      if (pol.k_list() && (long long)((M + 127) / 128) * ((N + 127) / 128) * batch >= 128) may_split = false;
+      static_assert(Pol::SPLIT_K && Pol::EPI == 1, "map products are planned by plan_map_product");
+      pl = plan_map_product(M, N, K, batch, (int)sizeof(T), Pol::A_KS, Pol::B_KS, pol.k_list());
+    } else {
+      pl = plan_gemm_async(M, N, K, batch, (int)sizeof(T), Pol::SPLIT_K, Pol::A_KS, Pol::B_KS, Pol::EPI);
     }
-    const GemmPlan pl = plan_gemm_async(M, N, K, batch, (int)sizeof(T), may_split, Pol::A_KS, Pol::B_KS, Pol::EPI);
     const GemmShape g{pl.bm, pl.bn, 4, 2, (M + pl.bm - 1) / pl.bm, (N + pl.bn - 1) / pl.bn, pl.nsplit};
     const dim3 grid(g.tiles_m * g.tiles_n * batch * g.nsplit);
     {

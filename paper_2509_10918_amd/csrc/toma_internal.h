@@ -87,6 +87,16 @@ inline GemmPlan plan_gemm_async(int M, int N, int K, int batch, int elem_size, b
   return best;
 }
 
+// Tile and K split of the merge (M = destinations, K = sources) and unmerge (M = sources, K =
+// destinations) products of a merge region.  With a block map the work per workgroup is not known on
+// the host: splitting K would mostly split empty steps, so K stays whole unless the tiles alone
+// cannot occupy the chip.
+inline GemmPlan plan_map_product(int M, int N, int K, int batch, int elem_size, bool a_ks, bool b_ks, bool has_map) {
+  bool may_split = true;
+  if (has_map && (long long)((M + 127) / 128) * ((N + 127) / 128) * batch >= 128) may_split = false;
+  return plan_gemm_async(M, N, K, batch, elem_size, may_split, a_ks, b_ks, 1);
+}
+
 // The single-pass merge-weight kernel keeps a (32 sources) x (all destinations of the merge region)
 // logit tile in the accumulators of one workgroup: it needs the destinations of a region to be
 // 128 * {1, 2, 4, 8, 16}, the sources a multiple of 32, and rows of a multiple of 128 bytes.

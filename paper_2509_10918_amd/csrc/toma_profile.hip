@@ -95,3 +95,18 @@ TOMA_API int toma_profile_read(const char *kernel, int32_t *launches, float *tot
     }
   return TOMA_ERR_UNSUPPORTED;
 }
+
+TOMA_API int toma_profile_map_product(const toma_desc *desc, int which, int32_t *out3) {
+  if (!out3) return TOMA_ERR_NULL;
+  Shape s;
+  int rc = make_shape(desc, nullptr, &s);
+  if (rc != TOMA_OK) return rc;
+  Workspace w;
+  plan_workspace(s, &w);
+  const int es = s.dtype == TOMA_BF16 ? 2 : 4;
+  const int M = which == 0 ? s.Dr : s.Nr, K = which == 0 ? s.Nr : s.Dr;
+  if ((which != 0 && which != 1) || !gemm_async_fits(M, s.C, K, es)) return TOMA_ERR_UNSUPPORTED;
+  const GemmPlan pl = plan_map_product(M, s.C, K, s.B * s.R, es, which == 1, true, w.occ_sb != 0);
+  out3[0] = pl.bm; out3[1] = pl.bn; out3[2] = pl.nsplit;
+  return TOMA_OK;
+}

@@ -142,3 +142,28 @@ def test_mlp_matches_numpy_and_scipy_erf(oracle):
     eye = np.eye(16)
     assert np.allclose(oracle.mlp(big, eye, eye), big, rtol=1e-12)
     assert np.allclose(oracle.mlp(-big, eye, eye), 0.0, atol=1e-12)
+
+
+def test_cross_attention_matches_library_sdpa(oracle):
+    """Queries from one token set, keys / values from another of a different width and length, against
+    torch's SDPA in float64; with the context equal to the queries it is the self-attention above; a
+    single context token makes every output row that token's value (softmax over one key)."""
+    rng = np.random.default_rng(41)
+    B, Lq, Tc, C, Cc, heads = 2, 19, 7, 24, 40, 3
+    U, Ctx = rng.standard_normal((B, Lq, C)), rng.standard_normal((B, Tc, Cc))
+    Wq = rng.standard_normal((C, C)) / np.sqrt(C)
+    Wk, Wv = (rng.standard_normal((Cc, C)) / np.sqrt(Cc) for _ in range(2))
+    Wo = rng.standard_normal((C, C)) / np.sqrt(C)
+    O = oracle.cross_attend(U, Ctx, Wq, Wk, Wv, heads)
+    dh = C // heads
+    q, k, v = torch.from_numpy(U @ Wq), torch.from_numpy(Ctx @ Wk), torch.from_numpy(Ctx @ Wv)
+    sp = lambda t: t.reshape(B, -1, heads, dh).transpose(1, 2)
+    ref = torch.nn.functional.scaled_dot_product_attention(sp(q), sp(k), sp(v)).transpose(1, 2).reshape(B, Lq, C).numpy()
+    assert np.allclose(O, ref, atol=1e-12)
+    assert np.allclose(oracle.cross_attend(U, Ctx, Wq, Wk, Wv, heads, Wo=Wo), ref @ Wo, atol=1e-12)
+    W = _weights(rng, C)
+    assert np.allclose(oracle.cross_attend(U, U, *W, heads=heads), oracle.attend(U, None, *W, heads=heads), atol=1e-12)
+    one = oracle.cross_attend(U, Ctx[:, :1], Wq, Wk, Wv, heads)
+    assert np.allclose(one, np.repeat(Ctx[:, :1] @ Wv, Lq, axis=1), atol=1e-12)
+    # a transposed weight or a softmax over the wrong axis does not survive these
+    assert not np.allclose(oracle.cross_attend(U, Ctx, Wq.T.copy(), Wk, Wv, heads), ref, atol=1e-3)

@@ -163,3 +163,82 @@ def test_unchosen_destination_is_clamped_and_counted(oracle):
     assert clamps == 1 and Z[0, 1] < 1e-20
     Xm = oracle.merge(d, X, A, Z)
     assert np.all(np.isfinite(Xm))
+
+
+def _random_weights(rng, B, R, Dr, Nr, density=0.2):
+    A = rng.uniform(0.1, 1.0, (B, R, Dr, Nr)) * (rng.uniform(size=(B, R, Dr, Nr)) < density)
+    A[..., 0] += 0.05          # no empty rows
+    return A, A.sum(axis=3).reshape(B, R * Dr)
+
+
+def test_pinv_unmerge_is_the_moore_penrose_solution(oracle):
+    """Sec. 4.2.2: X' -> A~^+ X'.  Pinned by what defines the pseudo-inverse rather than by the routine
+    that computes it: for rows of full rank it is the paper's closed form A~^T (A~ A~^T)^-1 X' (solved
+    here as a linear system); A~ Y reproduces X' exactly then; Y lies in the row space of A~ (minimum
+    norm); and tokens land at their grid positions in both merge modes."""
+    rng = np.random.default_rng(51)
+    B, H, W, C, th, tw, k = 2, 8, 8, 5, 4, 4, 6
+    for R in (1, 4):
+        d = oracle.make_desc(B, H, W, C, th, tw, k, R, 0.1)
+        Dr, Nr = 4 * k // R, H * W // R
+        A, Z = _random_weights(rng, B, R, Dr, Nr)
+        O = rng.standard_normal((B, 4 * k + 3, C))            # three extra rows that must be ignored
+        Y = oracle.unmerge_pinv(d, A, Z, O, rcond=1e-12)
+        _, _, token_of = oracle.region_map(H, W, th, tw)
+        for b in range(B):
+            for rho in range(R):
+                At = A[b, rho] / Z[b, rho * Dr:(rho + 1) * Dr, None]
+                Xp = O[b, rho * Dr:(rho + 1) * Dr]
+                toks = np.arange(H * W) if R == 1 else token_of[rho]
+                closed = At.T @ np.linalg.solve(At @ At.T, Xp)
+                assert np.allclose(Y[b, toks], closed, atol=1e-10)
+                assert np.allclose(At @ Y[b, toks], Xp, atol=1e-10)
+                # minimum norm: nothing outside the row space of A~
+                null = np.eye(Nr) - At.T @ np.linalg.solve(At @ At.T, At)
+                assert np.abs(null @ Y[b, toks]).max() < 1e-10
+
+
+def test_pinv_unmerge_equals_transpose_unmerge_for_orthonormal_rows(oracle):
+    """The paper's argument for the transpose: when A~ A~^T = I the two unmerges coincide.  Rows that
+    are one-hot on distinct sources (hard assignment of one source per destination) are orthonormal."""
+    rng = np.random.default_rng(52)
+    B, H, W, C = 1, 4, 8, 3
+    d = oracle.make_desc(B, H, W, C, 4, 8, 10, 1, 0.1)
+    A = np.zeros((B, 1, 10, 32))
+    A[0, 0, np.arange(10), rng.choice(32, 10, replace=False)] = 1.0
+    Z = A.sum(axis=3).reshape(B, 10)
+    O = rng.standard_normal((B, 10, C))
+    assert np.allclose(oracle.unmerge_pinv(d, A, Z, O, rcond=1e-12), oracle.unmerge(d, A, Z, O), atol=1e-13)
+    sv, dev = oracle.merge_matrix_spectrum(d, A, Z)
+    assert np.allclose(sv, 1.0) and dev.max() < 1e-14
+
+
+def test_pinv_unmerge_with_deficient_rank_and_the_cut_off(oracle):
+    """Rank-deficient merge matrices (the closed form does not exist): a destination that received no
+    weight (zero row) is ignored; two destinations with identical rows share their inputs' mean (least
+    squares), which keeping only one of them would not give; and a singular value below rcond * largest
+    counts as zero while one above is inverted."""
+    rng = np.random.default_rng(53)
+    B, H, W, C = 1, 4, 8, 4
+    d = oracle.make_desc(B, H, W, C, 4, 8, 6, 1, 0.1)
+    A, Z = _random_weights(rng, B, 1, 6, 32, density=0.4)
+    A[0, 0, 2] = 0.0                       # nobody chose destination 2
+    A[0, 0, 5] = A[0, 0, 4]                # destinations 4 and 5 weigh the same sources equally
+    Z = A.sum(axis=3).reshape(B, 6)
+    O = rng.standard_normal((B, 6, C))
+    Y = oracle.unmerge_pinv(d, A, Z, O, rcond=1e-9)
+    keep = [0, 1, 3, 4]
+    At = A[0, 0, keep] / Z[0, keep, None]
+    Xp = O[0, keep].copy()
+    Xp[3] = 0.5 * (O[0, 4] + O[0, 5])
+    assert np.allclose(Y[0], At.T @ np.linalg.solve(At @ At.T, Xp), atol=1e-9)
+    Xp[3] = O[0, 4]
+    assert not np.allclose(Y[0], At.T @ np.linalg.solve(At @ At.T, Xp), atol=1e-3)
+    # the cut-off: two orthogonal rows with norms 1 and 1e-3 (before normalisation they are rows of A~
+    # already: Z = 1 is passed)
+    d2 = oracle.make_desc(1, 2, 4, 2, 2, 4, 2, 1, 0.1)
+    A2 = np.zeros((1, 1, 2, 8)); A2[0, 0, 0, 0] = 1.0; A2[0, 0, 1, 1] = 1e-3
+    O2 = np.array([[[1.0, 2.0], [3.0, 4.0]]])
+    kept = oracle.unmerge_pinv(d2, A2, np.ones((1, 2)), O2, rcond=1e-4)
+    cut = oracle.unmerge_pinv(d2, A2, np.ones((1, 2)), O2, rcond=1e-2)
+    assert np.allclose(kept[0, 1], [3000.0, 4000.0]) and np.allclose(cut[0, 1], 0.0) and np.allclose(cut[0, 0], [1.0, 2.0])
