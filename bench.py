@@ -280,6 +280,33 @@ def main():
         "kernels": per_kernel,
     }
 
+    # the two unmerges of Sec. 4.2.2 side by side (App. E.4 compares them end to end): transpose against
+    # Moore-Penrose, where the latter's region size limit allows it
+    if R == w.P and w.d_loc <= 128:
+        O_in = torch.randn((w.B, w.D + w.T_extra, w.C), device="cuda").to(tdt)
+        reps = max(args.steps // 4, 10)
+
+        def time_it(fn):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e6 / reps
+
+        t_us = time_it(lambda: tb.toma_unmerge(desc, A, Z, amap, O_in, Y, ws))
+        tb.toma_profile_enable(True)
+        p_us = time_it(lambda: tb.toma_unmerge_pinv(desc, A, Z, O_in, 1e-2, Y, ws))
+        parts = {}
+        for name in ("pinv_eig", "pinv_apply"):
+            n, total = tb.toma_profile_read(name)
+            parts[name + "_us"] = total * 1e3 / max(n, 1)
+        tb.toma_profile_enable(False)
+        out["unmerge_variants"] = {"transpose_us": t_us, "pseudo_inverse_us": p_us, "rcond": 1e-2, **parts,
+                                   "context": "paper, SDXL end to end: 4.8 s / image with the transpose, 10.1 s with the "
+                                              "pseudo-inverse (App. E.4, hardware not stated)"}
+
     if not args.no_cpu_baseline:
         from oracle import toma_oracle as orc
         f64 = lambda a: None if a is None else np.asarray(a, dtype=np.float64)

@@ -171,6 +171,22 @@ int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *X
                 const void *Wo_opt, void *O, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Cross-attention with the merged tokens as queries (Sec. 5.1: the ToMA_once variant merges once per
+ * transformer block and runs every module of the block - self-attention, cross-attention, MLP - on
+ * the merged tokens before one unmerge).  Eq. 1 with tau = 1 and separate token sets:
+ * Q = U Wq; K = Ctx Wk, V = Ctx Wv; per head O_h = softmax(Q_h K_h^T / sqrt(head_dim)) V_h over the
+ * context tokens; heads concatenated; O = O Wo when Wo_opt is given.
+ *   U     in   [B, L, C]           L = D + attn->t_extra query tokens per sample (e.g. the output of
+ *                                  toma_attend, or the merged tokens themselves)
+ *   Ctx   in   [B, t_ctx, c_ctx]   context tokens (e.g. text embeddings); c_ctx % 32 == 0, t_ctx <= L
+ *   Wq    in   [C, C];  Wk, Wv in [c_ctx, C];  Wo_opt in [C, C]   row-major, y = x W
+ *   O     out  [B, L, C]           may not alias U
+ */
+int toma_cross_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *U, const void *Ctx,
+                      int32_t t_ctx, int32_t c_ctx, const void *Wq, const void *Wk, const void *Wv,
+                      const void *Wo_opt, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Transpose unmerge (Sec. 4.2.2; Alg. 3 step 3): Y[token(s)] = sum_j (A_js / Z_j) O_j for every
  * source s, written at the token's grid position (the region split is undone by addressing).
  *   O  in   [B, o_rows, C]   o_rows >= D; only rows [0, D) of each sample are read
@@ -178,6 +194,24 @@ int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *X
  */
 int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *amap, const void *O,
                  int32_t o_rows, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Moore-Penrose unmerge (Sec. 4.2.2, first display; the alternative the paper measures the transpose
+ * against in App. E.4): Y[token(s)] = sum_j (A~^+)_sj O_j with A~ = A / Z the row-normalised merge
+ * matrix of each merge region and A~^+ its pseudo-inverse, = A~^T (A~ A~^T)^-1 when the rows of A~ are
+ * independent.  They often are not (a destination nobody chose is a zero row; near-duplicate
+ * destinations give nearly dependent rows), so the pseudo-inverse is taken with a cut-off, as numerical
+ * libraries do: singular values of A~ that are <= rcond * the largest count as zero.  The paper does not
+ * name one; with tau = 0.1 the merge matrices of smooth inputs have a bulk of singular values in
+ * [0.2, 1] and a few stragglers of 1e-4 and below, so 1e-2 separates them.
+ * Computed in double precision from the stored A and Z (eigen-decomposition of A~ A~^T per region).
+ *   rcond  in  0 <= rcond < 1
+ *   O, Y   as for toma_unmerge
+ * Limits: merge regions of at most 128 destinations (region-local merge at the usual sizes; one
+ * merge region per sample only for small grids); otherwise TOMA_ERR_UNSUPPORTED.
+ */
+int toma_unmerge_pinv(const toma_desc *desc, const void *A, const float *Z, const void *O, int32_t o_rows,
+                      float rcond, void *Y, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * One whole layer with pattern reuse (Alg. 3 + Sec. 4.3.2).  reuse_flags says what is taken from

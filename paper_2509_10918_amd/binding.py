@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libtoma.so")
 TOMA_F32, TOMA_BF16 = 0, 1
 TOMA_REUSE_IDX, TOMA_REUSE_A = 1, 2
 EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_select_static", "toma_merge", "toma_map_bytes",
-           "toma_map_build", "toma_merge_cached", "toma_attend", "toma_unmerge", "toma_layer", "toma_mlp", "toma_profile_enable",
+           "toma_map_build", "toma_merge_cached", "toma_attend", "toma_cross_attend", "toma_unmerge", "toma_unmerge_pinv", "toma_layer", "toma_mlp", "toma_profile_enable",
            "toma_profile_kernel_name", "toma_profile_read", "toma_profile_map_product")
 
 
@@ -73,10 +73,14 @@ def lib():
         L.toma_map_build.argtypes = [vp, vp, vp, vp]
         L.toma_merge_cached.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_attend.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_cross_attend.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_cross_attend.restype = ctypes.c_int
         L.toma_unmerge.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
+        L.toma_unmerge_pinv.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_float, vp, vp, sz, vp]
+        L.toma_unmerge_pinv.restype = ctypes.c_int
         L.toma_layer.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_mlp.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
-        for name in ("toma_select", "toma_merge", "toma_map_build", "toma_merge_cached", "toma_attend", "toma_unmerge",
+        for name in ("toma_select", "toma_merge", "toma_map_build", "toma_merge_cached", "toma_attend", "toma_cross_attend", "toma_unmerge", "toma_unmerge_pinv",
                      "toma_layer", "toma_mlp"):
             getattr(L, name).restype = ctypes.c_int
         L.toma_profile_enable.argtypes = [ctypes.c_int]
@@ -167,9 +171,20 @@ def toma_attend(desc, attn, Xm, X_extra, Wq, Wk, Wv, Wo, O, ws):
                              _ptr(Wo), _ptr(O), _ptr(ws), ws.numel(), _stream()), "toma_attend")
 
 
+def toma_cross_attend(desc, attn, U, Ctx, Wq, Wk, Wv, Wo, O, ws):
+    _check(lib().toma_cross_attend(_ref(desc), _ref(attn), _ptr(U), _ptr(Ctx), Ctx.shape[1], Ctx.shape[2], _ptr(Wq),
+                                   _ptr(Wk), _ptr(Wv), _ptr(Wo), _ptr(O), _ptr(ws), ws.numel(), _stream()),
+           "toma_cross_attend")
+
+
 def toma_unmerge(desc, A, Z, amap, O, Y, ws):
     _check(lib().toma_unmerge(_ref(desc), _ptr(A), _ptr(Z), _ptr(amap), _ptr(O), O.shape[1], _ptr(Y), _ptr(ws),
                               ws.numel(), _stream()), "toma_unmerge")
+
+
+def toma_unmerge_pinv(desc, A, Z, O, rcond, Y, ws):
+    _check(lib().toma_unmerge_pinv(_ref(desc), _ptr(A), _ptr(Z), _ptr(O), O.shape[1], float(rcond), _ptr(Y), _ptr(ws),
+                                   ws.numel(), _stream()), "toma_unmerge_pinv")
 
 
 def toma_layer(desc, attn, reuse_flags, X, X_extra, idx, A, Z, amap, Wq, Wk, Wv, Wo, Y, Y_extra, ws):

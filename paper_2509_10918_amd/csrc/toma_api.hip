@@ -84,6 +84,7 @@ void plan_workspace(const Shape &s, Workspace *w) {
     if (pu.nsplit > 1) part = std::max(part, (size_t)pu.nsplit * s.B * s.N * s.C * sizeof(float));
   }
   w->split = take(part);
+  w->pinv = take(pinv_workspace_bytes(s));  // eigenvectors and G^+ of the Moore-Penrose unmerge
   // the occupancy map of A is not scratch: it belongs to the caller's cache, next to (A, Z)
   if (occupancy_pays(s.Nr, s.Dr, s.C, (int)es)) {
     w->occ_db = (s.Dr + kOccDest - 1) / kOccDest;
@@ -267,6 +268,24 @@ TOMA_API int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, cons
                        static_cast<hipStream_t>(stream));
 }
 
+TOMA_API int toma_cross_attend(const toma_desc *desc, const toma_attn_desc *attn, const void *U, const void *Ctx,
+                               int32_t t_ctx, int32_t c_ctx, const void *Wq, const void *Wk, const void *Wv,
+                               const void *Wo_opt, void *O, void *ws, size_t ws_bytes, void *stream) {
+  if (!attn) return TOMA_ERR_NULL;
+  Shape s; Workspace w;
+  int rc = prepare(desc, attn, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (t_ctx <= 0 || c_ctx <= 0) return TOMA_ERR_SHAPE;
+  // keys and values of the context share the workspace sections sized for the L query rows
+  if (c_ctx % 32 || t_ctx > s.L || (long long)t_ctx * c_ctx >= (1ll << 31)) return TOMA_ERR_UNSUPPORTED;
+  if (!U || !Ctx || !Wq || !Wk || !Wv || !O) return TOMA_ERR_NULL;
+  if (misaligned(U, 16) || misaligned(Ctx, 16) || misaligned(Wq, 16) || misaligned(Wk, 16) || misaligned(Wv, 16) ||
+      misaligned(O, 16) || (Wo_opt && misaligned(Wo_opt, 16)))
+    return TOMA_ERR_ALIGN;
+  return launch_cross_attend(s, U, Ctx, t_ctx, c_ctx, Wq, Wk, Wv, Wo_opt, O, static_cast<char *>(ws), w,
+                             static_cast<hipStream_t>(stream));
+}
+
 TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const void *amap, const void *O,
                           int32_t o_rows, void *Y, void *ws, size_t ws_bytes, void *stream) {
   Shape s; Workspace w;
@@ -279,6 +298,18 @@ TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, 
   if (rc != TOMA_OK) return rc;
   return launch_unmerge(s, A, Z, static_cast<const uint8_t *>(amap), O, o_rows, false, Y, static_cast<char *>(ws), w,
                         static_cast<hipStream_t>(stream));
+}
+
+TOMA_API int toma_unmerge_pinv(const toma_desc *desc, const void *A, const float *Z, const void *O, int32_t o_rows,
+                               float rcond, void *Y, void *ws, size_t ws_bytes, void *stream) {
+  Shape s; Workspace w;
+  int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!A || !Z || !O || !Y) return TOMA_ERR_NULL;
+  if (o_rows < s.D || !(rcond >= 0.0f) || !(rcond < 1.0f)) return TOMA_ERR_SHAPE;
+  if (misaligned(A, 16) || misaligned(O, 16) || misaligned(Y, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
+  return launch_unmerge_pinv(s, A, Z, O, o_rows, rcond, Y, static_cast<char *>(ws), w,
+                             static_cast<hipStream_t>(stream));
 }
 
 TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse_flags, const void *X,

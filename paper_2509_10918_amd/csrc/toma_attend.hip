@@ -28,12 +28,13 @@ template <typename T> struct QkvPol {
   const T *W[3];
   T *out[3];
   int B, D, Tx, L, C, H, dh, dh_sh;  // dh_sh = log2(dh), or -1 if dh is not a power of two
-  __device__ __forceinline__ GemmCtx setup(int bz) const { return GemmCtx{B * L, C, C, 0, 0, bz}; }
+  int Kin;                           // width of the input rows (C for self-attention; the context's for cross-attention keys / values)
+  __device__ __forceinline__ GemmCtx setup(int bz) const { return GemmCtx{B * L, C, Kin, 0, 0, bz}; }
   __device__ __forceinline__ bool a_linear(int) const { return true; }
   __device__ __forceinline__ bool b_linear(int) const { return true; }
   __device__ __forceinline__ const T *a_ptr(const GemmCtx &, int m, int k) const {
     int b = m / L, l = m % L;
-    return l < D ? Xm + ((size_t)b * D + l) * C + k : Xe + ((size_t)b * Tx + (l - D)) * C + k;
+    return l < D ? Xm + ((size_t)b * D + l) * Kin + k : Xe + ((size_t)b * Tx + (l - D)) * Kin + k;
   }
   __device__ __forceinline__ const T *b_ptr(const GemmCtx &x, int n, int k) const {
     return W[x.z] + (size_t)k * C + n;
@@ -133,7 +134,7 @@ __device__ __forceinline__ void pack_probs(Frag<float> &f, const f32x4 &lo, cons
 
 template <typename T, int DH>
 __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *__restrict__ Kx,
-                                             const T *__restrict__ V, T *__restrict__ O, int L, int H,
+                                             const T *__restrict__ V, T *__restrict__ O, int Lq, int L, int H,
                                              float scale_log2, const float *__restrict__ Zs, int D) {
   constexpr int EPP = 16 / (int)sizeof(T);
   constexpr int LD = DH + EPP;        // LDS row stride (elements) of the K and V tiles [64][DH]
@@ -146,8 +147,9 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
   const int h = blockIdx.y, b = blockIdx.z;
+  // Lq queries attend to L keys / values (the same tokens in self-attention)
   const size_t head = ((size_t)b * H + h) * L * DH;
-  const T *Qh = Q + head, *Kh = Kx + head, *Vh = V + head;
+  const T *Qh = Q + ((size_t)b * H + h) * Lq * DH, *Kh = Kx + head, *Vh = V + head;
   const int q_w = blockIdx.x * 128 + w * 32;
 
   // queries as B-operand fragments: lane = query column, slots = head_dim 32 kk + 8 g + i
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
 #pragma unroll
   for (int qt = 0; qt < QT; qt++) {
     int q = q_w + 16 * qt + c;
-    q = q < L ? q : L - 1;
+    q = q < Lq ? q : Lq - 1;
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
       const T *src = Qh + (size_t)q * DH + 32 * kk + 8 * g;
@@ -282,9 +284,9 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
     l += wave_xor_f32(l, 32);
     float inv = 1.0f / l;
     int q = q_w + 16 * qt + c;
-    if (q >= L) continue;
+    if (q >= Lq) continue;
     if (Zs && q < D) inv /= fmaxf(Zs[(size_t)b * D + q], 1e-20f);  // unmerge input: O / Z
-    T *dst = O + ((size_t)b * L + q) * Cw + h * DH + 4 * g;
+    T *dst = O + ((size_t)b * Lq + q) * Cw + h * DH + 4 * g;
 #pragma unroll
     for (int dt = 0; dt < DT; dt++) {
       alignas(16) T o[4];
@@ -344,7 +346,7 @@ __device__ __forceinline__ float rows4_sum_f32(float v) {
 // least eight).
 template <typename T, int DH, int QT>
 __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 256 ? 3 : 4) : (DH * sizeof(T) >= 256 ? 1 : 2)) void k_attn_async(
-    const T *__restrict__ Q, const T *__restrict__ Kx, const T *__restrict__ V, T *__restrict__ O, int L, int H,
+    const T *__restrict__ Q, const T *__restrict__ Kx, const T *__restrict__ V, T *__restrict__ O, int Lq, int L, int H,
     float scale_log2, const float *__restrict__ Zs, int D) {
   constexpr int ES = (int)sizeof(T), EPP = 16 / ES;
   constexpr int PPR = DH / EPP;       // 16-byte packets per K / V row
@@ -360,11 +362,12 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
   // one-dimensional grid over (sample, head, query block), remapped so that the blocks an XCD
   // receives are neighbours: the query blocks of a head then share that head's K and V in one L2
-  const int nq = (L + QB - 1) / QB;
+  // (Lq queries attend to L keys / values: the same tokens in self-attention)
+  const int nq = (Lq + QB - 1) / QB;
   const int work = xcd_remap(blockIdx.x, gridDim.x);
   const int qb = work % nq, h = (work / nq) % H, b = work / (nq * H);
   const size_t head = ((size_t)b * H + h) * L * DH;
-  const T *Qh = Q + head, *Kh = Kx + head, *Vh = V + head;
+  const T *Qh = Q + ((size_t)b * H + h) * Lq * DH, *Kh = Kx + head, *Vh = V + head;
   const int q_w = qb * QB + w * (16 * QT);
   const int nt = (L + 63) / 64;
 
@@ -372,7 +375,7 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
 #pragma unroll
   for (int qt = 0; qt < QT; qt++) {
     int q = q_w + 16 * qt + c;
-    q = q < L ? q : L - 1;
+    q = q < Lq ? q : Lq - 1;
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
       const T *src = Qh + (size_t)q * DH + 32 * kk + 8 * g;
@@ -564,9 +567,9 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
     const float l = rows4_sum_f32(l_run[qt]);
     float inv = 1.0f / l;
     int q = q_w + 16 * qt + c;
-    if (q >= L) continue;
+    if (q >= Lq) continue;
     if (Zs && q < D) inv /= fmaxf(Zs[(size_t)b * D + q], 1e-20f);  // unmerge input: O / Z
-    T *dst = O + ((size_t)b * L + q) * Cw + h * DH + 4 * g;
+    T *dst = O + ((size_t)b * Lq + q) * Cw + h * DH + 4 * g;
 #pragma unroll
     for (int dt = 0; dt < DT; dt++) {
       alignas(16) T o[4];
@@ -618,8 +621,8 @@ static int attn_waves(int L, int heads_x_batch, int ring_bytes, int waves_per_cu
 #endif
 // nw: waves per workgroup, 0 = chosen by attn_waves
 template <typename T, int DH>
-static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O, const float *Zs, hipStream_t st,
-                        int nw = 0) {
+static void launch_attn(const Shape &s, int Lq, int Lk, const T *Q, const T *K, const T *V, T *O, const float *Zs,
+                        hipStream_t st, int nw = 0) {
   float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   KernelTimer kt(K_ATTN, st);
   // load-to-LDS pipeline when a row is at least eight packets and the ring of four tiles fits the LDS
@@ -628,17 +631,17 @@ static void launch_attn(const Shape &s, const T *Q, const T *K, const T *V, T *O
   if constexpr (kRowPackets >= 8 && kRing <= 160 * 1024 - 4096) {
     if (TOMA_ATTN_QT == 1) {
       constexpr bool kWide = DH * sizeof(T) >= 256;  // three waves per SIMD fit the registers, else four
-      if (nw < (kWide ? 8 : 4) || nw > 12) nw = attn_waves(s.L, s.heads * s.B, kRing, kWide ? 12 : 16, kWide ? 8 : 4, kWide ? 2.3f : 2.0f);
-      dim3 grid((s.L + 16 * nw - 1) / (16 * nw) * s.heads * s.B);
-      hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(64 * nw), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+      if (nw < (kWide ? 8 : 4) || nw > 12) nw = attn_waves(Lq, s.heads * s.B, kRing, kWide ? 12 : 16, kWide ? 8 : 4, kWide ? 2.3f : 2.0f);
+      dim3 grid((Lq + 16 * nw - 1) / (16 * nw) * s.heads * s.B);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(64 * nw), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D);
     } else {
-      dim3 grid((s.L + 127) / 128 * s.heads * s.B);
-      hipLaunchKernelGGL((k_attn_async<T, DH, 2>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+      dim3 grid((Lq + 127) / 128 * s.heads * s.B);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 2>), grid, dim3(256), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D);
     }
     return;
   }
-  dim3 grid((s.L + 127) / 128, s.heads, s.B);
-  hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, s.L, s.heads, scale_log2, Zs, s.D);
+  dim3 grid((Lq + 127) / 128, s.heads, s.B);
+  hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D);
 }
 
 template <typename T>
@@ -650,15 +653,15 @@ static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const vo
   p.Xm = static_cast<const T *>(Xm); p.Xe = static_cast<const T *>(Xe);
   p.W[0] = static_cast<const T *>(Wq); p.W[1] = static_cast<const T *>(Wk); p.W[2] = static_cast<const T *>(Wv);
   p.out[0] = Q; p.out[1] = K; p.out[2] = V;
-  p.B = s.B; p.D = s.D; p.Tx = s.T; p.L = s.L; p.C = s.C; p.H = s.heads; p.dh = s.head_dim;
+  p.B = s.B; p.D = s.D; p.Tx = s.T; p.L = s.L; p.C = s.C; p.H = s.heads; p.dh = s.head_dim; p.Kin = s.C;
   p.dh_sh = -1;
   for (int sh = 0; sh < 16; sh++) if ((1 << sh) == s.head_dim) p.dh_sh = sh;
   launch_gemm<T>(K_QKV, p, s.B * s.L, s.C, s.C, 3, st);
   T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
   switch (s.head_dim) {
-    case 32: launch_attn<T, 32>(s, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
-    case 64: launch_attn<T, 64>(s, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
-    case 128: launch_attn<T, 128>(s, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
+    case 32: launch_attn<T, 32>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
+    case 64: launch_attn<T, 64>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
+    case 128: launch_attn<T, 128>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
     default: return TOMA_ERR_UNSUPPORTED;
   }
   if (Wo) {
@@ -675,6 +678,49 @@ int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq
                   hipStream_t st) {
   return s.dtype == TOMA_BF16 ? attend_typed<bf16_t>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st)
                               : attend_typed<float>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st);
+}
+
+// Cross-attention: queries from the L rows of U, keys / values from t_ctx context rows of width c_ctx.
+template <typename T>
+static int cross_typed(const Shape &s, const void *U, const void *Ctx, int t_ctx, int c_ctx, const void *Wq,
+                       const void *Wk, const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w,
+                       hipStream_t st) {
+  T *Q = reinterpret_cast<T *>(ws + w.q), *K = reinterpret_cast<T *>(ws + w.k), *V = reinterpret_cast<T *>(ws + w.v);
+  QkvPol<T> pq{};
+  pq.Xm = static_cast<const T *>(U); pq.Xe = nullptr;
+  pq.W[0] = static_cast<const T *>(Wq); pq.W[1] = pq.W[2] = nullptr;
+  pq.out[0] = Q; pq.out[1] = pq.out[2] = nullptr;
+  pq.B = s.B; pq.D = s.L; pq.Tx = 0; pq.L = s.L; pq.C = s.C; pq.H = s.heads; pq.dh = s.head_dim; pq.Kin = s.C;
+  pq.dh_sh = -1;
+  for (int sh = 0; sh < 16; sh++) if ((1 << sh) == s.head_dim) pq.dh_sh = sh;
+  launch_gemm<T>(K_QKV, pq, s.B * s.L, s.C, s.C, 1, st);
+  QkvPol<T> pk = pq;
+  pk.Xm = static_cast<const T *>(Ctx);
+  pk.W[0] = static_cast<const T *>(Wk); pk.W[1] = static_cast<const T *>(Wv);
+  pk.out[0] = K; pk.out[1] = V;
+  pk.D = t_ctx; pk.L = t_ctx; pk.Kin = c_ctx;
+  launch_gemm<T>(K_QKV, pk, s.B * t_ctx, s.C, c_ctx, 2, st);
+  T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
+  switch (s.head_dim) {
+    case 32: launch_attn<T, 32>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, st); break;
+    case 64: launch_attn<T, 64>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, st); break;
+    case 128: launch_attn<T, 128>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, st); break;
+    default: return TOMA_ERR_UNSUPPORTED;
+  }
+  if (Wo) {
+    ProjPol<T> pp{};
+    pp.In = Oh; pp.Wt = static_cast<const T *>(Wo); pp.Out = static_cast<T *>(O);
+    pp.rows = s.B * s.L; pp.C = s.C; pp.L = s.L; pp.D = s.D; pp.Zs = nullptr;
+    launch_gemm<T>(K_PROJ, pp, s.B * s.L, s.C, s.C, 1, st);
+  }
+  return launch_status();
+}
+
+int launch_cross_attend(const Shape &s, const void *U, const void *Ctx, int t_ctx, int c_ctx, const void *Wq,
+                        const void *Wk, const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w,
+                        hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? cross_typed<bf16_t>(s, U, Ctx, t_ctx, c_ctx, Wq, Wk, Wv, Wo, O, ws, w, st)
+                              : cross_typed<float>(s, U, Ctx, t_ctx, c_ctx, Wq, Wk, Wv, Wo, O, ws, w, st);
 }
 
 template <typename T>

@@ -21,7 +21,7 @@ struct Shape {
 
 // Offsets (bytes) of the scratch sections inside the caller's workspace.
 struct Workspace {
-  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, total;
+  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, pinv, total;
   int stat_parts, z_parts;
   // occupancy map of A, kept by the caller next to (A, Z): blocks of kOccDest destinations x kOccSrc
   // sources per merge region (0: this shape uses none)
@@ -141,9 +141,17 @@ int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, c
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
                   const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
                   hipStream_t st);
+// U: [B, L, C] query tokens; Ctx: [B, t_ctx, c_ctx] context tokens; Wk, Wv: [c_ctx, C]
+int launch_cross_attend(const Shape &s, const void *U, const void *Ctx, int t_ctx, int c_ctx, const void *Wq,
+                        const void *Wk, const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w,
+                        hipStream_t st);
 // prescaled: the merged rows of O were already divided by Z (see launch_attend)
 int launch_unmerge(const Shape &s, const void *A, const float *Z, const uint8_t *occ, const void *O, int o_rows,
                    bool prescaled, void *Y, char *ws, const Workspace &w, hipStream_t st);
+// Y = (A / Z)^+ O with singular values <= rcond * largest dropped; merge regions of up to 128 destinations
+size_t pinv_workspace_bytes(const Shape &s);
+int launch_unmerge_pinv(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, float rcond, void *Y,
+                        char *ws, const Workspace &w, hipStream_t st);
 int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t st);
 // Out = gelu(In W1) W2 on `rows` rows; Hbuf is [rows, hidden] scratch of the same dtype
 int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const void *W1, const void *W2, void *Hbuf,
@@ -151,7 +159,7 @@ int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const voi
 
 // Kernel identifiers of the profiling aid (toma_profile_*): one per kernel of the path.
 enum KernelId { K_GRAM = 0, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
-                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_COUNT };
+                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_PINV_EIG, K_PINV_APPLY, K_COUNT };
 
 // Brackets one launch with HIP events on its stream while profiling is enabled; free otherwise.
 struct KernelTimer {

@@ -92,6 +92,20 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.toma_unmerge(dp, x, x, x, x, 100, x, ws, need, None) == 2          # fewer rows than D
     assert L.toma_layer(dp, ap, 4, x, None, x, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
     assert L.toma_layer(dp, ap, 0, x, None, None, x, x, x, x, x, x, None, x, None, ws, need, None) == 1
+    # cross-attention: context shape and size limits, null checks
+    assert L.toma_cross_attend(dp, ap, x, x, 77, 2048, x, x, x, None, None, ws, need, None) == 1
+    assert L.toma_cross_attend(dp, ap, x, x, 0, 2048, x, x, x, None, x, ws, need, None) == 2
+    assert L.toma_cross_attend(dp, ap, x, x, 77, 2050, x, x, x, None, x, ws, need, None) == 5
+    assert L.toma_cross_attend(dp, ap, x, x, 5000, 2048, x, x, x, None, x, ws, need, None) == 5   # more context than queries
+    assert L.toma_cross_attend(dp, None, x, x, 77, 2048, x, x, x, None, x, ws, need, None) == 1
+    # Moore-Penrose unmerge: cut-off range, region size limit
+    assert L.toma_unmerge_pinv(dp, x, x, x, 2048, ctypes.c_float(1e-2), x, ws, need, None) == 5   # 2048 destinations in one region
+    tl = _d(merge_regions=16)
+    tlp, need_tl = ctypes.addressof(tl), tb.toma_workspace_bytes(tl, a)
+    assert L.toma_unmerge_pinv(tlp, x, x, x, 2048, ctypes.c_float(1.5), x, ws, need_tl, None) == 2
+    assert L.toma_unmerge_pinv(tlp, x, x, x, 100, ctypes.c_float(1e-2), x, ws, need_tl, None) == 2
+    assert L.toma_unmerge_pinv(tlp, x, None, x, 2048, ctypes.c_float(1e-2), x, ws, need_tl, None) == 1
+    assert L.toma_unmerge_pinv(tlp, x, x, x, 2048, ctypes.c_float(1e-2), x, ws, tb.toma_workspace_bytes(tl, None) - 1, None) == 4
     # feed-forward module: dtype, shape, divisibility, null and alignment checks
     assert L.toma_mlp(1, 4096, 640, 2560, x, x, x, x, None, None) == 1
     assert L.toma_mlp(1, 0, 640, 2560, x, x, x, x, x, None) == 2

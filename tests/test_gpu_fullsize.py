@@ -157,3 +157,31 @@ def test_hires_reuse_sequence_tile(oracle):
         for b in range(w.B):
             toks = np.concatenate([token_of[p] for p in regions[b]])
             _report(f"Y step {t} sample {b}", Y[b, toks], Y_ref[b, toks], tol)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["sdxl1", "flux"])
+def test_pinv_unmerge_full_size(oracle, name):
+    """Moore-Penrose unmerge at the benchmark sizes with region-local merge (128 / 64 destinations per
+    region): the library's stored (A, Z) against numpy's pseudo-inverse, and the spectrum that
+    Sec. 4.2.2's orthonormality argument is about, as found on these inputs."""
+    w = W[name]
+    R, tol = w.P, tg.TOL[w.dtype]
+    inp = synth.make_inputs(w)
+    d = tg.oracle_desc(oracle, w, R)
+    dv = tg.Device(w, inp, R)
+    idx = dv.select()
+    A, Z, _ = dv.merge()
+    sv, dev = oracle.merge_matrix_spectrum(d, A, np.maximum(Z, 1e-20))
+    rel = sv / sv.max(axis=2, keepdims=True)
+    rcond = 1e-2
+    assert not np.any((rel > rcond / 6) & (rel < rcond * 6)), "a singular value sits near the cut"
+    print(f"[pinv full] {name}: {int((rel <= rcond).sum())} of {rel.size} singular values below {rcond:g} "
+          f"({int((Z < 1e-20).sum())} destinations without weight); ||A~A~^T - I||_2 max {dev.max():.3f} "
+          f"median {np.median(dev):.3f} min {dev.min():.3f}", flush=True)
+    rng = np.random.default_rng(81)
+    O = synth.quantize(w, rng.standard_normal((w.B, w.D + w.T_extra, w.C)).astype(np.float32))
+    dv.O.copy_(tg.dev(O, w.dtype))
+    tb.toma_unmerge_pinv(dv.desc, dv.A, dv.Z, dv.O, rcond, dv.Y, dv.ws)
+    torch.cuda.synchronize()
+    _report("Y (pseudo-inverse unmerge)", tg.host(dv.Y), oracle.unmerge_pinv(d, A, np.maximum(Z, 1e-20), _f64(O), rcond), tol)

@@ -469,6 +469,171 @@ def test_block_with_one_merge_and_two_modules(oracle, cases):
     _check_stage("Y after merge, attention, mlp, unmerge", dv.unmerge(), Y_ref, tol)
 
 
+@pytest.mark.parametrize("case,t_ctx,c_ctx,use_wo", [("tiny", 9, 32, False), ("small_bf16", 77, 160, True),
+                                                      ("small_bf16", 64, 128, False), ("extra", 200, 256, True)])
+def test_cross_attention(oracle, cases, case, t_ctx, c_ctx, use_wo):
+    """Cross-attention with the [merged ; extra] tokens as queries and a context of another length and
+    width (Sec. 5.1, ToMA_once): context widths that take the tiled product and one that does not,
+    fewer context tokens than one key tile and more, with and without the output projection."""
+    w, inp = cases[case]
+    tol = tg.TOL[w.dtype]
+    rng = np.random.default_rng(61)
+    q = lambda a: synth.quantize(w, np.asarray(a, np.float32))
+    L = w.D + w.T_extra
+    U = q(rng.standard_normal((w.B, L, w.C)))
+    Ctx = q(rng.standard_normal((w.B, t_ctx, c_ctx)))
+    Wq = q(rng.standard_normal((w.C, w.C)) / np.sqrt(w.C))
+    Wk, Wv = (q(rng.standard_normal((c_ctx, w.C)) / np.sqrt(c_ctx)) for _ in range(2))
+    Wo = q(rng.standard_normal((w.C, w.C)) / np.sqrt(w.C)) if use_wo else None
+    print(f"[cross] {case}: L={L} C={w.C} heads={w.heads} context {t_ctx} x {c_ctx} Wo={use_wo}", flush=True)
+    dv = tg.Device(w, inp, 1)
+    dt = w.dtype
+    O = torch.empty((w.B, L, w.C), dtype=dv.X.dtype, device="cuda")
+    tb.toma_cross_attend(dv.desc, dv.attn, tg.dev(U, dt), tg.dev(Ctx, dt), tg.dev(Wq, dt), tg.dev(Wk, dt), tg.dev(Wv, dt),
+                         None if Wo is None else tg.dev(Wo, dt), O, dv.ws)
+    torch.cuda.synchronize()
+    ref = oracle.cross_attend(_f64(U), _f64(Ctx), _f64(Wq), _f64(Wk), _f64(Wv), w.heads, Wo=None if Wo is None else _f64(Wo))
+    _check_stage("O (cross-attention)", tg.host(O), ref, tol)
+
+
+def test_block_with_one_merge_and_three_modules(oracle, cases):
+    """A transformer block in the ToMA_once style (Sec. 5.1): one merge, then self-attention,
+    cross-attention to a text-like context and the feed-forward module, all on the merged tokens
+    (residual paths left out), one unmerge; chained on the device and in the oracle."""
+    w, inp = cases["small_bf16"]
+    tol = tg.TOL[w.dtype]
+    rng = np.random.default_rng(62)
+    q = lambda a: synth.quantize(w, np.asarray(a, np.float32))
+    hidden, t_ctx, c_ctx = 4 * w.C, 77, 128
+    W1, W2 = q(rng.standard_normal((w.C, hidden)) / np.sqrt(w.C)), q(rng.standard_normal((hidden, w.C)) / np.sqrt(hidden))
+    Ctx = q(rng.standard_normal((w.B, t_ctx, c_ctx)))
+    Cq = q(rng.standard_normal((w.C, w.C)) / np.sqrt(w.C))
+    Ck, Cv = (q(rng.standard_normal((c_ctx, w.C)) / np.sqrt(c_ctx)) for _ in range(2))
+    X = _f64(inp["X"])
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    d = tg.oracle_desc(oracle, w, 1)
+    idx, _, _ = oracle.select(d, X)
+    A, Z, _ = oracle.merge_weights(d, X, idx)
+    Xm = oracle.merge(d, X, A, Z)
+    O1 = oracle.attend(Xm, None, *Wts, heads=w.heads)
+    O2 = oracle.cross_attend(O1, _f64(Ctx), _f64(Cq), _f64(Ck), _f64(Cv), w.heads)
+    F = oracle.mlp(O2, _f64(W1), _f64(W2))
+    Y_ref = oracle.unmerge(d, A, Z, F)
+    dv = tg.Device(w, inp, 1)
+    dt = w.dtype
+    dv.merge(idx=idx)
+    dv.attend()
+    O2d = torch.empty_like(dv.O)
+    tb.toma_cross_attend(dv.desc, dv.attn, dv.O, tg.dev(Ctx, dt), tg.dev(Cq, dt), tg.dev(Ck, dt), tg.dev(Cv, dt), None,
+                         O2d, dv.ws)
+    Hb = torch.empty((w.B * w.D, hidden), dtype=dv.O.dtype, device="cuda")
+    tb.toma_mlp(O2d, tg.dev(W1, dt), tg.dev(W2, dt), Hb, dv.O)
+    _check_stage("Y after merge, attention, cross-attention, mlp, unmerge", dv.unmerge(), Y_ref, tol)
+
+
+@pytest.mark.parametrize("tile_local", [False, True])
+def test_two_layers_share_one_pattern(oracle, cases, tile_local):
+    """Sec. 4.3.2: destinations and merge weights are shared across layers of a block type.  Layer 1
+    computes the pattern on its tokens; layer 2 has different tokens and different projections and
+    runs on the cached (A, Z, block map) of layer 1; both against the oracle doing the same."""
+    w, inp = cases["small_bf16"]
+    R = w.P if tile_local else 1
+    tol = tg.TOL[w.dtype]
+    rng = np.random.default_rng(63)
+    q = lambda a: synth.quantize(w, np.asarray(a, np.float32))
+    X1 = _f64(inp["X"])
+    W1 = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    X2f = q(0.7 * inp["X"] + 0.7 * rng.standard_normal(inp["X"].shape))       # another layer's hidden states
+    W2f = [q(rng.standard_normal((w.C, w.C)) / np.sqrt(w.C)) for _ in range(3)]
+    d = tg.oracle_desc(oracle, w, R)
+    ref1 = oracle.layer(d, X1, *W1, heads=w.heads)
+    ref2 = oracle.layer(d, _f64(X2f), *[_f64(a) for a in W2f], heads=w.heads, idx=ref1["idx"], AZ=(ref1["A"], ref1["Z"]))
+    dv = tg.Device(w, inp, R)
+    Y1, _ = dv.layer(0)
+    _check_stage("Y layer 1", Y1, ref1["Y"], tol)
+    A1, Z1 = tg.host(dv.A), tg.host(dv.Z)
+    dv.Wq, dv.Wk, dv.Wv = (tg.dev(a, w.dtype) for a in W2f)
+    Y2, _ = dv.layer(tb.TOMA_REUSE_A, X=X2f)
+    _check_stage("Y layer 2 on layer 1's pattern", Y2, ref2["Y"], tol)
+    assert np.array_equal(tg.host(dv.A), A1) and np.array_equal(tg.host(dv.Z), Z1)
+    # and it differs from what layer 2's own pattern would give (the cache is really what was used)
+    own = oracle.layer(d, _f64(X2f), *[_f64(a) for a in W2f], heads=w.heads)
+    assert tg.max_rel(own["Y"], ref2["Y"]) > 10 * tol or not np.array_equal(own["idx"], ref1["idx"])
+
+
+def _clean_rcond(oracle, d, A, Z):
+    """A cut-off with no singular value of any region's A~ near it (a value sitting on the cut could
+    fall on either side in the two evaluations), and the spectrum's summary."""
+    sv, dev = oracle.merge_matrix_spectrum(d, A, Z)
+    rel = sv / np.maximum(sv.max(axis=2, keepdims=True), 1e-300)
+    for rcond in (1e-2, 3e-3, 3e-2, 1e-3):
+        if not np.any((rel > rcond / 6) & (rel < rcond * 6)):
+            return rcond, rel, dev
+    pytest.skip("no clean gap in the spectrum of the merge matrices")
+
+
+@pytest.mark.parametrize("case,tile_local", [("tiny", False), ("tiny", True), ("small_bf16", True), ("extra", True),
+                                             ("stripe", True)])
+def test_pinv_unmerge(oracle, cases, case, tile_local):
+    """Moore-Penrose unmerge (Sec. 4.2.2) of the library's own stored (A, Z): against numpy's
+    pseudo-inverse of the same matrices in float64, with the cut-off placed in a gap of the spectrum."""
+    w, inp = cases[case]
+    R = w.P if tile_local else 1
+    tol = tg.TOL[w.dtype]
+    rng = np.random.default_rng(71)
+    d = tg.oracle_desc(oracle, w, R)
+    dv = tg.Device(w, inp, R)
+    idx, _, _ = oracle.select(d, _f64(inp["X"]))
+    A, Z, _ = dv.merge(idx=idx)
+    rcond, rel, dev = _clean_rcond(oracle, d, A, np.maximum(Z, 1e-20))
+    below = int((rel <= rcond).sum())
+    print(f"[pinv] {case} merge_regions={R}: Dr={w.D // R} rcond={rcond:g}; singular values below the cut: {below} of "
+          f"{rel.size}; ||A~A~^T - I||_2 max {dev.max():.3f} median {np.median(dev):.3f}", flush=True)
+    O = synth.quantize(w, rng.standard_normal((w.B, w.D + w.T_extra, w.C)).astype(np.float32))
+    dv.O.copy_(tg.dev(O, w.dtype))
+    tb.toma_unmerge_pinv(dv.desc, dv.A, dv.Z, dv.O, rcond, dv.Y, dv.ws)
+    torch.cuda.synchronize()
+    Y_ref = oracle.unmerge_pinv(d, A, np.maximum(Z, 1e-20), _f64(O), rcond)
+    _check_stage("Y (pseudo-inverse unmerge)", tg.host(dv.Y), Y_ref, tol)
+    # it is not the transpose unmerge in disguise (the merge matrices here are far from orthonormal)
+    assert tg.max_rel(oracle.unmerge(d, A, np.maximum(Z, 1e-20), _f64(O)), Y_ref) > 10 * tol
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_pinv_unmerge_of_rank_deficient_weights(oracle, dtype):
+    """Planted merge matrices whose rows are dependent in every way the cut has to handle: a destination
+    with no weight (zero row), two destinations with identical rows, and a row that is a combination of
+    two others - against numpy's pseudo-inverse (least-squares, minimum-norm answer)."""
+    w = synth.scaled(W["tiny"], name="pinv_planted", dtype=dtype, B=2, H=16, W=16, C=64, tile_h=8, tile_w=8, keep=0.5,
+                     heads=1, index=27)
+    inp = synth.make_inputs(w)
+    R, tol = w.P, tg.TOL[dtype]
+    rng = np.random.default_rng(72)
+    d = tg.oracle_desc(oracle, w, R)
+    dv = tg.Device(w, inp, R)
+    Dr, Nr = w.d_loc, w.n_loc
+    A = (rng.uniform(0.25, 1.0, (w.B, R, Dr, Nr)) * (rng.uniform(size=(w.B, R, Dr, Nr)) < 0.15)).astype(np.float32)
+    A[..., np.arange(Dr), np.arange(Dr)] += 0.5              # every destination weighs a source of its own
+    A[0, 1, 3] = 0.0                                         # nobody chose destination 3 of region 1
+    A[1, 0, 7] = A[1, 0, 2]                                  # identical rows
+    A[1, 2, 9] = 0.5 * A[1, 2, 4] + 0.25 * A[1, 2, 5]        # a dependent row (exact in bf16: powers of two)
+    A = _f64(synth.quantize(w, A))
+    A[1, 2, 9] = 0.5 * A[1, 2, 4] + 0.25 * A[1, 2, 5]
+    A = _f64(synth.quantize(w, A.astype(np.float32)))
+    Z = A.sum(axis=3).reshape(w.B, w.D)
+    dv.plant(A, Z)
+    rcond, rel, dev = _clean_rcond(oracle, d, A, np.maximum(Z, 1e-20))
+    below = (rel <= rcond).sum(axis=2)
+    print(f"[pinv planted] {dtype}: rcond={rcond:g}, singular values below the cut per region: {below.tolist()}", flush=True)
+    assert below[0, 1] >= 1 and below[1, 0] >= 1 and below[1, 2] >= 1
+    O = synth.quantize(w, rng.standard_normal((w.B, w.D, w.C)).astype(np.float32))
+    dv.O.copy_(tg.dev(O, dtype))
+    tb.toma_unmerge_pinv(dv.desc, dv.A, dv.Z, dv.O, rcond, dv.Y, dv.ws)
+    torch.cuda.synchronize()
+    _check_stage("Y (pseudo-inverse unmerge, deficient rank)", tg.host(dv.Y),
+                 oracle.unmerge_pinv(d, A, np.maximum(Z, 1e-20), _f64(O), rcond), tol)
+
+
 def test_binding_reports_errors_on_device():
     w, = (W["tiny"],)
     inp = synth.make_inputs(w)
