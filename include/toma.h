@@ -196,6 +196,28 @@ int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, const voi
                  int32_t o_rows, void *Y, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Merge and unmerge with the weights recomputed instead of stored (Sec. 4.2.1: the merge weights ARE
+ * scaled dot-product attention, A = SDPA(X, D, I, tau), so A~ X and A~^T X' can be evaluated as
+ * attention-shaped products without A ever existing in memory: useful where A is not reused across
+ * steps, or is large - one merge region over a 128 x 128 grid stores half a gigabyte).
+ *   toma_merge_recompute    Z_j = sum_s A_js and Xm_j = (1 / Z_j) sum_s A_js x_s with A_js evaluated on
+ *                           the fly; also fills wcache
+ *   toma_unmerge_recompute  Y[token(s)] = sum_j A_js O_j / Z_j for the SAME X and idx
+ *   wcache  toma_recompute_cache_bytes(desc) bytes, 256-byte aligned, caller-owned, opaque: per source
+ *           token the normaliser of its softmax over the destinations, and per (source, slice of
+ *           destinations) the evidence by which tiles of weights that are entirely zero are skipped -
+ *           O(N * D / 64) floats instead of A's N * D elements
+ * Results agree with toma_merge / toma_unmerge to rounding (the weights enter the products rounded to
+ * the element type here as there).  Limits: C <= 3072, at most 65536 tokens per merge region.
+ */
+size_t toma_recompute_cache_bytes(const toma_desc *desc);
+int toma_merge_recompute(const toma_desc *desc, const void *X, const int32_t *idx, float *Z, void *wcache,
+                         void *Xm, void *ws, size_t ws_bytes, void *stream);
+int toma_unmerge_recompute(const toma_desc *desc, const void *X, const int32_t *idx, const float *Z,
+                           const void *wcache, const void *O, int32_t o_rows, void *Y, void *ws,
+                           size_t ws_bytes, void *stream);
+
+/*
  * Moore-Penrose unmerge (Sec. 4.2.2, first display; the alternative the paper measures the transpose
  * against in App. E.4): Y[token(s)] = sum_j (A~^+)_sj O_j with A~ = A / Z the row-normalised merge
  * matrix of each merge region and A~^+ its pseudo-inverse, = A~^T (A~ A~^T)^-1 when the rows of A~ are
@@ -219,10 +241,13 @@ int toma_unmerge_pinv(const toma_desc *desc, const void *A, const float *Z, cons
  *   0                  select, weights, merge, attention, unmerge; idx, A, Z, amap are written
  *   TOMA_REUSE_IDX     idx is read; weights are recomputed; A, Z, amap are written
  *   TOMA_REUSE_A       idx is ignored, A, Z and amap are read (implies TOMA_REUSE_IDX)
+ *   TOMA_RECOMPUTE_WEIGHTS   (alone or with TOMA_REUSE_IDX) no A is written or read: the merge and the
+ *                      unmerge recompute the weights (toma_merge_recompute / toma_unmerge_recompute);
+ *                      A and amap may be NULL; Z is written
  *   Y            out  [B, N, C]
  *   Y_extra_opt  out  [B, t_extra, C]  rows of O that belong to the extra tokens (NULL iff none)
  */
-enum { TOMA_REUSE_IDX = 1, TOMA_REUSE_A = 2 };
+enum { TOMA_REUSE_IDX = 1, TOMA_REUSE_A = 2, TOMA_RECOMPUTE_WEIGHTS = 4 };
 int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint32_t reuse_flags,
                const void *X, const void *X_extra_opt, int32_t *idx, void *A, float *Z, void *amap,
                const void *Wq, const void *Wk, const void *Wv, const void *Wo_opt, void *Y,

@@ -13,9 +13,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtoma.so")
 
 TOMA_F32, TOMA_BF16 = 0, 1
-TOMA_REUSE_IDX, TOMA_REUSE_A = 1, 2
+TOMA_REUSE_IDX, TOMA_REUSE_A, TOMA_RECOMPUTE_WEIGHTS = 1, 2, 4
 EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_select_static", "toma_merge", "toma_map_bytes",
-           "toma_map_build", "toma_merge_cached", "toma_attend", "toma_cross_attend", "toma_unmerge", "toma_unmerge_pinv", "toma_layer", "toma_mlp", "toma_profile_enable",
+           "toma_map_build", "toma_merge_cached", "toma_attend", "toma_cross_attend", "toma_unmerge", "toma_unmerge_pinv", "toma_recompute_cache_bytes", "toma_merge_recompute",
+           "toma_unmerge_recompute", "toma_layer", "toma_mlp", "toma_profile_enable",
            "toma_profile_kernel_name", "toma_profile_read", "toma_profile_map_product")
 
 
@@ -76,11 +77,18 @@ def lib():
         L.toma_cross_attend.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_cross_attend.restype = ctypes.c_int
         L.toma_unmerge.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
+        L.toma_recompute_cache_bytes.restype = ctypes.c_size_t
+        L.toma_recompute_cache_bytes.argtypes = [vp]
+        L.toma_merge_recompute.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.toma_merge_recompute.restype = ctypes.c_int
+        L.toma_unmerge_recompute.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, sz, vp]
+        L.toma_unmerge_recompute.restype = ctypes.c_int
         L.toma_unmerge_pinv.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_float, vp, vp, sz, vp]
         L.toma_unmerge_pinv.restype = ctypes.c_int
         L.toma_layer.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.toma_mlp.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
-        for name in ("toma_select", "toma_merge", "toma_map_build", "toma_merge_cached", "toma_attend", "toma_cross_attend", "toma_unmerge", "toma_unmerge_pinv",
+        for name in ("toma_select", "toma_merge", "toma_map_build", "toma_merge_cached", "toma_attend", "toma_cross_attend", "toma_unmerge", "toma_unmerge_pinv", "toma_recompute_cache_bytes", "toma_merge_recompute",
+           "toma_unmerge_recompute",
                      "toma_layer", "toma_mlp"):
             getattr(L, name).restype = ctypes.c_int
         L.toma_profile_enable.argtypes = [ctypes.c_int]
@@ -180,6 +188,20 @@ def toma_cross_attend(desc, attn, U, Ctx, Wq, Wk, Wv, Wo, O, ws):
 def toma_unmerge(desc, A, Z, amap, O, Y, ws):
     _check(lib().toma_unmerge(_ref(desc), _ptr(A), _ptr(Z), _ptr(amap), _ptr(O), O.shape[1], _ptr(Y), _ptr(ws),
                               ws.numel(), _stream()), "toma_unmerge")
+
+
+def toma_recompute_cache_bytes(desc):
+    return lib().toma_recompute_cache_bytes(_ref(desc))
+
+
+def toma_merge_recompute(desc, X, idx, Z, wcache, Xm, ws):
+    _check(lib().toma_merge_recompute(_ref(desc), _ptr(X), _ptr(idx), _ptr(Z), _ptr(wcache), _ptr(Xm), _ptr(ws),
+                                      ws.numel(), _stream()), "toma_merge_recompute")
+
+
+def toma_unmerge_recompute(desc, X, idx, Z, wcache, O, Y, ws):
+    _check(lib().toma_unmerge_recompute(_ref(desc), _ptr(X), _ptr(idx), _ptr(Z), _ptr(wcache), _ptr(O), O.shape[1],
+                                        _ptr(Y), _ptr(ws), ws.numel(), _stream()), "toma_unmerge_recompute")
 
 
 def toma_unmerge_pinv(desc, A, Z, O, rcond, Y, ws):

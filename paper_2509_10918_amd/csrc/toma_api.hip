@@ -53,10 +53,9 @@ void plan_workspace(const Shape &s, Workspace *w) {
   auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
   // row strides of the partial-result arrays: one entry per wave slice of the weights product
   // (sources x destinations x C), whose block tile is planned here exactly as at launch
-  if (weights_single_pass(s.Nr, s.Dr, s.C, s.B * s.R, (int)es)) {
-    w->stat_parts = 1;           // (unused by the single-pass kernel)
-    w->z_parts = s.Nr / 32;      // one partial row sum per 32-source workgroup
-  } else if (gemm_async_fits(s.Nr, s.Dr, s.C, (int)es)) {
+  // (the statistics pass always gets its room: the single-pass weights kernel does not use it, the
+  // entry points that recompute weights instead of storing them do)
+  if (gemm_async_fits(s.Nr, s.Dr, s.C, (int)es)) {
     const GemmPlan pw = plan_gemm_async(s.Nr, s.Dr, s.C, s.B * s.R, (int)es, false, false, false, 3);
     w->stat_parts = 2 * ((s.Dr + pw.bn - 1) / pw.bn);
     w->z_parts = 4 * ((s.Nr + pw.bm - 1) / pw.bm);
@@ -64,6 +63,7 @@ void plan_workspace(const Shape &s, Workspace *w) {
     w->stat_parts = 2 * ((s.Dr + 63) / 64);
     w->z_parts = 2 * ((s.Nr + 63) / 64);
   }
+  if (weights_single_pass(s.Nr, s.Dr, s.C, s.B * s.R, (int)es)) w->z_parts = s.Nr / 32;  // one partial row sum per 32-source workgroup
   w->sim = take((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(float));
   w->stats = take((size_t)s.B * s.N * w->stat_parts * 2 * sizeof(float));
   w->lse = take((size_t)s.B * s.N * sizeof(float));
@@ -84,7 +84,8 @@ void plan_workspace(const Shape &s, Workspace *w) {
     if (pu.nsplit > 1) part = std::max(part, (size_t)pu.nsplit * s.B * s.N * s.C * sizeof(float));
   }
   w->split = take(part);
-  w->pinv = take(pinv_workspace_bytes(s));  // eigenvectors and G^+ of the Moore-Penrose unmerge
+  w->pinv = take(pinv_workspace_bytes(s));
+  w->fcache = take(fused_cache_bytes(s, *w));  // statistics of recomputed weights inside one toma_layer call  // eigenvectors and G^+ of the Moore-Penrose unmerge
   // the occupancy map of A is not scratch: it belongs to the caller's cache, next to (A, Z)
   if (occupancy_pays(s.Nr, s.Dr, s.C, (int)es)) {
     w->occ_db = (s.Dr + kOccDest - 1) / kOccDest;
@@ -300,6 +301,43 @@ TOMA_API int toma_unmerge(const toma_desc *desc, const void *A, const float *Z, 
                         static_cast<hipStream_t>(stream));
 }
 
+TOMA_API size_t toma_recompute_cache_bytes(const toma_desc *desc) {
+  Shape s;
+  Workspace w;
+  if (make_shape(desc, nullptr, &s) != TOMA_OK) return 0;
+  plan_workspace(s, &w);
+  return fused_cache_bytes(s, w);
+}
+
+TOMA_API int toma_merge_recompute(const toma_desc *desc, const void *X, const int32_t *idx, float *Z, void *wcache,
+                                  void *Xm, void *ws, size_t ws_bytes, void *stream) {
+  Shape s; Workspace w;
+  int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!X || !idx || !Z || !wcache || !Xm) return TOMA_ERR_NULL;
+  if (misaligned(X, 16) || misaligned(Xm, 16) || misaligned(Z, 4) || misaligned(idx, 4) || misaligned(wcache, 256))
+    return TOMA_ERR_ALIGN;
+  return launch_merge_fused(s, X, idx, Z, Xm, static_cast<char *>(wcache), w, static_cast<hipStream_t>(stream));
+}
+
+TOMA_API int toma_unmerge_recompute(const toma_desc *desc, const void *X, const int32_t *idx, const float *Z,
+                                    const void *wcache, const void *O, int32_t o_rows, void *Y, void *ws,
+                                    size_t ws_bytes, void *stream) {
+  Shape s; Workspace w;
+  int rc = prepare(desc, nullptr, ws, ws_bytes, &s, &w);
+  if (rc != TOMA_OK) return rc;
+  if (!X || !idx || !Z || !wcache || !O || !Y) return TOMA_ERR_NULL;
+  if (o_rows < s.D) return TOMA_ERR_SHAPE;
+  if (misaligned(X, 16) || misaligned(O, 16) || misaligned(Y, 16) || misaligned(Z, 4) || misaligned(idx, 4) ||
+      misaligned(wcache, 256))
+    return TOMA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char *wsb = static_cast<char *>(ws);
+  rc = launch_scale_rows(s, O, Z, o_rows, wsb + w.os, st);
+  if (rc != TOMA_OK) return rc;
+  return launch_unmerge_fused(s, X, idx, static_cast<const char *>(wcache), wsb + w.os, s.D, Y, w, st);
+}
+
 TOMA_API int toma_unmerge_pinv(const toma_desc *desc, const void *A, const float *Z, const void *O, int32_t o_rows,
                                float rcond, void *Y, void *ws, size_t ws_bytes, void *stream) {
   Shape s; Workspace w;
@@ -320,10 +358,12 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
   Shape s; Workspace w;
   int rc = prepare(desc, attn, ws, ws_bytes, &s, &w);
   if (rc != TOMA_OK) return rc;
-  if (reuse_flags & ~(uint32_t)(TOMA_REUSE_IDX | TOMA_REUSE_A)) return TOMA_ERR_UNSUPPORTED;
+  if (reuse_flags & ~(uint32_t)(TOMA_REUSE_IDX | TOMA_REUSE_A | TOMA_RECOMPUTE_WEIGHTS)) return TOMA_ERR_UNSUPPORTED;
+  const bool recompute = (reuse_flags & TOMA_RECOMPUTE_WEIGHTS) != 0;
+  if (recompute && (reuse_flags & TOMA_REUSE_A)) return TOMA_ERR_UNSUPPORTED;  // there is no A to reuse
   const bool reuse_a = (reuse_flags & TOMA_REUSE_A) != 0;
   const bool reuse_idx = reuse_a || (reuse_flags & TOMA_REUSE_IDX) != 0;
-  if (!X || !A || !Z || !Wq || !Wk || !Wv || !Y) return TOMA_ERR_NULL;
+  if (!X || (!A && !recompute) || !Z || !Wq || !Wk || !Wv || !Y) return TOMA_ERR_NULL;
   if (!reuse_a && !idx) return TOMA_ERR_NULL;
   if ((s.T > 0) != (X_extra_opt != nullptr) || (s.T > 0) != (Y_extra_opt != nullptr)) return TOMA_ERR_NULL;
   if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Y, 16) || misaligned(Z, 4) || misaligned(Wq, 16) ||
@@ -331,7 +371,7 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
       (X_extra_opt && misaligned(X_extra_opt, 16)) || (Y_extra_opt && misaligned(Y_extra_opt, 16)) ||
       (Wo_opt && misaligned(Wo_opt, 16)))
     return TOMA_ERR_ALIGN;
-  rc = check_map(w, amap);
+  rc = recompute ? TOMA_OK : check_map(w, amap);
   if (rc != TOMA_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char *wsb = static_cast<char *>(ws);
@@ -342,17 +382,22 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
     rc = launch_select(s, X, idx, nullptr, nullptr, wsb, w, st);
     if (rc != TOMA_OK) return rc;
   }
-  if (!reuse_a) {  // (a cached A comes with its map)
-    rc = launch_weights(s, X, idx, A, Z, occ, wsb, w, st);
-    if (rc != TOMA_OK) return rc;
+  if (recompute) {  // no A: the weights are recomputed inside the merge and again inside the unmerge
+    rc = launch_merge_fused(s, X, idx, Z, Xm, wsb + w.fcache, w, st);
+  } else {
+    if (!reuse_a) {  // (a cached A comes with its map)
+      rc = launch_weights(s, X, idx, A, Z, occ, wsb, w, st);
+      if (rc != TOMA_OK) return rc;
+    }
+    rc = launch_merge(s, X, A, Z, occ, Xm, wsb, w, st);
   }
-  rc = launch_merge(s, X, A, Z, occ, Xm, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   // inside the layer the attention writes its merged rows already divided by Z (the unmerge's
   // input), so no separate scaling pass runs; the extra-token rows stay as they are
   rc = launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, Z, wsb, w, st);
   if (rc != TOMA_OK) return rc;
-  rc = launch_unmerge(s, A, Z, occ, O, s.L, true, Y, wsb, w, st);
+  rc = recompute ? launch_unmerge_fused(s, X, idx, wsb + w.fcache, O, s.L, Y, w, st)
+                 : launch_unmerge(s, A, Z, occ, O, s.L, true, Y, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   if (s.T > 0) rc = launch_copy_extra(s, O, Y_extra_opt, st);
   return rc;

@@ -697,6 +697,13 @@ inline GemmShape choose_gemm_shape(int M, int N, int batch) {
   return make_gemm_shape(M, N, 64, 64, 2, 2);
 }
 
+// Width (in columns) of one wave's slice of the block tile that launch_gemm picks for a product that
+// may not split K: the granularity of per-slice results such as the weights' statistics.
+inline int weight_stats_slice(int M, int N, int K, int batch, int elem_size) {
+  if (gemm_async_fits(M, N, K, elem_size)) return plan_gemm_async(M, N, K, batch, elem_size, false, false, false, 3).bn / 2;
+  return choose_gemm_shape(M, N, batch).bn / 2;
+}
+
 template <typename T, typename Pol>
 inline GemmShape launch_gemm(int kernel_id, const Pol &pol, int M, int N, int K, int batch, hipStream_t st) {
   if (gemm_async_fits(M, N, K, (int)sizeof(T))) {

@@ -21,7 +21,7 @@ struct Shape {
 
 // Offsets (bytes) of the scratch sections inside the caller's workspace.
 struct Workspace {
-  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, pinv, total;
+  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, pinv, fcache, total;
   int stat_parts, z_parts;
   // occupancy map of A, kept by the caller next to (A, Z): blocks of kOccDest destinations x kOccSrc
   // sources per merge region (0: this shape uses none)
@@ -129,6 +129,10 @@ void plan_workspace(const Shape &s, Workspace *w);
 // gain, gap: optional outputs (null: not wanted)
 int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, float *gap, char *ws,
                   const Workspace &w, hipStream_t st);
+// Pass 1 of the merge weights alone: stats[region][source][part] = (largest logit, sum of exponentials)
+// over each slice of *slice destinations, lse[region][source] = log-sum-exp over all destinations
+int launch_weight_stats(const Shape &s, const void *X, const int32_t *idx, float2 *stats, int stat_parts, float *lse,
+                        int *slice, hipStream_t st);
 // occ: the occupancy map that travels with (A, Z), w.occ_bytes bytes (null iff the shape uses none).
 // launch_weights writes it along with A and Z; launch_occupancy rebuilds it from a stored A;
 // launch_merge / launch_unmerge read it.
@@ -148,6 +152,16 @@ int launch_cross_attend(const Shape &s, const void *U, const void *Ctx, int t_ct
 // prescaled: the merged rows of O were already divided by Z (see launch_attend)
 int launch_unmerge(const Shape &s, const void *A, const float *Z, const uint8_t *occ, const void *O, int o_rows,
                    bool prescaled, void *Y, char *ws, const Workspace &w, hipStream_t st);
+// Os[b][j] = O[b][j] / max(Z[b][j], 1e-20) for the D merged rows of every sample
+int launch_scale_rows(const Shape &s, const void *O, const float *Z, int o_rows, void *Os, hipStream_t st);
+// Merge / unmerge with the weights recomputed instead of read from a stored A.  cache: fused_cache_bytes()
+// bytes written by launch_merge_fused (log-sum-exp per source and the statistics that say which tiles of
+// weights are empty) and read by launch_unmerge_fused; Os as for launch_unmerge with prescaled rows.
+size_t fused_cache_bytes(const Shape &s, const Workspace &w);
+int launch_merge_fused(const Shape &s, const void *X, const int32_t *idx, float *Z, void *Xm, char *cache,
+                       const Workspace &w, hipStream_t st);
+int launch_unmerge_fused(const Shape &s, const void *X, const int32_t *idx, const char *cache, const void *Os,
+                         int os_rows, void *Y, const Workspace &w, hipStream_t st);
 // Y = (A / Z)^+ O with singular values <= rcond * largest dropped; merge regions of up to 128 destinations
 size_t pinv_workspace_bytes(const Shape &s);
 int launch_unmerge_pinv(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, float rcond, void *Y,
@@ -159,7 +173,7 @@ int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const voi
 
 // Kernel identifiers of the profiling aid (toma_profile_*): one per kernel of the path.
 enum KernelId { K_GRAM = 0, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
-                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_PINV_EIG, K_PINV_APPLY, K_COUNT };
+                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_PINV_EIG, K_PINV_APPLY, K_MERGE_FUSED, K_UNMERGE_FUSED, K_COUNT };
 
 // Brackets one launch with HIP events on its stream while profiling is enabled; free otherwise.
 struct KernelTimer {

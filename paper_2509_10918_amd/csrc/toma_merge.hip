@@ -17,39 +17,9 @@
 
 #include "toma_gemm.h"
 #include "toma_internal.h"
+#include "toma_region.h"
 
 namespace toma {
-
-template <typename T> struct RegionView {
-  const T *X;
-  RegionMap map;
-  int N, C, D, R, Nr, Dr;
-  // Sources are enumerated region by region in both merge modes (local order inside a region), so
-  // that the columns of A that a region's destinations actually weigh - its own tokens and a few
-  // neighbours - are contiguous: with one merge region per sample, source s is token s % N_loc of
-  // selection region s / N_loc.
-  int sh_nloc, sh_tw, sh_pw;  // log2 of N_loc, tile_w and regions per grid row when all are powers of two, else -1
-  __device__ __forceinline__ int token(int rho, int s) const {
-    if (R != 1) return map.token(rho, s);
-    if (sh_nloc >= 0) {  // the usual shapes: no divisions
-      const int p = s >> sh_nloc, l = s & ((1 << sh_nloc) - 1);
-      const int r = (p >> sh_pw) * map.tile_h + (l >> sh_tw), c = ((p & (map.pw - 1)) << sh_tw) + (l & (map.tile_w - 1));
-      return r * map.W + c;
-    }
-    const int n_loc = map.tile_h * map.tile_w;
-    return map.token(s / n_loc, s % n_loc);
-  }
-  // token(rho, s + step) - token(rho, s) does not depend on s (inside one selection region)
-  __device__ __forceinline__ bool token_linear(int step) const {
-    if (R == 1) return map.tile_w == map.W;  // full-width regions: region order is grid order
-    return step % map.tile_w == 0;
-  }
-  // token(rho, s + i) - token(rho, s) does not depend on s for s a multiple of step and i < step:
-  // steps start on a region row and stay inside one selection region
-  __device__ __forceinline__ bool token_step_uniform(int step) const {
-    return step % map.tile_w == 0 && (map.tile_h * map.tile_w) % step == 0;
-  }
-};
 
 // ---- pass 1 and pass 2 of the weights ----------------------------------------------------------
 template <typename T, bool WRITE> struct WeightsPol {
@@ -681,15 +651,31 @@ int launch_occupancy(const Shape &s, const void *A, uint8_t *occ, const Workspac
   return launch_status();
 }
 
-template <typename T> static RegionView<T> make_view(const Shape &s, const void *X) {
-  RegionView<T> v;
-  v.X = static_cast<const T *>(X);
-  v.map = RegionMap{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
-  v.N = s.N; v.C = s.C; v.D = s.D; v.R = s.R; v.Nr = s.Nr; v.Dr = s.Dr;
-  auto log2_exact = [](int x) { int sh = 0; while ((1 << sh) < x) sh++; return (1 << sh) == x ? sh : -1; };
-  v.sh_nloc = log2_exact(s.n_loc); v.sh_tw = log2_exact(s.tile_w); v.sh_pw = log2_exact(v.map.pw);
-  if (v.sh_nloc < 0 || v.sh_tw < 0 || v.sh_pw < 0) v.sh_nloc = v.sh_tw = v.sh_pw = -1;
-  return v;
+// Pass 1 of the weights: per source row and slice of destinations (max logit, sum of exponentials),
+// then lse[source] = log sum over all destinations.  k_lse also zeroes `zero_words` words at `zero`.
+template <typename T>
+static GemmShape stats_pass(const Shape &s, const void *X, const int32_t *idx, float2 *stats, int stat_parts, float *lse,
+                            uint32_t *zero, size_t zero_words, hipStream_t st) {
+  WeightsPol<T, false> p1{};
+  p1.v = make_view<T>(s, X);
+  p1.idx = idx; p1.scale = s.scale;
+  p1.stats = stats; p1.parts = stat_parts;
+  const int batch = s.B * s.R;
+  const GemmShape gs = launch_gemm<T>(K_WSTATS, p1, s.Nr, s.Dr, s.C, batch, st);
+  const int rows = batch * s.Nr;
+  KernelTimer kt(K_LSE, st);
+  hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, stats, lse, rows, stat_parts, gs.wgn * gs.tiles_n, zero,
+                     zero_words);
+  return gs;
+}
+
+int launch_weight_stats(const Shape &s, const void *X, const int32_t *idx, float2 *stats, int stat_parts, float *lse,
+                        int *slice, hipStream_t st) {
+  const GemmShape gs = s.dtype == TOMA_BF16 ? stats_pass<bf16_t>(s, X, idx, stats, stat_parts, lse, nullptr, 0, st)
+                                            : stats_pass<float>(s, X, idx, stats, stat_parts, lse, nullptr, 0, st);
+  *slice = gs.bn / gs.wgn;
+  if (*slice != weight_stats_slice(s.Nr, s.Dr, s.C, s.B * s.R, s.dtype == TOMA_BF16 ? 2 : 4)) return TOMA_ERR_LAUNCH;
+  return launch_status();
 }
 
 template <typename T>
@@ -728,28 +714,21 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
     if (launch_status() != TOMA_OK) return TOMA_ERR_LAUNCH;
     return own_map ? TOMA_OK : launch_occupancy(s, A, occ_out, w, st);
   }
-  WeightsPol<T, false> p1{};
-  p1.v = make_view<T>(s, X);
-  p1.idx = idx; p1.scale = s.scale;
-  p1.stats = reinterpret_cast<float2 *>(ws + w.stats); p1.parts = w.stat_parts;
-  const GemmShape gs = launch_gemm<T>(K_WSTATS, p1, s.Nr, s.Dr, s.C, batch, st);
+  float2 *stats = reinterpret_cast<float2 *>(ws + w.stats);
   float *lse = reinterpret_cast<float *>(ws + w.lse);
-  int rows = batch * s.Nr;
   // the write pass fills the occupancy map too (every wave tile lies inside one block of
   // destinations: the wave slices of the planner's tiles divide kOccDest); k_lse zeroes it first
   const bool own_map = w.occ_sb != 0;
   uint8_t *occ = own_map ? occ_out : nullptr;
   const size_t occ_words = own_map ? ((size_t)batch * w.occ_db * w.occ_sb + 3) / 4 : 0;
-  { KernelTimer kt(K_LSE, st);
-    hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, p1.stats, lse, rows, w.stat_parts, gs.wgn * gs.tiles_n,
-                       reinterpret_cast<uint32_t *>(occ), occ_words); }
+  const GemmShape gs = stats_pass<T>(s, X, idx, stats, w.stat_parts, lse, reinterpret_cast<uint32_t *>(occ), occ_words, st);
   WeightsPol<T, true> p2{};
-  p2.v = p1.v; p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
+  p2.v = make_view<T>(s, X); p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
   p2.A = static_cast<T *>(A); p2.lda = s.Nr;
   p2.zpart = zpart; p2.zparts = w.z_parts;
   p2.occ = occ; p2.occ_db = w.occ_db; p2.occ_sb = w.occ_sb;
   // (pass 1 wrote one statistic per wave slice of its tiles: slices of bn / wgn destinations)
-  p2.seen = p1.stats; p2.seen_parts = w.stat_parts; p2.slice = gs.bn / gs.wgn;
+  p2.seen = stats; p2.seen_parts = w.stat_parts; p2.slice = gs.bn / gs.wgn;
   const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
   { KernelTimer kt(K_ZSUM, st);
     hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
@@ -778,6 +757,19 @@ int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, c
                  char *ws, const Workspace &w, hipStream_t st) {
   return s.dtype == TOMA_BF16 ? merge_typed<bf16_t>(s, X, A, Z, occ, Xm, ws, w, st)
                               : merge_typed<float>(s, X, A, Z, occ, Xm, ws, w, st);
+}
+
+int launch_scale_rows(const Shape &s, const void *O, const float *Z, int o_rows, void *Os, hipStream_t st) {
+  const size_t total = (size_t)s.B * s.D * s.C;
+  KernelTimer kt(K_SCALE, st);
+  const dim3 grid((unsigned)((total + 255) / 256));
+  if (s.dtype == TOMA_BF16)
+    hipLaunchKernelGGL(k_scale_rows<bf16_t>, grid, dim3(256), 0, st, static_cast<const bf16_t *>(O), Z,
+                       static_cast<bf16_t *>(Os), s.D, o_rows, s.C, total);
+  else
+    hipLaunchKernelGGL(k_scale_rows<float>, grid, dim3(256), 0, st, static_cast<const float *>(O), Z,
+                       static_cast<float *>(Os), s.D, o_rows, s.C, total);
+  return launch_status();
 }
 
 template <typename T>

@@ -90,7 +90,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.toma_attend(dp, None, x, None, x, x, x, None, x, ws, need, None) == 1
     assert L.toma_attend(dp, ap, x, x, x, x, x, None, x, ws, need, None) == 1   # extra tokens given, t_extra == 0
     assert L.toma_unmerge(dp, x, x, x, x, 100, x, ws, need, None) == 2          # fewer rows than D
-    assert L.toma_layer(dp, ap, 4, x, None, x, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
+    assert L.toma_layer(dp, ap, 16, x, None, x, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
     assert L.toma_layer(dp, ap, 0, x, None, None, x, x, x, x, x, x, None, x, None, ws, need, None) == 1
     # cross-attention: context shape and size limits, null checks
     assert L.toma_cross_attend(dp, ap, x, x, 77, 2048, x, x, x, None, None, ws, need, None) == 1
@@ -106,6 +106,14 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.toma_unmerge_pinv(tlp, x, x, x, 100, ctypes.c_float(1e-2), x, ws, need_tl, None) == 2
     assert L.toma_unmerge_pinv(tlp, x, None, x, 2048, ctypes.c_float(1e-2), x, ws, need_tl, None) == 1
     assert L.toma_unmerge_pinv(tlp, x, x, x, 2048, ctypes.c_float(1e-2), x, ws, tb.toma_workspace_bytes(tl, None) - 1, None) == 4
+    # recomputed weights: cache size, null and alignment checks, flag combinations of the layer
+    assert tb.toma_recompute_cache_bytes(d) > 2 * 4096 * 4 and tb.toma_recompute_cache_bytes(None) == 0
+    assert L.toma_merge_recompute(dp, x, x, x, None, x, ws, need, None) == 1
+    assert L.toma_merge_recompute(dp, x, x, x, x + 16, x, ws, need, None) == 3
+    assert L.toma_unmerge_recompute(dp, x, x, x, x, x, 100, x, ws, need, None) == 2
+    assert L.toma_unmerge_recompute(dp, x, x, None, x, x, 2048, x, ws, need, None) == 1
+    assert L.toma_layer(dp, ap, 4 | 2, x, None, x, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
+    assert L.toma_layer(dp, ap, 8, x, None, x, x, x, x, x, x, x, None, x, None, ws, need, None) == 5
     # feed-forward module: dtype, shape, divisibility, null and alignment checks
     assert L.toma_mlp(1, 4096, 640, 2560, x, x, x, x, None, None) == 1
     assert L.toma_mlp(1, 0, 640, 2560, x, x, x, x, x, None) == 2

@@ -57,6 +57,12 @@ def test_full_workload_layer(oracle, name, tile_local):
     Yi, _ = dv.layer(tb.TOMA_REUSE_IDX)
     Ya, _ = dv.layer(tb.TOMA_REUSE_A)
     assert np.array_equal(Yi, Y) and np.array_equal(Ya, Y)
+    # the same layer with the weights recomputed inside merge and unmerge instead of stored (Sec. 4.2.1)
+    Yr, Yre = dv.layer(tb.TOMA_RECOMPUTE_WEIGHTS | tb.TOMA_REUSE_IDX)
+    _report("Z (recomputed weights)", tg.host(dv.Z), ref["Z"], tol)
+    _report("Y (recomputed weights)", Yr, ref["Y"], tol)
+    if Yre is not None:
+        _report("Y_extra (recomputed weights)", Yre, ref["Y_extra"], tol)
 
 
 @pytest.mark.timeout(1500)
@@ -96,7 +102,12 @@ def test_hires_reuse_sequence_global(oracle):
             assert np.array_equal(dv.idx.cpu().numpy(), idx)
             _report("Z step 0", tg.host(dv.Z), Z, tol)
             _report("Y step 0", Y, ref["Y"], tol)
-            del ref
+            # the same step with the weights recomputed instead of stored (no half-gigabyte A)
+            A_keep = dv.A.clone()
+            Yr, _ = dv.layer(tb.TOMA_RECOMPUTE_WEIGHTS | tb.TOMA_REUSE_IDX, X=Xt)
+            _report("Y step 0 (recomputed weights)", Yr, ref["Y"], tol)
+            assert torch.equal(dv.A, A_keep)
+            del ref, A_keep
             continue
         if sel:
             idx, _, _ = oracle.select(d, X)

@@ -634,6 +634,69 @@ def test_pinv_unmerge_of_rank_deficient_weights(oracle, dtype):
                  oracle.unmerge_pinv(d, A, np.maximum(Z, 1e-20), _f64(O), rcond), tol)
 
 
+@pytest.mark.parametrize("tile_local", [False, True])
+@pytest.mark.parametrize("name", list(CASES))
+def test_merge_unmerge_with_recomputed_weights(oracle, cases, name, tile_local):
+    """Sec. 4.2.1's attention form of the merge: Z, the merged tokens and the unmerged output with
+    the weights evaluated on the fly (no A in memory) against the oracle's definitions, and the whole
+    layer through the same path (alone and on cached picks)."""
+    w, inp = cases[name]
+    R = w.P if tile_local else 1
+    tol = tg.TOL[w.dtype]
+    print(f"[recompute] {name} merge_regions={R}", flush=True)
+    X = _f64(inp["X"])
+    Xe = None if inp["X_extra"] is None else _f64(inp["X_extra"])
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    d = tg.oracle_desc(oracle, w, R)
+    ref = oracle.layer(d, X, *Wts, heads=w.heads, Xe=Xe)
+    dv = tg.Device(w, inp, R)
+    Z, Xm = dv.merge_recompute(idx=ref["idx"])
+    _check_stage("Z", Z, ref["Z"], tol)
+    _check_stage("Xm", Xm, ref["Xm"], tol)
+    rng = np.random.default_rng(91)
+    O_in = synth.quantize(w, rng.standard_normal((w.B, w.D + w.T_extra, w.C)).astype(np.float32))
+    Y = dv.unmerge_recompute(O=O_in)
+    _check_stage("Y", Y, oracle.unmerge(d, ref["A"], ref["Z"], _f64(O_in)), tol)
+    dv.A.zero_()     # the layer through this path neither reads nor writes A
+    Yl, Ye = dv.layer(tb.TOMA_RECOMPUTE_WEIGHTS)
+    bad, _, _ = tg.compare_picks(oracle, w, X, dv.idx.cpu().numpy())
+    assert not bad
+    _check_stage("Y (layer)", Yl, ref["Y"], tol)
+    if Ye is not None:
+        _check_stage("Y_extra (layer)", Ye, ref["Y_extra"], tol)
+    assert not dv.A.any()
+    Yi, _ = dv.layer(tb.TOMA_RECOMPUTE_WEIGHTS | tb.TOMA_REUSE_IDX)
+    assert np.array_equal(Yi, Yl)
+    with pytest.raises(tb.TomaError):
+        dv.layer(tb.TOMA_RECOMPUTE_WEIGHTS | tb.TOMA_REUSE_A)
+
+
+@pytest.mark.parametrize("dtype,tau,C", [("bf16", 0.1, 64), ("bf16", 3.0, 64), ("bf16", 100.0, 64), ("bf16", 0.1, 1024),
+                                         ("bf16", 3.0, 1280), ("bf16", 1.0, 3072), ("f32", 0.1, 32), ("f32", 2.0, 320),
+                                         ("f32", 8.0, 1024)])
+def test_recomputed_weights_skip_only_empty_tiles(oracle, dtype, tau, C):
+    """Temperatures from almost one-hot weights (nearly every tile of weights skipped) to almost uniform
+    ones (none skipped), and every channel width the kernel is instantiated for: recomputed merge and
+    unmerge against the dense definitions."""
+    big = C > 640
+    w = synth.scaled(W["tiny"], name="rc", dtype=dtype, B=2 if not big else 1, H=32 if big else 64, W=32 if big else 64,
+                     C=C, tile_h=16, tile_w=16, keep=0.5, heads=max(1, C // 64), tau=tau, index=29)
+    print(f"[recompute tiles] {dtype} tau={tau} C={C} N={w.N} D={w.D}", flush=True)
+    inp = synth.make_inputs(w)
+    tol = tg.TOL[dtype]
+    X = _f64(inp["X"])
+    d = tg.oracle_desc(oracle, w, 1)
+    idx, _, _ = oracle.select(d, X)
+    A_ref, Z_ref, _ = oracle.merge_weights(d, X, idx)
+    dv = tg.Device(w, inp, 1)
+    Z, Xm = dv.merge_recompute(idx=idx)
+    _check_stage("Z", Z, Z_ref, tol)
+    _check_stage("Xm", Xm, oracle.merge(d, X, A_ref, Z_ref), tol)
+    rng = np.random.default_rng(92)
+    O_in = synth.quantize(w, rng.standard_normal((w.B, w.D, w.C)).astype(np.float32))
+    _check_stage("Y", dv.unmerge_recompute(O=O_in), oracle.unmerge(d, A_ref, Z_ref, _f64(O_in)), tol)
+
+
 def test_binding_reports_errors_on_device():
     w, = (W["tiny"],)
     inp = synth.make_inputs(w)

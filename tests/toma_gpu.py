@@ -116,6 +116,23 @@ class Device:
         torch.cuda.synchronize()
         return host(self.Xm)
 
+    def merge_recompute(self, idx=None):
+        """Merge with the weights recomputed on the fly: (Z, Xm); fills the statistics cache."""
+        if idx is not None:
+            self.idx.copy_(torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)))
+        if not hasattr(self, "wcache"):
+            self.wcache = torch.empty(tb.toma_recompute_cache_bytes(self.desc), dtype=torch.uint8, device="cuda")
+        tb.toma_merge_recompute(self.desc, self.X, self.idx, self.Z, self.wcache, self.Xm, self.ws)
+        torch.cuda.synchronize()
+        return host(self.Z), host(self.Xm)
+
+    def unmerge_recompute(self, O=None):
+        if O is not None:
+            self.O.copy_(dev(O, self.w.dtype))
+        tb.toma_unmerge_recompute(self.desc, self.X, self.idx, self.Z, self.wcache, self.O, self.Y, self.ws)
+        torch.cuda.synchronize()
+        return host(self.Y)
+
     def attend(self, Xm=None, Wo=None):
         if Xm is not None:
             self.Xm.copy_(dev(Xm, self.w.dtype))
