@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 METRIC = "µs per merge+attn+unmerge layer call (SDXL 4096×640); % bf16 MFMA / HBM roofline"
-PEAK = {"hbm": 8000.0, "bf16": 2500.0, "f32": 157.3, "f64": 78.6}   # GB/s, TFLOP/s (MI355X, dense)
+PEAK = {"hbm": 8000.0, "bf16": 2500.0, "f32": 157.3, "f64": 78.6, "i8": 5000.0}   # GB/s, TFLOP/s, TOP/s (MI355X, dense)
 
 
 def executed_fraction(amap, desc, which, tile, esize):
@@ -60,9 +60,19 @@ def kernel_work(w, R, esize, exec_frac=None):
     tiles = w.n_loc // 16
     tri = (tiles * (tiles + 1) / 2) / (tiles * tiles)      # blocks on or above the diagonal
     ef = exec_frac or {}
+    if w.dtype == "bf16":
+        # exact similarities on the int8 matrix cores: sixteen limb-pair products per pair of 32-token
+        # blocks on or above the diagonal, channels padded to 64
+        nb = (w.n_loc + 31) // 32
+        cpad = (w.C + 63) // 64 * 64
+        gram = dict(bound="i8", amount=16 * 2 * w.B * w.P * (nb * (nb + 1) // 2) * 32 * 32 * cpad, equiv=f["similarity"],
+                    limit="int8 matrix cores at one wave per SIMD (268 registers), operands straight from L2")
+    else:
+        gram = dict(bound="f64", amount=f["similarity"] * tri, equiv=f["similarity"],
+                    limit="issue rate of the fp64 matrix-core products (a bare loop of them reaches 43-47 TFLOP/s)")
     work = {
-        "gram": dict(bound="f64", amount=f["similarity"] * tri, equiv=f["similarity"],
-                     limit="issue rate of the fp64 matrix-core products (a bare loop of them reaches 43-47 TFLOP/s)"),
+        "gram": gram,
+        "limbs": dict(bound="hbm", amount=w.B * w.N * (w.C * esize + (w.C + 63) // 64 * 64 * 4 + 17)),
         "greedy": dict(bound="hbm", amount=w.B * w.P * w.n_loc * w.n_loc * 4 + 3 * w.B * w.D * 4,
                        equiv=costs.greedy_stream_bytes(w.B, w.P, w.n_loc, w.d_loc),
                        limit="latency: d_loc dependent rounds per region (argmax, LDS exchange, two barriers); S is "
@@ -95,13 +105,14 @@ def roofline_entry(name, work, avg_us, traffic=None):
         out = {"kernel": name, "bound": "hbm", "achieved": wk["amount"] / sec / 1e9, "peak": PEAK["hbm"], "unit": "GB/s"}
     else:
         out = {"kernel": name, "bound": "mfma", "achieved": wk["amount"] / sec / 1e12, "peak": PEAK[bound],
-               "unit": "TFLOP/s", "mfma_dtype": bound}
+               "unit": "TOP/s" if bound == "i8" else "TFLOP/s", "mfma_dtype": bound}
     out["frac"] = out["achieved"] / out["peak"]
     out["traffic"] = traffic
     if "equiv" in wk:
         scale = 1e9 if bound == "hbm" else 1e12
         out["equiv_achieved"] = wk["equiv"] / sec / scale
-        out["equiv_frac"] = out["equiv_achieved"] / out["peak"]
+        if bound != "i8":   # (the textbook count is in flops of another unit there: a rate, no fraction)
+            out["equiv_frac"] = out["equiv_achieved"] / out["peak"]
     if traffic:
         out["traffic_GBps"] = traffic / sec / 1e9
         out["traffic_frac_of_hbm"] = out["traffic_GBps"] / PEAK["hbm"]
@@ -190,6 +201,10 @@ def main():
     ms = timed(main_flags, args.steps)
     ms_idx = timed(tb.TOMA_REUSE_IDX, args.steps)
     ms_a = timed(tb.TOMA_REUSE_A, args.steps)
+    # the same calls with the weights recomputed inside merge and unmerge instead of stored (Sec. 4.2.1)
+    sub = max(args.steps // 2, 5)
+    ms_rc = timed(tb.TOMA_RECOMPUTE_WEIGHTS, sub)
+    ms_rc_idx = timed(tb.TOMA_RECOMPUTE_WEIGHTS | tb.TOMA_REUSE_IDX, sub)
     per_position = None
     ms_full = ms
     if seq:
@@ -216,6 +231,12 @@ def main():
         if n:
             per_kernel[name] = {"launches_per_step": n / args.steps, "avg_us": total * 1e3 / n,
                                 "us_per_step": total * 1e3 / args.steps}
+    timed(tb.TOMA_RECOMPUTE_WEIGHTS | tb.TOMA_REUSE_IDX, sub)
+    recompute_kernels = {}
+    for name in ("weights_stats", "lse", "merge_recompute", "unmerge_recompute"):
+        n, total = tb.toma_profile_read(name)
+        if n:
+            recompute_kernels[name] = total * 1e3 / n
     tb.toma_profile_enable(False)
     # products actually executed by the block-skipping merge / unmerge: counted from the block map
     call(0)
@@ -248,7 +269,7 @@ def main():
     roofline = roofline_entry(dominant, work, per_kernel[dominant]["avg_us"], traffic.get(dominant))
     roofline["avg_us"] = per_kernel[dominant]["avg_us"]
     roofline["traffic_source"] = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)"
-    mfma_k = [k for k in per_kernel if per_kernel[k]["bound"] == "mfma" and k != "gram"]
+    mfma_k = [k for k in per_kernel if per_kernel[k]["bound"] == "mfma" and k not in ("gram", "limbs")]
     mfma_flops = sum(work[k]["amount"] * per_kernel[k]["launches_per_step"] for k in mfma_k)
     mfma_equiv = sum(work[k].get("equiv", work[k]["amount"]) * per_kernel[k]["launches_per_step"] for k in mfma_k)
     mfma_us = sum(per_kernel[k]["us_per_step"] for k in mfma_k)
@@ -267,6 +288,10 @@ def main():
                             "toma_layer, nothing cached (select + weights + merge + attention + unmerge)")},
         "roofline": roofline,
         "us_idx_cached": ms_idx * 1e3, "us_idx_and_weights_cached": ms_a * 1e3,
+        "recomputed_weights": {"us_nothing_cached": ms_rc * 1e3, "us_idx_cached": ms_rc_idx * 1e3,
+                               "kernel_avg_us": recompute_kernels,
+                               "note": "toma_layer with TOMA_RECOMPUTE_WEIGHTS: no A is written or read; compare "
+                                       "us_idx_cached here with the stored-weights us_idx_cached"},
         "sequence": None if not seq else {
             "schedule": ["select+weights" if f == 0 else ("weights" if f == tb.TOMA_REUSE_IDX else "cached") for f in plan],
             "us_per_position": per_position, "us_amortised": ms * 1e3, "us_nothing_cached": ms_full * 1e3},
@@ -383,6 +408,12 @@ def main():
                      f"--warmup {args.warmup}\n"
                      f"us per layer call: nothing cached {ms_full * 1e3 if seq else ms * 1e3:.1f}; idx cached {ms_idx * 1e3:.1f}; "
                      f"idx + weights cached {ms_a * 1e3:.1f}" + (f"; along the reuse schedule {ms * 1e3:.1f}" if seq else "") + "\n")
+            fh.write(f"with recomputed weights (no stored A): nothing cached {ms_rc * 1e3:.1f}; idx cached {ms_rc_idx * 1e3:.1f} "
+                     f"(" + ", ".join(f"{k} {v:.1f}" for k, v in recompute_kernels.items()) + ")\n")
+            if "unmerge_variants" in out:
+                uv = out["unmerge_variants"]
+                fh.write(f"unmerge alone: transpose {uv['transpose_us']:.1f} us, Moore-Penrose (rcond {uv['rcond']:g}) "
+                         f"{uv['pseudo_inverse_us']:.1f} us (eigen-decomposition {uv['pinv_eig_us']:.1f}, apply {uv['pinv_apply_us']:.1f})\n")
             if cb:
                 fh.write(f"fp64 oracle on {cb['cores']} host threads: {cb['value'] / 1e6:.2f} s ({cb['sample']})\n")
             ms_ = out["mfma_stages"]

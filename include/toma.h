@@ -83,7 +83,8 @@ const char *toma_status_string(int status);
  * For every (sample, region): S_ij = cos(x_i, x_j) over the region's tokens; first pick = largest
  * row sum; every later pick maximises sum_j max(0, S_ij - m_j) over tokens not yet picked, with
  * m_j the largest similarity of token j to the picks so far.  Ties go to the lowest index.
- * Similarities are evaluated in double precision from the stored token values and rounded once
+ * Similarities are evaluated to double precision from the stored token values (bf16 tokens: exactly,
+ * as integer sums on the int8 matrix cores; fp32 tokens: on the fp64 matrix cores) and rounded once
  * to the nearest multiple of 2^-30; the sums and comparisons over them are exact (64-bit integers),
  * so the picks do not depend on any summation order and mathematically tied candidates (frequent:
  * two tokens that only improve each other's coverage) are exact ties, decided by index alone.
@@ -101,10 +102,11 @@ int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_
  * toma_select for callers that cannot hand over or allocate a workspace (code under HIP graph
  * capture, tight serving loops, harnesses that forbid device allocation): the same selection, same
  * arguments and results, with its scratch (the regions' similarity matrices, B * P * N_loc^2 32-bit
- * words) in a buffer of TOMA_STATIC_SCRATCH_BYTES that is part of the library's device code and
- * present once on every GPU.  No device memory is allocated or freed, at any call.
- *   - Shapes whose similarity matrices exceed the buffer return TOMA_ERR_WORKSPACE (the SDXL-sized
- *     layers fit: 2 x 16 regions of 256 tokens are 8 MiB; the 128 x 128 grid does not).
+ * words, and for bf16 tokens their fixed-point copy, 4 bytes per element) in a buffer of
+ * TOMA_STATIC_SCRATCH_BYTES that is part of the library's device code and present once on every GPU.
+ * No device memory is allocated or freed, at any call.
+ *   - Shapes whose scratch exceeds the buffer return TOMA_ERR_WORKSPACE (the SDXL-sized layers fit:
+ *     2 x 4096 tokens of width 640 need 8 + 20 MiB; the 128 x 128 grid does not).
  *   - The GPU the stream belongs to must be the current device of the calling thread.  The buffer's
  *     address on that GPU is looked up on the first call there (TOMA_ERR_LAUNCH if the runtime
  *     refuses).
@@ -112,7 +114,7 @@ int toma_select(const toma_desc *desc, const void *X, int32_t *idx, float *gain_
  *     streams, different threads) race on it; order them.  Nothing in the buffer needs clearing
  *     between calls (every similarity that is read was written by the same call).
  */
-#define TOMA_STATIC_SCRATCH_BYTES (16u << 20)
+#define TOMA_STATIC_SCRATCH_BYTES (32u << 20)
 int toma_select_static(const toma_desc *desc, const void *X, int32_t *idx, float *gain_opt,
                        float *gap_opt, void *stream);
 

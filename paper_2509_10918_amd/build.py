@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtoma.so")
-SOURCES = ["toma_api.hip", "toma_select.hip", "toma_merge.hip", "toma_attend.hip", "toma_pinv.hip", "toma_fused.hip", "toma_profile.hip"]
+SOURCES = ["toma_api.hip", "toma_select.hip", "toma_gram_i8.hip", "toma_merge.hip", "toma_attend.hip", "toma_pinv.hip", "toma_fused.hip", "toma_profile.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-parameter", "-Wno-inline-asm"]
 

@@ -65,6 +65,7 @@ void plan_workspace(const Shape &s, Workspace *w) {
   }
   if (weights_single_pass(s.Nr, s.Dr, s.C, s.B * s.R, (int)es)) w->z_parts = s.Nr / 32;  // one partial row sum per 32-source workgroup
   w->sim = take((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(float));
+  w->gram = take(gram_i8_workspace_bytes(s));  // limb planes, norms and flags of the int8 similarity kernel
   w->stats = take((size_t)s.B * s.N * w->stat_parts * 2 * sizeof(float));
   w->lse = take((size_t)s.B * s.N * sizeof(float));
   w->zpart = take((size_t)s.B * s.D * w->z_parts * sizeof(float));
@@ -212,11 +213,10 @@ TOMA_API int toma_select_static(const toma_desc *desc, const void *X, int32_t *i
   if (misaligned(X, 16) || misaligned(idx, 4) || (gain_opt && misaligned(gain_opt, 4)) ||
       (gap_opt && misaligned(gap_opt, 4)))
     return TOMA_ERR_ALIGN;
-  // the selection reads and writes only the similarity section: lay it out at the buffer's start
+  // the selection uses only the similarity sections of the workspace: they come first in its layout
   plan_workspace(s, &w);
-  const size_t need = up256((size_t)s.B * s.P * s.n_loc * s.n_loc * sizeof(int32_t));
-  if (need > (size_t)TOMA_STATIC_SCRATCH_BYTES) return TOMA_ERR_WORKSPACE;
-  w.sim = 0;
+  const size_t need = w.gram + up256(gram_i8_workspace_bytes(s));
+  if (w.sim != 0 || need > (size_t)TOMA_STATIC_SCRATCH_BYTES) return TOMA_ERR_WORKSPACE;
   char *buf = nullptr;
   rc = static_scratch(&buf);
   if (rc != TOMA_OK) return rc;

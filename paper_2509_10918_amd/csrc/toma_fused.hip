@@ -37,7 +37,7 @@ template <typename T, bool UNMERGE> struct FusedPol {
   const int32_t *idx;   // [B][D]
   const T *Os;          // unmerge: [B][os_rows][C], rows [0, D) already divided by Z
   int os_rows;
-  const float *lse;     // [B*R][Nr]
+  const float2 *lse;    // [B*R][Nr]: (largest logit, log of the sum of exponentials) of each source's softmax
   const float2 *stats;  // [B*R][Nr][parts]: (largest logit, .) per slice of `slice` destinations
   int parts, slice;
   float scale;
@@ -64,7 +64,8 @@ template <typename T, bool UNMERGE> struct FusedPol {
     const int j0 = UNMERGE ? n0 : m0, j1 = UNMERGE ? n1 : m1;  // destinations
     const int p0 = j0 / slice, p1 = min((j1 - 1) / slice, parts - 1);
     for (int s = s0; s < s1; s++) {
-      const float l = lse[(size_t)z * v.Nr + s];
+      const float2 ml = lse[(size_t)z * v.Nr + s];
+      const float l = ml.x + ml.y;
       const float2 *row = stats + ((size_t)z * v.Nr + s) * parts;
       for (int q = p0; q <= p1; q++)
         if (!(row[q].x - l < -kFusedEmptyGap)) return true;
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(512) void k_fused(const FusedPol<T, UNMERGE> pol) {
   constexpr int ITEMS = BQ * kFusedKeys / 4;   // <= 512
   const bool maker = tid < ITEMS;
   const int pm = tid / 8, pk0 = (tid % 8) * 4;  // query row and first key of the item
-  float bias_q = 0.f;
+  float2 bias_q = make_float2(0.f, 0.f);
   if (UNMERGE && maker && m0 + pm < NQ) bias_q = pol.lse[(size_t)z * v.Nr + m0 + pm];
   float zsum = 0.f;  // merge: row sum of the weights of query pm (thread tid % 8 == 0 holds it)
 
@@ -191,9 +192,10 @@ __global__ __launch_bounds__(512) void k_fused(const FusedPol<T, UNMERGE> pol) {
 #pragma unroll
       for (int u = 0; u < 4; u++) {
         const int n = n0 + pk0 + u;
-        float bias = bias_q;
-        if (!UNMERGE) bias = n < NK ? pol.lse[(size_t)z * v.Nr + n] : 0.f;
-        float p = (n < NK && m0 + pm < NQ) ? __expf(lg[u] * pol.scale - bias) : 0.f;
+        float2 bias = bias_q;
+        if (!UNMERGE) bias = n < NK ? pol.lse[(size_t)z * v.Nr + n] : make_float2(0.f, 0.f);
+        // (logit - largest logit) is small and nearly exact; only then the log of the sum comes off
+        float p = (n < NK && m0 + pm < NQ) ? __expf(__builtin_fmaf(lg[u], pol.scale, -bias.x) - bias.y) : 0.f;
         o[u] = from_f32<T>(p);
         rowsum += to_f32(o[u]);
       }
@@ -279,40 +281,64 @@ static int launch_fused(const Shape &s, const FusedPol<T, UNMERGE> &pol, int ker
   KernelTimer kt(kernel_id, st);
 #define TOMA_FUSED_LAUNCH(RT, CTC, NCH)                                                                            \
   hipLaunchKernelGGL((k_fused<T, UNMERGE, RT, CTC, NCH>), dim3((NQ + 16 * RT - 1) / (16 * RT), s.B * s.R), dim3(512), 0, st, pol)
+  // Queries per workgroup: a workgroup walks its key tiles one after the other, so the grid should
+  // have a workgroup for every CU before a workgroup gets more queries (16 RT, RT = 4, 2 or 1).
+  const long long regions = (long long)s.B * s.R;
+  auto rt_for = [&](int rt_max) {
+    int rt = rt_max;
+    while (rt > 1 && ((NQ + 16 * rt - 1) / (16 * rt)) * regions < 256) rt >>= 1;
+    return rt;
+  };
+#define TOMA_FUSED_BY_RT(CTC)                                      \
+  switch (rt_for(4)) {                                             \
+    case 4: TOMA_FUSED_LAUNCH(4, CTC, 1); break;                   \
+    case 2: TOMA_FUSED_LAUNCH(2, CTC, 1); break;                   \
+    default: TOMA_FUSED_LAUNCH(1, CTC, 1); break;                  \
+  }
   // (chunks of the value tile: two of them, 32 rows each, have to fit the LDS next to the rest)
-  if (s.C <= 128) TOMA_FUSED_LAUNCH(4, 1, 1);
-  else if (s.C <= 256) TOMA_FUSED_LAUNCH(4, 2, 1);
-  else if constexpr (sizeof(T) == 2) {
-    if (s.C <= 640) TOMA_FUSED_LAUNCH(4, 5, 1);
-    else if (s.C <= 1280) TOMA_FUSED_LAUNCH(2, 5, 2);
+  if constexpr (sizeof(T) == 2) {
+    if (s.C <= 128) { TOMA_FUSED_BY_RT(1) }
+    else if (s.C <= 256) { TOMA_FUSED_BY_RT(2) }
+    else if (s.C <= 640) { TOMA_FUSED_BY_RT(5) }
+    else if (s.C <= 1280) { if (rt_for(2) == 2) TOMA_FUSED_LAUNCH(2, 5, 2); else TOMA_FUSED_LAUNCH(1, 5, 2); }
     else if (s.C <= 3072) TOMA_FUSED_LAUNCH(1, 4, 6);
     else return TOMA_ERR_UNSUPPORTED;
   } else {
-    if (s.C <= 768) TOMA_FUSED_LAUNCH(4, 2, 3);
+    // fp32: 64 queries per workgroup wherever the accumulators allow, so that a wave adds up a logit
+    // over all channels in the order the statistics pass did: logit minus largest logit is then exact
+    // for the weights that matter, as in the stored-weights kernels (fp32 logits of several hundred
+    // leave no room for two independent roundings inside a 1e-4 tolerance)
+    if (s.C <= 128) TOMA_FUSED_LAUNCH(4, 1, 1);
+    else if (s.C <= 256) TOMA_FUSED_LAUNCH(4, 2, 1);
+    else if (s.C <= 768) TOMA_FUSED_LAUNCH(4, 2, 3);
     else if (s.C <= 1280) TOMA_FUSED_LAUNCH(2, 2, 5);
     else if (s.C <= 3072) TOMA_FUSED_LAUNCH(1, 2, 12);
     else return TOMA_ERR_UNSUPPORTED;
   }
+#undef TOMA_FUSED_BY_RT
 #undef TOMA_FUSED_LAUNCH
   return launch_status();
 }
 
+// cache layout: lse2 [B*N] float2, lse [B*N] float (the statistics pass writes it; unused here), statistics
+static size_t fused_lse2_bytes(const Shape &s) { return ((size_t)s.B * s.N * sizeof(float2) + 255) & ~(size_t)255; }
+static size_t fused_lse_bytes(const Shape &s) { return ((size_t)s.B * s.N * sizeof(float) + 255) & ~(size_t)255; }
 size_t fused_cache_bytes(const Shape &s, const Workspace &w) {
-  const size_t lse = ((size_t)s.B * s.N * sizeof(float) + 255) & ~(size_t)255;
-  return lse + (size_t)s.B * s.N * w.stat_parts * sizeof(float2);
+  return fused_lse2_bytes(s) + fused_lse_bytes(s) + (size_t)s.B * s.N * w.stat_parts * sizeof(float2);
 }
 
 template <typename T>
 static int merge_fused_typed(const Shape &s, const void *X, const int32_t *idx, float *Z, void *Xm, char *cache,
                              const Workspace &w, hipStream_t st) {
-  float *lse = reinterpret_cast<float *>(cache);
-  float2 *stats = reinterpret_cast<float2 *>(cache + (((size_t)s.B * s.N * sizeof(float) + 255) & ~(size_t)255));
+  float2 *lse2 = reinterpret_cast<float2 *>(cache);
+  float *lse = reinterpret_cast<float *>(cache + fused_lse2_bytes(s));
+  float2 *stats = reinterpret_cast<float2 *>(cache + fused_lse2_bytes(s) + fused_lse_bytes(s));
   int slice = 0;
-  int rc = launch_weight_stats(s, X, idx, stats, w.stat_parts, lse, &slice, st);
+  int rc = launch_weight_stats(s, X, idx, stats, w.stat_parts, lse, lse2, &slice, st);
   if (rc != TOMA_OK) return rc;
   FusedPol<T, false> p{};
   p.v = make_view<T>(s, X);
-  p.idx = idx; p.Os = nullptr; p.os_rows = 0; p.lse = lse; p.stats = stats; p.parts = w.stat_parts; p.slice = slice;
+  p.idx = idx; p.Os = nullptr; p.os_rows = 0; p.lse = lse2; p.stats = stats; p.parts = w.stat_parts; p.slice = slice;
   p.scale = s.scale; p.out = static_cast<T *>(Xm); p.Z = Z;
   return launch_fused<T, false>(s, p, K_MERGE_FUSED, st);
 }
@@ -326,13 +352,13 @@ int launch_merge_fused(const Shape &s, const void *X, const int32_t *idx, float 
 template <typename T>
 static int unmerge_fused_typed(const Shape &s, const void *X, const int32_t *idx, const char *cache, const void *Os,
                                int os_rows, void *Y, const Workspace &w, hipStream_t st) {
-  const float *lse = reinterpret_cast<const float *>(cache);
-  const float2 *stats = reinterpret_cast<const float2 *>(cache + (((size_t)s.B * s.N * sizeof(float) + 255) & ~(size_t)255));
+  const float2 *lse2 = reinterpret_cast<const float2 *>(cache);
+  const float2 *stats = reinterpret_cast<const float2 *>(cache + fused_lse2_bytes(s) + fused_lse_bytes(s));
   // the slice width of the statistics is a function of the shape: the planner that ran the pass says it
   const int slice = weight_stats_slice(s.Nr, s.Dr, s.C, s.B * s.R, (int)sizeof(T));
   FusedPol<T, true> p{};
   p.v = make_view<T>(s, X);
-  p.idx = idx; p.Os = static_cast<const T *>(Os); p.os_rows = os_rows; p.lse = lse; p.stats = stats;
+  p.idx = idx; p.Os = static_cast<const T *>(Os); p.os_rows = os_rows; p.lse = lse2; p.stats = stats;
   p.parts = w.stat_parts; p.slice = slice; p.scale = s.scale; p.out = static_cast<T *>(Y); p.Z = nullptr;
   return launch_fused<T, true>(s, p, K_UNMERGE_FUSED, st);
 }

@@ -1,0 +1,390 @@
+// Cosine similarity of bf16 tokens on the int8 matrix cores, exactly (paper Sec. 4.1: S = cos(x_i, x_j)
+// inside each region).
+//
+// The selection decides on similarities rounded to a grid of 2^-30 and needs them accurate far below
+// that, which fp32 accumulation cannot give; the fp64 matrix cores can (k_gram) but are slow.  A bf16
+// value is an 8-bit significand times a power of two, so the dot product of two tokens is an integer
+// sum once every token is written in fixed point against its own largest exponent:
+//     x_ic = q_ic * 2^(E_i - 156),   q_ic = +-significand << (22 - (E_i - e_ic))    (|q| < 2^30)
+// and q splits into four signed bytes q = l0 + 256 l1 + 256^2 l2 + 256^3 l3 ("limbs").  Then
+//     <x_i, x_j> = 2^(E_i + E_j - 312) * sum over limb pairs (a, b) of 256^(a+b) * <l_a(i), l_b(j)>,
+// sixteen int8 products with int32 accumulators (exact: |sum| <= 4 * C * 2^14 < 2^31 for C <= 16384),
+// added up per a + b and combined in double precision with one rounding that matters.  The int8 matrix
+// cores are 64 times faster than the fp64 ones, so sixteen products still come out far ahead.
+//   k_limbs    one pass over X: per token the largest exponent, the norm (double), the limb planes
+//              (layout below), and for the rare element too small for the fixed point (more than 22
+//              binary orders below the token's largest: about one in 10^6 elements of Gaussian data)
+//              its channel and the part of its value that was dropped, which k_gram_i8's epilogue adds
+//              back exactly; a token with more than a few such elements has its rows of S recomputed
+//              in double precision by the selection kernel's prologue instead.
+//   k_gram_i8  one workgroup per (region, pair of 64-token blocks on or above the diagonal), the two
+//              panels of limbs staged through LDS per 64 channels, 64 products per wave and chunk; the
+//              epilogue scales by the tokens' norms, rounds to the grid and stores both triangles.
+// Limb layout: token row = ceil(C / 64) * 64 channels; per group of 16 channels 64 bytes: limb 0 of the
+// 16 channels, then limb 1, 2, 3.  A lane's operand for one limb and 16 channels is one 16-byte packet.
+#include "toma_common.h"
+#include "toma_internal.h"
+
+namespace toma {
+
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+constexpr int kLimbShift = 22;
+
+// One wave per token: lane l takes the 16-channel groups l, l + 64, ... (ITER of them); the token's row
+// stays in registers between finding its largest exponent and converting it, so X is read once, and
+// there are as many waves as tokens to hide the memory latency of this small streaming pass.
+// Elements too small for the fixed point (at most kFixMax per token are listed; more than that and the
+// token's rows of S are recomputed wholesale by the selection kernel) leave a correction behind: their
+// channel and the part of their value the fixed point dropped, which k_gram_i8 adds back exactly.
+constexpr int kFixMax = 4;
+struct LimbFix { int32_t n; int32_t ch[kFixMax]; double res[kFixMax]; };  // n > kFixMax: too many, see flag
+
+template <int ITER>
+__global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uint32_t *__restrict__ Xq,
+                                              double *__restrict__ nrm, double *__restrict__ rnp,
+                                              uint8_t *__restrict__ flag, LimbFix *__restrict__ fixes, int rows, int C,
+                                              int groups_pad) {
+  __shared__ int fixn[4];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, token = blockIdx.x * 4 + w;
+  if (lane == 0) fixn[w] = 0;
+  if (token >= rows) return;  // (whole waves leave together; nothing below crosses waves)
+  const uint32_t *src = reinterpret_cast<const uint32_t *>(X + (size_t)token * C);  // two elements per word
+  const int groups = C / 16;
+  u32x4 pk[ITER][2];
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int g = lane + 64 * it;
+    if (g < groups) {
+      pk[it][0] = *reinterpret_cast<const u32x4 *>(src + 8 * g);
+      pk[it][1] = *reinterpret_cast<const u32x4 *>(src + 8 * g + 4);
+    } else {
+      pk[it][0] = pk[it][1] = (u32x4){0u, 0u, 0u, 0u};
+    }
+  }
+  // ---- largest exponent and sum of squares ----
+  int emax = 1;
+  double sq = 0.0;
+#pragma unroll
+  for (int it = 0; it < ITER; it++)
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      const uint32_t word = pk[it][i >> 2][i & 3];
+      emax = max(emax, (int)((word >> 7) & 0xffu));
+      emax = max(emax, (int)((word >> 23) & 0xffu));
+      const double lo = (double)__builtin_bit_cast(float, word << 16), hi = (double)__builtin_bit_cast(float, word & 0xffff0000u);
+      sq = fma(lo, lo, sq);
+      sq = fma(hi, hi, sq);
+    }
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    emax = max(emax, __shfl_xor(emax, m, 64));
+    sq += __shfl_xor(sq, m, 64);
+  }
+  // ---- fixed point against the largest exponent, split into limbs ----
+  uint32_t *dst = Xq + (size_t)token * groups_pad * 16;
+  LimbFix *fx = fixes + token;
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int g = lane + 64 * it;
+    if (g >= groups_pad) continue;
+    uint32_t lq[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      const uint32_t word = pk[it][i >> 3][(i >> 1) & 3];
+      const uint32_t bits = (i & 1) ? (word >> 16) : (word & 0xffffu);
+      const int e = (int)((bits >> 7) & 0xffu);
+      const uint32_t sig = e ? (0x80u | (bits & 0x7fu)) : (bits & 0x7fu);
+      const int sh = kLimbShift - (emax - max(e, 1));
+      uint32_t mag;
+      if (sh >= 0) {
+        mag = sig << sh;
+      } else {
+        const int down = min(-sh, 31);
+        mag = sig >> down;
+        if ((sig & ((1u << down) - 1u)) != 0u) {
+          // what the fixed point drops: value - (+-mag) * 2^(emax - 156), exact in double
+          const double val = (double)__builtin_bit_cast(float, bits << 16);
+          const double kept = ldexp((double)mag, emax - 156);
+          const int at = atomicAdd(&fixn[w], 1);
+          if (at < kFixMax) { fx->ch[at] = 16 * g + i; fx->res[at] = val - ((bits & 0x8000u) ? -kept : kept); }
+        }
+      }
+      const int32_t q = (bits & 0x8000u) ? -(int32_t)mag : (int32_t)mag;
+      // signed bytes: adding 128 to each of the three low bytes (carries and all) and flipping
+      // their top bits leaves l0 + 256 l1 + 256^2 l2 + 256^3 l3 == q with every l in [-128, 127]
+      lq[i] = ((uint32_t)q + 0x00808080u) ^ 0x00808080u;
+    }
+    // byte k of the sixteen words -> limb plane k (four words)
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      u32x4 o;
+#pragma unroll
+      for (int m = 0; m < 4; m++) {
+        const uint32_t sel = (uint32_t)k | ((uint32_t)(4 + k) << 8);  // byte k of the low word, byte k of the high word
+        const uint32_t p01 = __builtin_amdgcn_perm(lq[4 * m + 1], lq[4 * m], sel);
+        const uint32_t p23 = __builtin_amdgcn_perm(lq[4 * m + 3], lq[4 * m + 2], sel);
+        o[m] = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+      }
+      *reinterpret_cast<u32x4 *>(dst + 16 * g + 4 * k) = o;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+  if (lane == 0) {
+    const int nfix = __hip_atomic_load(&fixn[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const double n = fmax(sqrt(sq), 1e-12);
+    nrm[token] = n;
+    rnp[token] = ldexp(1.0 / n, emax - 141);  // so that (sum of q q) * rnp_i * rnp_j = cos * 2^30
+    fx->n = nfix;
+    flag[token] = nfix == 0 ? 0 : (nfix <= kFixMax ? 1 : 2);  // 1: corrected by k_gram_i8; 2: recompute the rows
+  }
+}
+
+// One workgroup of four waves (2 x 2) per (region, pair of 64-token blocks on or above the diagonal):
+// wave (wi, wj) owns the 32 x 32 block of S made of tokens 32 wi .. of the row block and 32 wj .. of
+// the column block, as 2 x 2 tiles with seven int32 accumulators each (one per limb-index sum).  Per
+// 64 channels the two 64-token panels (256 bytes of limbs per token) go global -> registers -> LDS once
+// and every wave reads its 32 + 32 rows from there: half the L2 traffic of waves fetching their own
+// operands, which is what bounded that variant.  The next chunk's panels are fetched into registers
+// while the matrix cores work on the current one.
+constexpr int kGramRow = 256 + 16;  // bytes per token and chunk in LDS: 16 packets plus one of padding (bank spread)
+
+// with the fixed-point dot product and the norms: cos * 2^30 = dot_q * rnp_i * rnp_j.  A token whose
+// fixed point dropped part of an element (flag 1) has x = xq + res on the listed channels, so
+// <x_i, x_j> = <xq_i, xq_j> + sum_fix(i) res * x_j[ch] + sum_fix(j) res * xq_i[ch].
+struct GramFix { const bf16_t *X; const double *nrm; const uint8_t *flag; const LimbFix *fixes; int C; };
+
+__global__ __launch_bounds__(256, 2) void k_gram_i8(const uint32_t *__restrict__ Xq, const double *__restrict__ rnp,
+                                                   int32_t *__restrict__ S, RegionMap map, int N, int P, int n_loc,
+                                                   int row_words, int nchunks, int nb64, int units, GramFix fix) {
+  __shared__ __align__(16) char panel[2][64 * kGramRow];  // [A rows | B rows]
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
+  const int wi = w >> 1, wj = w & 1;
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  const int bp = work / units, unit = work - bp * units;
+  int bm = 0, rest = unit;  // unit enumerates the block pairs (bm <= bn) row by row
+  while (rest >= nb64 - bm) { rest -= nb64 - bm; bm++; }
+  const int bn = bm + rest;
+  const int b = bp / P, p = bp % P;
+
+  // staging: thread t moves packets t, t + 256, ... of each panel (64 rows x 16 packets per chunk)
+  const uint32_t *src[2][4];
+  int dst[4];
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    const int q = tid + 256 * u, row = q >> 4, pk = q & 15;
+    const int la = min(64 * bm + row, n_loc - 1), lb = min(64 * bn + row, n_loc - 1);
+    src[0][u] = Xq + ((size_t)b * N + map.token(p, la)) * row_words + 4 * pk;
+    src[1][u] = Xq + ((size_t)b * N + map.token(p, lb)) * row_words + 4 * pk;
+    dst[u] = row * kGramRow + 16 * pk;
+  }
+  i32x4 stage[2][4];
+  auto fetch = [&](int k) {
+#pragma unroll
+    for (int h = 0; h < 2; h++)
+#pragma unroll
+      for (int u = 0; u < 4; u++) stage[h][u] = *reinterpret_cast<const i32x4 *>(src[h][u] + 64 * k);
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int h = 0; h < 2; h++)
+#pragma unroll
+      for (int u = 0; u < 4; u++) *reinterpret_cast<i32x4 *>(&panel[h][dst[u]]) = stage[h][u];
+  };
+
+  // does any of this block pair's 128 tokens carry a correction?  (almost never; the flag is asked
+  // for here and first looked at after the main loop, so its latency costs nothing)
+  uint8_t my_flag = 0;
+  size_t my_token = 0;
+  if (tid < 128) {
+    const int l = 64 * (tid < 64 ? bm : bn) + (tid & 63);
+    my_token = (size_t)b * N + map.token(p, min(l, n_loc - 1));
+    my_flag = l < n_loc ? fix.flag[my_token] : 0;
+  }
+
+  i32x4 acc[2][2][7];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int s = 0; s < 7; s++) acc[i][j][s] = (i32x4){0, 0, 0, 0};
+
+  // this lane's operand packets: row 32 wi + 16 t + c (A) / 32 wj + 16 t + c (B), channel group g, limb l
+  const char *fa = &panel[0][(32 * wi + c) * kGramRow + 64 * g];
+  const char *fb = &panel[1][(32 * wj + c) * kGramRow + 64 * g];
+  fetch(0);
+  for (int k = 0; k < nchunks; k++) {
+    __syncthreads();  // every wave is done with the previous chunk's panels
+    stash();
+    __syncthreads();
+    if (k + 1 < nchunks) fetch(k + 1);
+    i32x4 a[2][4], bb[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+      for (int l = 0; l < 4; l++) {
+        a[t][l] = *reinterpret_cast<const i32x4 *>(fa + 16 * t * kGramRow + 16 * l);
+        bb[t][l] = *reinterpret_cast<const i32x4 *>(fb + 16 * t * kGramRow + 16 * l);
+      }
+#pragma unroll
+    for (int la = 0; la < 4; la++)
+#pragma unroll
+      for (int lb = 0; lb < 4; lb++)
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+            acc[i][j][la + lb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i][la], bb[j][lb], acc[i][j][la + lb], 0, 0, 0);
+  }
+
+  // Corrections (rare).  Slots 0..63 are the pair's row tokens, 64..127 its column tokens.  Up to kSlots
+  // flagged slots get a vector of 64 corrections each, one per partner on the other side, computed by
+  // the whole workgroup with every load independent; beyond that (never seen) each element looks its
+  // correction up by itself, slowly.
+  constexpr int kSlots = 8;
+  __shared__ LimbFix sfix[128];  // n = 0 for a token without corrections
+  __shared__ double cvec[kSlots][64];
+  __shared__ int8_t slot_of[128];
+  __shared__ uint8_t flagged[kSlots];
+  __shared__ int nflagged;
+  if (tid == 0) nflagged = 0;
+  const bool corrected = __syncthreads_or(my_flag == 1) != 0;
+  bool by_element = false;
+  if (corrected) {
+    if (tid < 128) {
+      if (my_flag == 1) {
+        sfix[tid] = fix.fixes[my_token];
+        const int k = atomicAdd(&nflagged, 1);
+        slot_of[tid] = (int8_t)(k < kSlots ? k : -1);
+        if (k < kSlots) flagged[k] = (uint8_t)tid;
+      } else {
+        sfix[tid].n = 0;
+        slot_of[tid] = -1;
+      }
+    }
+    __syncthreads();
+    by_element = nflagged > kSlots;
+    const int nf = min(nflagged, kSlots);
+    for (int k = w; k < nf; k += 4) {
+      const int f = flagged[k], q = 64 * (1 - (f >> 6)) + lane;  // the flagged slot and this lane's partner slot
+      const int lf = min(64 * (f < 64 ? bm : bn) + (f & 63), n_loc - 1), lq = min(64 * (q < 64 ? bm : bn) + lane, n_loc - 1);
+      const size_t tf = (size_t)b * N + map.token(p, lf), tq = (size_t)b * N + map.token(p, lq);
+      const LimbFix &ff = sfix[f], &fq = sfix[q];
+      double corr = 0.0;
+#pragma unroll
+      for (int a = 0; a < kFixMax; a++)
+        if (a < ff.n) {
+          double xq = (double)(float)fix.X[tq * fix.C + ff.ch[a]];
+          // a column token's dropped parts meet the row token's fixed-point value, not its full one
+          if (f >= 64)
+            for (int u = 0; u < fq.n; u++)
+              if (fq.ch[u] == ff.ch[a]) xq -= fq.res[u];
+          corr = fma(ff.res[a], xq, corr);
+        }
+      cvec[k][lane] = corr * 1073741824.0 / (fix.nrm[tf] * fix.nrm[tq]);
+    }
+    __syncthreads();
+  }
+
+  // cos * 2^30 = (sum_s acc_s 256^s) * rnp_i * rnp_j; lane holds column (token j) c and rows 4 g + r
+  int32_t *Sr = S + (size_t)bp * n_loc * n_loc;
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int col = 64 * bn + 32 * wj + 16 * j + c;
+      const bool col_ok = col < n_loc;
+      const size_t tj = (size_t)b * N + map.token(p, min(col, n_loc - 1));
+      const double rj = rnp[tj];
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int row = 64 * bm + 32 * wi + 16 * i + 4 * g + r;
+        if (!col_ok || row >= n_loc) continue;
+        const size_t ti = (size_t)b * N + map.token(p, row);
+        const double ri = rnp[ti];
+        // the three high sums are exact in double (below 2^48); the low four lose at most 2^3 of 2^58 and up
+        const double hi = fma((double)acc[i][j][6][r], 65536.0, fma((double)acc[i][j][5][r], 256.0, (double)acc[i][j][4][r]));
+        const double lo = fma((double)acc[i][j][3][r], 16777216.0,
+                              fma((double)acc[i][j][2][r], 65536.0, fma((double)acc[i][j][1][r], 256.0, (double)acc[i][j][0][r])));
+        const double dot = fma(hi, 4294967296.0, lo);
+        double cs = dot * ri * rj;
+        if (corrected) {
+          const int rs = 32 * wi + 16 * i + 4 * g + r, cl = 32 * wj + 16 * j + c;  // row slot, column slot - 64
+          if (!by_element) {
+            const int ki = slot_of[rs], kj = slot_of[64 + cl];
+            if (ki >= 0) cs += cvec[ki][cl];
+            if (kj >= 0) cs += cvec[kj][rs];
+          } else {
+            const LimbFix &fi = sfix[rs], &fj = sfix[64 + cl];
+            if (fi.n | fj.n) {
+              double corr = 0.0;
+              for (int a = 0; a < fi.n; a++) corr = fma(fi.res[a], (double)(float)fix.X[tj * fix.C + fi.ch[a]], corr);
+              for (int a = 0; a < fj.n; a++) {
+                double xi = (double)(float)fix.X[ti * fix.C + fj.ch[a]];
+                for (int u = 0; u < fi.n; u++)
+                  if (fi.ch[u] == fj.ch[a]) xi -= fi.res[u];
+                corr = fma(fj.res[a], xi, corr);
+              }
+              cs += corr * 1073741824.0 / (fix.nrm[ti] * fix.nrm[tj]);
+            }
+          }
+        }
+        const int32_t v = (int32_t)rint(cs);
+        Sr[(size_t)row * n_loc + col] = v;
+        if (bm != bn) Sr[(size_t)col * n_loc + row] = v;
+      }
+    }
+}
+
+size_t gram_i8_workspace_bytes(const Shape &s) {
+  // (channels: the limb pass keeps a token's row in registers, up to 3072 of them; work: the kernel
+  // goes in 64 x 64 blocks of S, one workgroup each, 64 channels at a time, and with the limb pass in
+  // front it only beats the fp64 kernel's finer units once there are enough block-chunks to fill the
+  // chip several times over - measured: 3200 of them tie, 7680 win by a sixth, 12800 by a quarter)
+  const int nb64 = (s.n_loc + 63) / 64;
+  const long long block_chunks = (long long)s.B * s.P * (nb64 * (nb64 + 1) / 2) * ((s.C + 63) / 64);
+  if (s.dtype != TOMA_BF16 || s.C > 3072 || block_chunks < 4096) return 0;
+  const size_t rows = (size_t)s.B * s.N;
+  const size_t words = (size_t)((s.C + 63) / 64) * 64;  // one word (four limbs) per channel of the padded row
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  return up(rows * words * 4) + 2 * up(rows * sizeof(double)) + up(rows) + up(rows * sizeof(LimbFix));
+}
+
+// S for every region of a bf16 input; ws_part: gram_i8_workspace_bytes() bytes.  Leaves the per-token
+// norms and flags where the selection kernel's prologue finds them (returned through the pointers).
+int launch_gram_i8(const Shape &s, const void *X, int32_t *S, char *ws_part, const double **nrm_out,
+                   const uint8_t **flag_out, hipStream_t st) {
+  const size_t rows = (size_t)s.B * s.N;
+  const int nchunks = (s.C + 63) / 64, row_words = nchunks * 64, groups_pad = nchunks * 4;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  uint32_t *Xq = reinterpret_cast<uint32_t *>(ws_part);
+  double *nrm = reinterpret_cast<double *>(ws_part + up(rows * row_words * 4));
+  double *rnp = reinterpret_cast<double *>(reinterpret_cast<char *>(nrm) + up(rows * sizeof(double)));
+  uint8_t *flag = reinterpret_cast<uint8_t *>(reinterpret_cast<char *>(rnp) + up(rows * sizeof(double)));
+  LimbFix *fixes = reinterpret_cast<LimbFix *>(reinterpret_cast<char *>(flag) + up(rows));
+  RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
+  {
+    KernelTimer kt(K_LIMBS, st);
+    const dim3 grid((unsigned)((rows + 3) / 4));
+    const bf16_t *Xb = static_cast<const bf16_t *>(X);
+    const int iter = (groups_pad + 63) / 64;  // (the padded row: its zero groups are written too)
+#define TOMA_LIMBS_CASE(IT) \
+  hipLaunchKernelGGL(k_limbs<IT>, grid, dim3(256), 0, st, Xb, Xq, nrm, rnp, flag, fixes, (int)rows, s.C, groups_pad)
+    if (iter <= 1) TOMA_LIMBS_CASE(1);
+    else if (iter <= 2) TOMA_LIMBS_CASE(2);
+    else if (iter <= 3) TOMA_LIMBS_CASE(3);
+    else return TOMA_ERR_UNSUPPORTED;
+#undef TOMA_LIMBS_CASE
+  }
+  const int nb64 = (s.n_loc + 63) / 64, units = nb64 * (nb64 + 1) / 2, regions = s.B * s.P;
+  KernelTimer kt(K_GRAM, st);
+  const GramFix gfix{static_cast<const bf16_t *>(X), nrm, flag, fixes, s.C};
+  hipLaunchKernelGGL(k_gram_i8, dim3(units * regions), dim3(256), 0, st, Xq, rnp, S, map, s.N, s.P, s.n_loc, row_words, nchunks,
+                     nb64, units, gfix);
+  *nrm_out = nrm;
+  *flag_out = flag;
+  return launch_status();
+}
+
+}  // namespace toma

@@ -21,7 +21,7 @@ struct Shape {
 
 // Offsets (bytes) of the scratch sections inside the caller's workspace.
 struct Workspace {
-  size_t sim, stats, lse, zpart, os, q, k, v, oh, xm, o, split, pinv, fcache, total;
+  size_t sim, gram, stats, lse, zpart, os, q, k, v, oh, xm, o, split, pinv, fcache, total;
   int stat_parts, z_parts;
   // occupancy map of A, kept by the caller next to (A, Z): blocks of kOccDest destinations x kOccSrc
   // sources per merge region (0: this shape uses none)
@@ -126,13 +126,20 @@ int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s);
 void plan_workspace(const Shape &s, Workspace *w);
 
 // stage launchers (each returns a toma_status)
+// Similarities of bf16 tokens on the int8 matrix cores (toma_gram_i8.hip): scratch size (0: this shape
+// takes the fp64 kernel instead) and launch; nrm_out / flag_out: per-token norms and the flags of tokens
+// whose rows of S the selection kernel has to recompute in double precision
+size_t gram_i8_workspace_bytes(const Shape &s);
+int launch_gram_i8(const Shape &s, const void *X, int32_t *S, char *ws_part, const double **nrm_out,
+                   const uint8_t **flag_out, hipStream_t st);
 // gain, gap: optional outputs (null: not wanted)
 int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, float *gap, char *ws,
                   const Workspace &w, hipStream_t st);
 // Pass 1 of the merge weights alone: stats[region][source][part] = (largest logit, sum of exponentials)
-// over each slice of *slice destinations, lse[region][source] = log-sum-exp over all destinations
+// over each slice of *slice destinations, lse[region][source] = log-sum-exp over all destinations,
+// lse2 = the same as (largest logit, log of the sum)
 int launch_weight_stats(const Shape &s, const void *X, const int32_t *idx, float2 *stats, int stat_parts, float *lse,
-                        int *slice, hipStream_t st);
+                        float2 *lse2, int *slice, hipStream_t st);
 // occ: the occupancy map that travels with (A, Z), w.occ_bytes bytes (null iff the shape uses none).
 // launch_weights writes it along with A and Z; launch_occupancy rebuilds it from a stored A;
 // launch_merge / launch_unmerge read it.
@@ -172,7 +179,7 @@ int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const voi
                void *Out, hipStream_t st);
 
 // Kernel identifiers of the profiling aid (toma_profile_*): one per kernel of the path.
-enum KernelId { K_GRAM = 0, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
+enum KernelId { K_LIMBS = 0, K_GRAM, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
                 K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_PINV_EIG, K_PINV_APPLY, K_MERGE_FUSED, K_UNMERGE_FUSED, K_COUNT };
 
 // Brackets one launch with HIP events on its stream while profiling is enabled; free otherwise.

@@ -209,8 +209,10 @@ template <typename T, bool WRITE> struct WeightsPol {
 // group per row, partials strided over its lanes; the combination order is fixed.
 // On the side it zeroes `zero_words` 32-bit words at `zero` (the occupancy map the write pass that
 // follows fills with ones), so that this needs no launch of its own.
-__global__ __launch_bounds__(256) void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse, int rows,
-                                            int stride, int parts, uint32_t *__restrict__ zero, size_t zero_words) {
+// (lse2, optional: the same as the pair (M, log sum), which keeps the bits that M + log sum rounds away)
+__global__ __launch_bounds__(256) void k_lse(const float2 *__restrict__ stats, float *__restrict__ lse,
+                                            float2 *__restrict__ lse2, int rows, int stride, int parts,
+                                            uint32_t *__restrict__ zero, size_t zero_words) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < zero_words; i += (size_t)gridDim.x * 256) zero[i] = 0;
   int row = (blockIdx.x * 256 + threadIdx.x) >> 4, c = threadIdx.x & 15;
   if (row >= rows) return;
@@ -221,7 +223,11 @@ __global__ __launch_bounds__(256) void k_lse(const float2 *__restrict__ stats, f
   float sum = 0.f;
   for (int i = c; i < parts; i += 16) sum += s[i].y * __expf(s[i].x - mx);
   sum = row16_sum_f32(sum);
-  if (c == 0) lse[row] = mx + __logf(sum);
+  if (c == 0) {
+    const float ls = __logf(sum);
+    lse[row] = mx + ls;
+    if (lse2) lse2[row] = make_float2(mx, ls);
+  }
 }
 
 // Z[j] = sum of the partial row sums (fixed order: reruns are bit-identical).
@@ -655,7 +661,7 @@ int launch_occupancy(const Shape &s, const void *A, uint8_t *occ, const Workspac
 // then lse[source] = log sum over all destinations.  k_lse also zeroes `zero_words` words at `zero`.
 template <typename T>
 static GemmShape stats_pass(const Shape &s, const void *X, const int32_t *idx, float2 *stats, int stat_parts, float *lse,
-                            uint32_t *zero, size_t zero_words, hipStream_t st) {
+                            float2 *lse2, uint32_t *zero, size_t zero_words, hipStream_t st) {
   WeightsPol<T, false> p1{};
   p1.v = make_view<T>(s, X);
   p1.idx = idx; p1.scale = s.scale;
@@ -664,15 +670,15 @@ static GemmShape stats_pass(const Shape &s, const void *X, const int32_t *idx, f
   const GemmShape gs = launch_gemm<T>(K_WSTATS, p1, s.Nr, s.Dr, s.C, batch, st);
   const int rows = batch * s.Nr;
   KernelTimer kt(K_LSE, st);
-  hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, stats, lse, rows, stat_parts, gs.wgn * gs.tiles_n, zero,
-                     zero_words);
+  hipLaunchKernelGGL(k_lse, dim3((rows + 15) / 16), dim3(256), 0, st, stats, lse, lse2, rows, stat_parts, gs.wgn * gs.tiles_n,
+                     zero, zero_words);
   return gs;
 }
 
 int launch_weight_stats(const Shape &s, const void *X, const int32_t *idx, float2 *stats, int stat_parts, float *lse,
-                        int *slice, hipStream_t st) {
-  const GemmShape gs = s.dtype == TOMA_BF16 ? stats_pass<bf16_t>(s, X, idx, stats, stat_parts, lse, nullptr, 0, st)
-                                            : stats_pass<float>(s, X, idx, stats, stat_parts, lse, nullptr, 0, st);
+                        float2 *lse2, int *slice, hipStream_t st) {
+  const GemmShape gs = s.dtype == TOMA_BF16 ? stats_pass<bf16_t>(s, X, idx, stats, stat_parts, lse, lse2, nullptr, 0, st)
+                                            : stats_pass<float>(s, X, idx, stats, stat_parts, lse, lse2, nullptr, 0, st);
   *slice = gs.bn / gs.wgn;
   if (*slice != weight_stats_slice(s.Nr, s.Dr, s.C, s.B * s.R, s.dtype == TOMA_BF16 ? 2 : 4)) return TOMA_ERR_LAUNCH;
   return launch_status();
@@ -721,7 +727,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   const bool own_map = w.occ_sb != 0;
   uint8_t *occ = own_map ? occ_out : nullptr;
   const size_t occ_words = own_map ? ((size_t)batch * w.occ_db * w.occ_sb + 3) / 4 : 0;
-  const GemmShape gs = stats_pass<T>(s, X, idx, stats, w.stat_parts, lse, reinterpret_cast<uint32_t *>(occ), occ_words, st);
+  const GemmShape gs = stats_pass<T>(s, X, idx, stats, w.stat_parts, lse, nullptr, reinterpret_cast<uint32_t *>(occ), occ_words, st);
   WeightsPol<T, true> p2{};
   p2.v = make_view<T>(s, X); p2.idx = idx; p2.scale = s.scale; p2.lse = lse;
   p2.A = static_cast<T *>(A); p2.lda = s.Nr;

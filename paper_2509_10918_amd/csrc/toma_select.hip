@@ -204,14 +204,16 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t k) {
   return ((uint64_t)top_hi << 32) | top_lo;
 }
 
+// What the selection kernel needs to recompute flagged rows of S in double precision (flag == null: none).
+struct RowFix { const bf16_t *X; const double *nrm; const uint8_t *flag; int N, C; };
+
 constexpr uint64_t kNoRunnerUp = ~0ull;  // recorded gap when the pick was the last candidate
 
 template <int NT, bool GAP>
-__global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *__restrict__ S,
-                                                             int32_t *__restrict__ idx,
+__global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int32_t *__restrict__ idx,
                                                              float *__restrict__ gain_out,
                                                              float *__restrict__ gap_out, RegionMap map,
-                                                             int P, int d_loc) {
+                                                             int P, int d_loc, RowFix fix) {
   constexpr int NL = 16 * NT;          // tokens in the region
   constexpr int NW = (NT + 1) / 2;     // waves, up to 32 columns each
   constexpr int RPL = (NL + 63) / 64;  // rows per lane: lane l holds rows RPL l .. RPL l + RPL - 1
@@ -226,7 +228,52 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(const int32_t *_
 
   const int bp = blockIdx.x, p = bp % P;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, cl = lane & 31;
-  const int32_t *Sr = S + (size_t)bp * NL * NL;
+  int32_t *Sr = S + (size_t)bp * NL * NL;
+
+  // Rows of S that the fixed-point similarity kernel could not do exactly (a token with more than a few
+  // elements far below its largest, flag 2: very rare) are recomputed here in double precision, before
+  // anything reads them.
+  if (fix.flag) {
+    const size_t tok0 = (size_t)(bp / P) * fix.N;
+    // (the flags of the region's tokens, one bit each, gathered once: keys[] is free until the rounds start)
+    uint32_t *fbits = reinterpret_cast<uint32_t *>(keys);
+    for (int l = threadIdx.x; l < 8; l += 64 * NW) fbits[l] = 0u;
+    __syncthreads();
+    int mine = 0;
+    for (int l = threadIdx.x; l < NL; l += 64 * NW)
+      if (fix.flag[tok0 + map.token(p, l)] == 2) { mine = 1; atomicOr(&fbits[l >> 5], 1u << (l & 31)); }
+    if (__syncthreads_or(mine)) {
+      for (int t = 0; t < NL; t++) {
+        if (!((fbits[t >> 5] >> (t & 31)) & 1u)) continue;  // (uniform)
+        const size_t tt = tok0 + map.token(p, t);
+        const bf16_t *xt = fix.X + tt * fix.C;
+        // a wave per partner token, its lanes across the channels (eight each per step)
+        for (int j = w; j < NL; j += NW) {
+          const size_t tj = tok0 + map.token(p, j);
+          const bf16_t *xj = fix.X + tj * fix.C;
+          double dot = 0.0;
+          for (int ch = 8 * lane; ch < fix.C; ch += 512) {
+            const Pkt pa = pkt_load(xt + ch), pb = pkt_load(xj + ch);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+              const uint32_t wa = pa.v[u], wb = pb.v[u];
+              dot += (double)__builtin_bit_cast(float, wa << 16) * (double)__builtin_bit_cast(float, wb << 16);
+              dot += (double)__builtin_bit_cast(float, wa & 0xffff0000u) * (double)__builtin_bit_cast(float, wb & 0xffff0000u);
+            }
+          }
+#pragma unroll
+          for (int msk = 1; msk < 64; msk <<= 1) dot += wave_xor_f64(dot, msk);
+          if (lane == 0) {
+            const int32_t v = (int32_t)rint(dot / (fix.nrm[tt] * fix.nrm[tj]) * kSimScale);
+            Sr[(size_t)t * NL + j] = v;
+            Sr[(size_t)j * NL + t] = v;
+          }
+        }
+      }
+      __threadfence();
+      __syncthreads();
+    }
+  }
 
   // Loaded through the symmetric element S[NW c + w][RPL l + v]: a lane reads RPL consecutive
   // words and consecutive lanes continue the run.
@@ -399,6 +446,15 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, f
   int32_t *S = reinterpret_cast<int32_t *>(ws + w.sim);
   RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
   const int tiles = s.n_loc / 16, units = tiles * (tiles + 1) / 2;
+  RowFix fix{nullptr, nullptr, nullptr, s.N, s.C};
+  if (sizeof(T) == 2 && gram_i8_workspace_bytes(s) != 0) {
+    // bf16 tokens: exact similarities on the int8 matrix cores
+    const double *nrm = nullptr;
+    const uint8_t *flag = nullptr;
+    const int rc = launch_gram_i8(s, X, S, ws + w.gram, &nrm, &flag, st);
+    if (rc != TOMA_OK) return rc;
+    fix = RowFix{reinterpret_cast<const bf16_t *>(X), nrm, flag, s.N, s.C};
+  } else
   { KernelTimer kt(K_GRAM, st);
   if (gram_k_split(s) == 2)
     hipLaunchKernelGGL((k_gram<T, 2>), dim3((units + 1) / 2 * s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
@@ -413,10 +469,10 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, f
   case NT:                                                                                                 \
     if (gap)                                                                                               \
       hipLaunchKernelGGL((k_greedy<NT, true>), dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, gap, \
-                         map, s.P, s.d_loc);                                                               \
+                         map, s.P, s.d_loc, fix);                                                          \
     else                                                                                                   \
       hipLaunchKernelGGL((k_greedy<NT, false>), dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, gap, \
-                         map, s.P, s.d_loc);                                                               \
+                         map, s.P, s.d_loc, fix);                                                          \
     break;
     TOMA_GREEDY_CASE(1)
     TOMA_GREEDY_CASE(2)
