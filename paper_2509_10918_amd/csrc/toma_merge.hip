@@ -242,6 +242,119 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
   if (c == 0) Z[row] = sum;
 }
 
+// The softmax over destinations and the stores of the one-pass kernel below.  acc[i][j] holds the
+// raw products of source rows 16 i + 4 g + r against destination 16 NJ w + 16 j + c; red / rowstat are
+// the workgroup's exchange buffers.
+template <typename T, int NJ>
+__device__ __forceinline__ void weights_one_pass_finish(f32x4 (&acc)[2][NJ], const RegionView<T> &v, float scale,
+                                                        T *__restrict__ A, int lda, float *__restrict__ zpart, int zparts,
+                                                        uint8_t *__restrict__ occ, int occ_db, int occ_sb,
+                                                        float (&red)[8][32], float (&rowstat)[32], int z, int mt) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
+  const int m0 = 32 * mt;
+  // ---- softmax over the destinations of every source row ----
+  // lane holds, of rows 16 i + 4 g + r, the columns 16 j + c of its wave's slice.  One exponential
+  // per value: e = 2^((acc - max) scale log2 e) replaces acc, and the stored weight is e / sum(e).
+  // (scale > 0, so the largest raw product is the largest logit; the fused multiply-add rounds
+  // (acc - max) scale once, which keeps the exponent of a logit of several thousand to ~1e-6)
+  const float k2 = scale * 1.44269504088896341f;
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      float m = -__builtin_inff();
+#pragma unroll
+      for (int j = 0; j < NJ; j++) m = fmaxf(m, acc[i][j][r]);
+      m = row16_max_f32(m);
+      if (c == 0) red[w][16 * i + 4 * g + r] = m;
+    }
+  __syncthreads();
+  if (tid < 32) {
+    float m = red[0][tid];
+#pragma unroll
+    for (int ww = 1; ww < 8; ww++) m = fmaxf(m, red[ww][tid]);
+    rowstat[tid] = m;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      const float mk = rowstat[16 * i + 4 * g + r] * k2;
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < NJ; j++) {
+        acc[i][j][r] = __builtin_amdgcn_exp2f(fmaf(acc[i][j][r], k2, -mk));
+        sum += acc[i][j][r];
+      }
+      sum = row16_sum_f32(sum);
+      if (c == 0) red[w][16 * i + 4 * g + r] = sum;  // (every wave read rowstat after the barrier above)
+    }
+  __syncthreads();
+  if (tid < 32) {
+    float sum = red[0][tid];
+#pragma unroll
+    for (int ww = 1; ww < 8; ww++) sum += red[ww][tid];  // fixed order
+    rowstat[tid] = 1.0f / sum;                           // (the row's largest logit contributes 1: sum >= 1)
+  }
+  __syncthreads();
+  // ---- A[j][s] = exp(L - lse[s]) = e / sum in dtype, destination-major; partial row sums of the stored values ----
+  float l4[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) l4[i][r] = rowstat[16 * i + 4 * g + r];
+  // occupancy of this wave's block(s) of A (kOccDest destinations x the workgroup's kOccSrc sources):
+  // any stored value that is not zero?  (occ is only passed when a wave's slice is whole blocks)
+  constexpr int kBlocks = 16 * NJ >= kOccDest ? 16 * NJ / kOccDest : 1;
+  bool nonzero[kBlocks];
+#pragma unroll
+  for (int h = 0; h < kBlocks; h++) nonzero[h] = false;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int n = w * 16 * NJ + 16 * j + c;
+    float colsum = 0.f;
+    alignas(16) T o[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        o[i][r] = from_f32<T>(acc[i][j][r] * l4[i][r]);
+        const float stored = to_f32(o[i][r]);
+        colsum += stored;
+        nonzero[16 * j / kOccDest % kBlocks] |= stored != 0.f;
+      }
+    T *row = A + ((size_t)z * v.Dr + n) * lda + m0;
+    if constexpr (sizeof(T) == 2) {
+      // A lane holds 8 bytes of each source tile (four sources); lanes g and g ^ 1 trade halves so
+      // that each stores one 16-byte packet and the four lanes of a destination a whole 64-byte run
+      // (even g: sources 4 g .. 4 g + 7 of tile 0, odd g: sources 4 (g - 1) .. 4 g + 3 of tile 1)
+      const u32x2 own0 = *reinterpret_cast<u32x2 *>(o[0]), own1 = *reinterpret_cast<u32x2 *>(o[1]);
+      const bool odd = g & 1;
+      const u32x2 give = odd ? own0 : own1;
+      u32x2 got;
+      got[0] = (uint32_t)__shfl_xor((int)give[0], 16, 64);
+      got[1] = (uint32_t)__shfl_xor((int)give[1], 16, 64);
+      const u32x4 pk = odd ? (u32x4){got[0], got[1], own1[0], own1[1]} : (u32x4){own0[0], own0[1], got[0], got[1]};
+      *reinterpret_cast<u32x4 *>(row + (odd ? 16 + 4 * (g - 1) : 4 * g)) = pk;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; i++) *reinterpret_cast<u32x4 *>(row + 16 * i + 4 * g) = *reinterpret_cast<u32x4 *>(o[i]);
+    }
+    colsum += wave_xor_f32(colsum, 16);
+    colsum += wave_xor_f32(colsum, 32);
+    if (g == 0) zpart[((size_t)z * v.Dr + n) * zparts + mt] = colsum;
+  }
+  if (occ) {
+    static_assert(kOccSrc == 32, "one source block per workgroup");
+#pragma unroll
+    for (int h = 0; h < kBlocks; h++) {
+      const bool any = __any(nonzero[h]);
+      if (lane == 0) occ[((size_t)z * occ_db + w * kBlocks + h) * occ_sb + mt] = any ? 1 : 0;
+    }
+  }
+}
+
 // ---- weights in one pass ------------------------------------------------------------------------
 // One workgroup (8 waves) holds the logits of 32 sources against ALL Dr = 128 NJ destinations of the
 // merge region in its accumulators (wave w: destinations 16 NJ w .. 16 NJ (w + 1) - 1, 2 x NJ MFMA
@@ -257,7 +370,8 @@ __global__ __launch_bounds__(256) void k_zsum(const float *__restrict__ zpart, f
 template <typename T, int NJ>
 __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, const int32_t *__restrict__ idx, float scale,
                                                      T *__restrict__ A, int lda, float *__restrict__ zpart,
-                                                     int zparts, uint8_t *__restrict__ occ, int occ_db, int occ_sb) {
+                                                     int zparts, uint8_t *__restrict__ occ, int occ_db, int occ_sb,
+                                                     int tiles) {
   constexpr int ES = (int)sizeof(T), EPS = 128 / ES;   // elements per K step
   constexpr int EPP = 16 / ES;
   constexpr int NH = ES == 2 ? 2 : 1;                  // fragments per row per K step
@@ -272,8 +386,12 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
   __shared__ float rowstat[32];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
-  const int z = blockIdx.y, b = z / v.R, rho = z % v.R;
-  const int m0 = blockIdx.x * 32;
+  // Every workgroup of a region streams the region's whole set of destination rows: the workgroups an
+  // XCD receives are consecutive source tiles of as few regions as possible, so that those rows stay
+  // in its L2 (two samples' rows at SDXL's first stage would not fit one L2 together).
+  const int work = xcd_remap(blockIdx.x, gridDim.x);
+  const int z = work / tiles, mt = work - z * tiles, b = z / v.R, rho = z % v.R;
+  const int m0 = mt * 32;
   const T *Xb = v.X + (size_t)b * v.N * v.C;
 
   // what this lane fetches of a 1 KiB chunk (8 rows x 128 bytes): row lane / 8, and the packet that
@@ -368,104 +486,7 @@ __global__ __launch_bounds__(512) void k_weights_fused(const RegionView<T> v, co
     fence();
   }
 
-  // ---- softmax over the destinations of every source row ----
-  // lane holds, of rows 16 i + 4 g + r, the columns 16 j + c of its wave's slice
-  float mx[2][4];
-#pragma unroll
-  for (int i = 0; i < 2; i++)
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      float m = -__builtin_inff();
-#pragma unroll
-      for (int j = 0; j < NJ; j++) {
-        acc[i][j][r] *= scale;
-        m = fmaxf(m, acc[i][j][r]);
-      }
-      m = row16_max_f32(m);
-      if (c == 0) red[w][16 * i + 4 * g + r] = m;
-    }
-  __syncthreads();
-  if (tid < 32) {
-    float m = red[0][tid];
-#pragma unroll
-    for (int ww = 1; ww < 8; ww++) m = fmaxf(m, red[ww][tid]);
-    rowstat[tid] = m;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < 2; i++)
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      mx[i][r] = rowstat[16 * i + 4 * g + r];
-      float sum = 0.f;
-#pragma unroll
-      for (int j = 0; j < NJ; j++) sum += __expf(acc[i][j][r] - mx[i][r]);
-      sum = row16_sum_f32(sum);
-      if (c == 0) red[w][16 * i + 4 * g + r] = sum;  // (every wave read rowstat after the barrier above)
-    }
-  __syncthreads();
-  if (tid < 32) {
-    float sum = red[0][tid];
-#pragma unroll
-    for (int ww = 1; ww < 8; ww++) sum += red[ww][tid];  // fixed order
-    rowstat[tid] = rowstat[tid] + __logf(sum);           // lse
-  }
-  __syncthreads();
-  // ---- A[j][s] = exp(L - lse[s]) in dtype, destination-major; partial row sums of the stored values ----
-  float l4[2][4];
-#pragma unroll
-  for (int i = 0; i < 2; i++)
-#pragma unroll
-    for (int r = 0; r < 4; r++) l4[i][r] = rowstat[16 * i + 4 * g + r];
-  // occupancy of this wave's block(s) of A (kOccDest destinations x the workgroup's kOccSrc sources):
-  // any stored value that is not zero?  (occ is only passed when a wave's slice is whole blocks)
-  constexpr int kBlocks = 16 * NJ >= kOccDest ? 16 * NJ / kOccDest : 1;
-  bool nonzero[kBlocks];
-#pragma unroll
-  for (int h = 0; h < kBlocks; h++) nonzero[h] = false;
-#pragma unroll
-  for (int j = 0; j < NJ; j++) {
-    const int n = w * 16 * NJ + 16 * j + c;
-    float colsum = 0.f;
-    alignas(16) T o[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; i++)
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        o[i][r] = from_f32<T>(__expf(acc[i][j][r] - l4[i][r]));
-        const float stored = to_f32(o[i][r]);
-        colsum += stored;
-        nonzero[16 * j / kOccDest % kBlocks] |= stored != 0.f;
-      }
-    T *row = A + ((size_t)z * v.Dr + n) * lda + m0;
-    if constexpr (sizeof(T) == 2) {
-      // A lane holds 8 bytes of each source tile (four sources); lanes g and g ^ 1 trade halves so
-      // that each stores one 16-byte packet and the four lanes of a destination a whole 64-byte run
-      // (even g: sources 4 g .. 4 g + 7 of tile 0, odd g: sources 4 (g - 1) .. 4 g + 3 of tile 1)
-      const u32x2 own0 = *reinterpret_cast<u32x2 *>(o[0]), own1 = *reinterpret_cast<u32x2 *>(o[1]);
-      const bool odd = g & 1;
-      const u32x2 give = odd ? own0 : own1;
-      u32x2 got;
-      got[0] = (uint32_t)__shfl_xor((int)give[0], 16, 64);
-      got[1] = (uint32_t)__shfl_xor((int)give[1], 16, 64);
-      const u32x4 pk = odd ? (u32x4){got[0], got[1], own1[0], own1[1]} : (u32x4){own0[0], own0[1], got[0], got[1]};
-      *reinterpret_cast<u32x4 *>(row + (odd ? 16 + 4 * (g - 1) : 4 * g)) = pk;
-    } else {
-#pragma unroll
-      for (int i = 0; i < 2; i++) *reinterpret_cast<u32x4 *>(row + 16 * i + 4 * g) = *reinterpret_cast<u32x4 *>(o[i]);
-    }
-    colsum += wave_xor_f32(colsum, 16);
-    colsum += wave_xor_f32(colsum, 32);
-    if (g == 0) zpart[((size_t)z * v.Dr + n) * zparts + blockIdx.x] = colsum;
-  }
-  if (occ) {
-    static_assert(kOccSrc == 32, "one source block per workgroup");
-#pragma unroll
-    for (int h = 0; h < kBlocks; h++) {
-      const bool any = __any(nonzero[h]);
-      if (lane == 0) occ[((size_t)z * occ_db + w * kBlocks + h) * occ_sb + blockIdx.x] = any ? 1 : 0;
-    }
-  }
+  weights_one_pass_finish<T, NJ>(acc, v, scale, A, lda, zpart, zparts, occ, occ_db, occ_sb, red, rowstat, z, mt);
 }
 
 // ---- merge -------------------------------------------------------------------------------------
@@ -692,17 +713,18 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   float *zpart = reinterpret_cast<float *>(ws + w.zpart);
   if (weights_single_pass(s.Nr, s.Dr, s.C, batch, (int)sizeof(T))) {
     const RegionView<T> v = make_view<T>(s, X);
-    const dim3 grid(s.Nr / 32, batch);
+    const int tiles = s.Nr / 32;
+    const dim3 grid(tiles * batch);
     // the kernel fills the occupancy map itself when a wave's slice of destinations is whole blocks
     const bool own_map = w.occ_sb != 0 && (s.Dr / 8) % kOccDest == 0;
     uint8_t *occ = own_map ? occ_out : nullptr;
     {
       KernelTimer kt(K_WWRITE, st);
       switch (s.Dr / 128) {
-#define TOMA_WF_CASE(NJ)                                                                                       \
-  case NJ:                                                                                                     \
-    hipLaunchKernelGGL((k_weights_fused<T, NJ>), grid, dim3(512), 0, st, v, idx, s.scale, static_cast<T *>(A), \
-                       s.Nr, zpart, w.z_parts, occ, w.occ_db, w.occ_sb);                                       \
+#define TOMA_WF_CASE(NJ)                                                                                         \
+  case NJ:                                                                                                       \
+    hipLaunchKernelGGL((k_weights_fused<T, NJ>), grid, dim3(512), 0, st, v, idx, s.scale, static_cast<T *>(A),   \
+                       s.Nr, zpart, w.z_parts, occ, w.occ_db, w.occ_sb, tiles);                                  \
     break;
         TOMA_WF_CASE(1)
         TOMA_WF_CASE(2)
