@@ -46,7 +46,7 @@ def executed_fraction(amap, desc, which, tile, esize):
     return float(act.mean())
 
 
-def kernel_work(w, R, esize, exec_frac=None):
+def kernel_work(w, R, esize, exec_frac=None, int8_gram=False):
     """Work per launch of each kernel: name -> dict(bound, amount, [equiv, limit]).
     amount = what the kernel as built has to execute or move (flops for the matrix-core kernels, bytes
     for the streaming ones); equiv = the count of the textbook formulation where the kernel reaches the
@@ -60,13 +60,16 @@ def kernel_work(w, R, esize, exec_frac=None):
     tiles = w.n_loc // 16
     tri = (tiles * (tiles + 1) / 2) / (tiles * tiles)      # blocks on or above the diagonal
     ef = exec_frac or {}
-    if w.dtype == "bf16":
-        # exact similarities on the int8 matrix cores: sixteen limb-pair products per pair of 32-token
-        # blocks on or above the diagonal, channels padded to 64
-        nb = (w.n_loc + 31) // 32
+    if int8_gram:
+        # exact similarities on the int8 matrix cores: sixteen limb-pair products per 64 x 32 block of S on or
+        # above the diagonal, channels padded to 64
+        nb64, nb32 = (w.n_loc + 63) // 64, (w.n_loc + 31) // 32
+        units = sum(nb32 - 2 * bm for bm in range(nb64))
         cpad = (w.C + 63) // 64 * 64
-        gram = dict(bound="i8", amount=16 * 2 * w.B * w.P * (nb * (nb + 1) // 2) * 32 * 32 * cpad, equiv=f["similarity"],
-                    limit="int8 matrix cores at one wave per SIMD (268 registers), operands straight from L2")
+        gram = dict(bound="i8", amount=16 * 2 * w.B * w.P * units * 64 * 32 * cpad, equiv=f["similarity"],
+                    limit="LDS bandwidth and fixed cost: a 32 x 16 wave tile reads 384 bytes of limbs per product "
+                          "(about 64 bytes a clock per CU is what 16-byte LDS reads reach here), and some 10 us per "
+                          "launch go to first loads, norms, the double-precision combination and the stores")
     else:
         gram = dict(bound="f64", amount=f["similarity"] * tri, equiv=f["similarity"],
                     limit="issue rate of the fp64 matrix-core products (a bare loop of them reaches 43-47 TFLOP/s)")
@@ -79,7 +82,11 @@ def kernel_work(w, R, esize, exec_frac=None):
                              "read once and stays in registers, 32 of 256 CUs are busy"),
         "weights_stats": dict(bound=mm, amount=f["weights"]),
         "lse": dict(bound="hbm", amount=w.B * w.N * 12),
-        "weights_write": dict(bound=mm, amount=f["weights"]),
+        # (the write pass of the two-pass weights skips the product of tiles that the first pass proved empty)
+        "weights_write": (dict(bound=mm, amount=f["weights"] * ef["weights_write"], equiv=f["weights"]) if "weights_write" in ef
+                          else dict(bound=mm, amount=f["weights"],
+                                    limit="L2 to CU bandwidth: every 32-source workgroup streams all destination rows "
+                                          "(with the products or the loads taken out the loop takes 30 / 21 of its 35 us)")),
         "zsum": dict(bound="hbm", amount=w.B * w.D * 8, limit="launch latency"),
         "merge": dict(bound=mm, amount=f["merge"] * ef.get("merge", 1.0), equiv=f["merge"]),
         "qkv": dict(bound=mm, amount=f["qkv"]),
@@ -249,7 +256,18 @@ def main():
             tile = tb.toma_profile_map_product(desc, which)
             if tile is not None:
                 exec_frac[name] = executed_fraction(m, desc, which, tile, esize)
-    work = kernel_work(w, R, esize, exec_frac)
+        tile = tb.toma_profile_map_product(desc, 2)
+        if tile is not None and "weights_write" in per_kernel:
+            # tiles of (tile[0] sources x tile[1] destinations) that hold a nonzero block: a lower bound on
+            # the tiles the write pass computes (it also computes tiles whose weights all round to zero but
+            # lie less than e^-110 below their row's sum)
+            spt, dpt = max(tile[0] // 32, 1), max(tile[1] // 128, 1)
+            occ = m != 0
+            z, db, sb = occ.shape
+            pad_d, pad_s = (-db) % dpt, (-sb) % spt
+            occ = np.pad(occ, ((0, 0), (0, pad_d), (0, pad_s)))
+            exec_frac["weights_write"] = float(occ.reshape(z, (db + pad_d) // dpt, dpt, (sb + pad_s) // spt, spt).any(axis=(2, 4)).mean())
+    work = kernel_work(w, R, esize, exec_frac, int8_gram="limbs" in per_kernel)
     # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command (profiles/)
     traffic = {}
     try:
@@ -262,9 +280,9 @@ def main():
         rec.update({k: v for k, v in roofline_entry(name, work, rec["avg_us"], traffic.get(name)).items()
                     if k != "kernel"})
     if "merge" in exec_frac:
-        for name in ("merge", "unmerge"):
-            if name in per_kernel:
-                per_kernel[name]["executed_share_of_k_steps"] = exec_frac[name]
+        for name in ("merge", "unmerge", "weights_write"):
+            if name in per_kernel and name in exec_frac:
+                per_kernel[name]["executed_share_of_k_steps" if name != "weights_write" else "executed_share_of_tiles_lower_bound"] = exec_frac[name]
     dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
     roofline = roofline_entry(dominant, work, per_kernel[dominant]["avg_us"], traffic.get(dominant))
     roofline["avg_us"] = per_kernel[dominant]["avg_us"]

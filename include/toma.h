@@ -287,7 +287,8 @@ int toma_mlp(int32_t dtype, int32_t rows, int32_t C, int32_t hidden, const void 
 int toma_profile_enable(int on);
 const char *toma_profile_kernel_name(int i);
 int toma_profile_read(const char *kernel, int32_t *launches, float *total_ms);
-/* Block tile the merge (which = 0) or unmerge (which = 1) product of this descriptor runs with:
+/* Block tile the merge (which = 0) or unmerge (which = 1) product of this descriptor runs with, or
+ * (which = 2) the write pass of the two-pass merge weights (rows = sources, columns = destinations):
  * out3 = {rows of the output per workgroup, columns, K split}.  A benchmark that holds the block map
  * can count from it which K steps (128 bytes of elements each) a workgroup's tile runs and so the
  * products actually executed.  Host arithmetic only; TOMA_ERR_UNSUPPORTED when the product does not

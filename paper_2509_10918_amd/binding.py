@@ -246,7 +246,8 @@ def toma_profile_read(kernel):
 
 
 def toma_profile_map_product(desc, which):
-    """(rows, columns, K split) of the block tile of the merge (0) / unmerge (1) product, or None."""
+    """(rows, columns, K split) of the block tile of the merge (0) / unmerge (1) product or of the write
+    pass of the two-pass weights (2), or None."""
     out = (ctypes.c_int32 * 3)()
     rc = lib().toma_profile_map_product(_ref(desc), int(which), out)
     return None if rc != 0 else tuple(out)

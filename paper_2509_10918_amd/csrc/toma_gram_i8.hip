@@ -17,9 +17,9 @@
 //              its channel and the part of its value that was dropped, which k_gram_i8's epilogue adds
 //              back exactly; a token with more than a few such elements has its rows of S recomputed
 //              in double precision by the selection kernel's prologue instead.
-//   k_gram_i8  one workgroup per (region, pair of 64-token blocks on or above the diagonal), the two
-//              panels of limbs staged through LDS per 64 channels, 64 products per wave and chunk; the
-//              epilogue scales by the tokens' norms, rounds to the grid and stores both triangles.
+//   k_gram_i8  one workgroup per (region, 64 x 32 block of S on or above the diagonal), the two panels of
+//              limbs staged through LDS per 64 channels, 32 products per wave and chunk; the epilogue
+//              scales by the tokens' norms, rounds to the grid and stores both triangles.
 // Limb layout: token row = ceil(C / 64) * 64 channels; per group of 16 channels 64 bytes: limb 0 of the
 // 16 channels, then limb 1, 2, 3.  A lane's operand for one limb and 16 channels is one 16-byte packet.
 #include "toma_common.h"
@@ -140,211 +140,245 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
   }
 }
 
-// One workgroup of four waves (2 x 2) per (region, pair of 64-token blocks on or above the diagonal):
-// wave (wi, wj) owns the 32 x 32 block of S made of tokens 32 wi .. of the row block and 32 wj .. of
-// the column block, as 2 x 2 tiles with seven int32 accumulators each (one per limb-index sum).  Per
-// 64 channels the two 64-token panels (256 bytes of limbs per token) go global -> registers -> LDS once
-// and every wave reads its 32 + 32 rows from there: half the L2 traffic of waves fetching their own
-// operands, which is what bounded that variant.  The next chunk's panels are fetched into registers
-// while the matrix cores work on the current one.
+// One workgroup of four waves (2 x 2) per (region, 64-token row block, 32-token column block at or right
+// of the row block's diagonal): wave (wi, wj) owns the 32 x 16 block of S made of tokens 32 wi .. of the
+// row block and 16 wj .. of the column block, as 2 x 1 tiles with seven int32 accumulators each (one per
+// limb-index sum).  Per 64 channels the two panels (256 bytes of limbs per token) go global -> registers
+// -> LDS once and every wave reads its 32 + 16 rows from there.  The LDS panels are double buffered, the
+// next chunk is fetched into registers while the matrix cores work on the current one, and three
+// workgroups share a CU: units this small keep every CU of the chip busy on an SDXL-sized input (640
+// of them) and hide each other's memory latency, which is what bounded 64 x 64 units.
 constexpr int kGramRow = 256 + 16;  // bytes per token and chunk in LDS: 16 packets plus one of padding (bank spread)
+constexpr int kGramPanel = (64 + 32) * kGramRow;  // row panel, then column panel
 
 // with the fixed-point dot product and the norms: cos * 2^30 = dot_q * rnp_i * rnp_j.  A token whose
 // fixed point dropped part of an element (flag 1) has x = xq + res on the listed channels, so
 // <x_i, x_j> = <xq_i, xq_j> + sum_fix(i) res * x_j[ch] + sum_fix(j) res * xq_i[ch].
 struct GramFix { const bf16_t *X; const double *nrm; const uint8_t *flag; const LimbFix *fixes; int C; };
 
-__global__ __launch_bounds__(256, 2) void k_gram_i8(const uint32_t *__restrict__ Xq, const double *__restrict__ rnp,
+// units of a region: row block bm (64 tokens) with the column blocks (32 tokens) 2 bm .. nb32 - 1
+__host__ __device__ inline int gram_units(int n_loc) {
+  const int nb64 = (n_loc + 63) / 64, nb32 = (n_loc + 31) / 32;
+  int u = 0;
+  for (int bm = 0; bm < nb64; bm++) u += nb32 - 2 * bm;
+  return u;
+}
+
+__global__ __launch_bounds__(256, 3) void k_gram_i8(const uint32_t *__restrict__ Xq, const double *__restrict__ rnp,
                                                    int32_t *__restrict__ S, RegionMap map, int N, int P, int n_loc,
-                                                   int row_words, int nchunks, int nb64, int units, GramFix fix) {
-  __shared__ __align__(16) char panel[2][64 * kGramRow];  // [A rows | B rows]
+                                                   int row_words, int nchunks, int units, GramFix fix) {
+  constexpr int kSlots = 8;  // flagged tokens of a unit that get a vector of corrections (see below)
+  struct FixArea { LimbFix sfix[96]; double cvec[kSlots][64]; int8_t slot_of[96]; uint8_t flagged[kSlots]; int nflagged; };
+  static_assert(sizeof(FixArea) <= 2 * kGramPanel, "the corrections reuse the panels' memory");
+  __shared__ __align__(16) char smem[2 * kGramPanel];  // two buffers of [64 row tokens | 32 column tokens]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
   const int wi = w >> 1, wj = w & 1;
   const int work = xcd_remap(blockIdx.x, gridDim.x);
   const int bp = work / units, unit = work - bp * units;
-  int bm = 0, rest = unit;  // unit enumerates the block pairs (bm <= bn) row by row
-  while (rest >= nb64 - bm) { rest -= nb64 - bm; bm++; }
-  const int bn = bm + rest;
+  const int nb32 = (n_loc + 31) / 32;
+  int bm = 0, rest = unit;
+  while (rest >= nb32 - 2 * bm) { rest -= nb32 - 2 * bm; bm++; }
+  const int bn = 2 * bm + rest;  // column block (32 tokens)
   const int b = bp / P, p = bp % P;
+  const int row0 = 64 * bm, col0 = 32 * bn;
 
-  // staging: thread t moves packets t, t + 256, ... of each panel (64 rows x 16 packets per chunk)
-  const uint32_t *src[2][4];
-  int dst[4];
+  // staging: thread t moves packets t, t + 256, ... of the panels (96 rows x 16 packets per chunk)
+  const uint32_t *src[6];
+  int dst[6];
 #pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int q = tid + 256 * u, row = q >> 4, pk = q & 15;
-    const int la = min(64 * bm + row, n_loc - 1), lb = min(64 * bn + row, n_loc - 1);
-    src[0][u] = Xq + ((size_t)b * N + map.token(p, la)) * row_words + 4 * pk;
-    src[1][u] = Xq + ((size_t)b * N + map.token(p, lb)) * row_words + 4 * pk;
+  for (int u = 0; u < 6; u++) {
+    const int q = tid + 256 * u, row = q >> 4, pk = q & 15;  // rows 0..63: row panel, 64..95: column panel
+    const int l = min(row < 64 ? row0 + row : col0 + row - 64, n_loc - 1);
+    src[u] = Xq + ((size_t)b * N + map.token(p, l)) * row_words + 4 * pk;
     dst[u] = row * kGramRow + 16 * pk;
   }
-  i32x4 stage[2][4];
-  auto fetch = [&](int k) {
+  // two register sets: chunk k travels in set k % 2, fetched three steps before its products
+  i32x4 stage[2][6];
+  auto fetch = [&](int k, auto set) {
 #pragma unroll
-    for (int h = 0; h < 2; h++)
-#pragma unroll
-      for (int u = 0; u < 4; u++) stage[h][u] = *reinterpret_cast<const i32x4 *>(src[h][u] + 64 * k);
+    for (int u = 0; u < 6; u++) stage[set()][u] = *reinterpret_cast<const i32x4 *>(src[u] + 64 * k);
   };
-  auto stash = [&]() {
+  auto stash = [&](int buf, auto set) {
 #pragma unroll
-    for (int h = 0; h < 2; h++)
-#pragma unroll
-      for (int u = 0; u < 4; u++) *reinterpret_cast<i32x4 *>(&panel[h][dst[u]]) = stage[h][u];
+    for (int u = 0; u < 6; u++) *reinterpret_cast<i32x4 *>(&smem[buf * kGramPanel + dst[u]]) = stage[set()][u];
   };
+  auto set0 = [] { return 0; };
+  auto set1 = [] { return 1; };
 
-  // does any of this block pair's 128 tokens carry a correction?  (almost never; the flag is asked
-  // for here and first looked at after the main loop, so its latency costs nothing)
+  // does any of this unit's 96 tokens carry a correction?  (almost never; the flag is asked for here
+  // and first looked at after the main loop, so its latency costs nothing)
   uint8_t my_flag = 0;
   size_t my_token = 0;
-  if (tid < 128) {
-    const int l = 64 * (tid < 64 ? bm : bn) + (tid & 63);
+  if (tid < 96) {
+    const int l = tid < 64 ? row0 + tid : col0 + tid - 64;
     my_token = (size_t)b * N + map.token(p, min(l, n_loc - 1));
     my_flag = l < n_loc ? fix.flag[my_token] : 0;
   }
 
-  i32x4 acc[2][2][7];
+  i32x4 acc[2][7];
 #pragma unroll
   for (int i = 0; i < 2; i++)
 #pragma unroll
-    for (int j = 0; j < 2; j++)
-#pragma unroll
-      for (int s = 0; s < 7; s++) acc[i][j][s] = (i32x4){0, 0, 0, 0};
+    for (int s = 0; s < 7; s++) acc[i][s] = (i32x4){0, 0, 0, 0};
 
-  // this lane's operand packets: row 32 wi + 16 t + c (A) / 32 wj + 16 t + c (B), channel group g, limb l
-  const char *fa = &panel[0][(32 * wi + c) * kGramRow + 64 * g];
-  const char *fb = &panel[1][(32 * wj + c) * kGramRow + 64 * g];
-  fetch(0);
-  for (int k = 0; k < nchunks; k++) {
-    __syncthreads();  // every wave is done with the previous chunk's panels
-    stash();
-    __syncthreads();
-    if (k + 1 < nchunks) fetch(k + 1);
-    i32x4 a[2][4], bb[2][4];
+  // this lane's operand packets: row 32 wi + 16 t + c of the row panel / 16 wj + c of the column panel,
+  // channel group g, limb l
+  const int fa = (32 * wi + c) * kGramRow + 64 * g;
+  const int fb = (64 + 16 * wj + c) * kGramRow + 64 * g;
+  auto products = [&](int k) {
+    const char *buf = &smem[(k & 1) * kGramPanel];
+    i32x4 a[2][4], bb[4];
 #pragma unroll
-    for (int t = 0; t < 2; t++)
+    for (int l = 0; l < 4; l++) {
+      bb[l] = *reinterpret_cast<const i32x4 *>(buf + fb + 16 * l);
 #pragma unroll
-      for (int l = 0; l < 4; l++) {
-        a[t][l] = *reinterpret_cast<const i32x4 *>(fa + 16 * t * kGramRow + 16 * l);
-        bb[t][l] = *reinterpret_cast<const i32x4 *>(fb + 16 * t * kGramRow + 16 * l);
-      }
+      for (int t = 0; t < 2; t++) a[t][l] = *reinterpret_cast<const i32x4 *>(buf + fa + 16 * t * kGramRow + 16 * l);
+    }
 #pragma unroll
     for (int la = 0; la < 4; la++)
 #pragma unroll
       for (int lb = 0; lb < 4; lb++)
 #pragma unroll
         for (int i = 0; i < 2; i++)
-#pragma unroll
-          for (int j = 0; j < 2; j++)
-            acc[i][j][la + lb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i][la], bb[j][lb], acc[i][j][la + lb], 0, 0, 0);
+          acc[i][la + lb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i][la], bb[lb], acc[i][la + lb], 0, 0, 0);
+  };
+  // step k: chunk k + 1 from its register set into the other LDS buffer (every wave left that buffer at
+  // the barrier that ended step k - 1), chunk k + 3 into the freed register set, products of chunk k
+  auto step = [&](int k, auto next_set) {
+    if (k + 1 < nchunks) stash((k + 1) & 1, next_set);
+    if (k + 3 < nchunks) fetch(k + 3, next_set);
+    products(k);
+    __syncthreads();
+  };
+  fetch(0, set0);
+  stash(0, set0);
+  if (nchunks > 1) fetch(1, set1);
+  if (nchunks > 2) fetch(2, set0);
+  __syncthreads();
+  for (int k = 0; k < nchunks; k += 2) {
+    step(k, set1);
+    if (k + 1 < nchunks) step(k + 1, set0);
   }
 
-  // Corrections (rare).  Slots 0..63 are the pair's row tokens, 64..127 its column tokens.  Up to kSlots
-  // flagged slots get a vector of 64 corrections each, one per partner on the other side, computed by
+  // Corrections (rare).  Slots 0..63 are the unit's row tokens, 64..95 its column tokens.  Up to kSlots
+  // flagged slots get a vector of corrections each, one per partner on the other side, computed by
   // the whole workgroup with every load independent; beyond that (never seen) each element looks its
-  // correction up by itself, slowly.
-  constexpr int kSlots = 8;
-  __shared__ LimbFix sfix[128];  // n = 0 for a token without corrections
-  __shared__ double cvec[kSlots][64];
-  __shared__ int8_t slot_of[128];
-  __shared__ uint8_t flagged[kSlots];
-  __shared__ int nflagged;
-  if (tid == 0) nflagged = 0;
+  // correction up by itself, slowly.  (The panels are dead by now: the loop ended with a barrier.)
+  FixArea &fx = *reinterpret_cast<FixArea *>(smem);
+  if (tid == 0) fx.nflagged = 0;
   const bool corrected = __syncthreads_or(my_flag == 1) != 0;
   bool by_element = false;
   if (corrected) {
-    if (tid < 128) {
+    if (tid < 96) {
       if (my_flag == 1) {
-        sfix[tid] = fix.fixes[my_token];
-        const int k = atomicAdd(&nflagged, 1);
-        slot_of[tid] = (int8_t)(k < kSlots ? k : -1);
-        if (k < kSlots) flagged[k] = (uint8_t)tid;
+        fx.sfix[tid] = fix.fixes[my_token];
+        const int k = atomicAdd(&fx.nflagged, 1);
+        fx.slot_of[tid] = (int8_t)(k < kSlots ? k : -1);
+        if (k < kSlots) fx.flagged[k] = (uint8_t)tid;
       } else {
-        sfix[tid].n = 0;
-        slot_of[tid] = -1;
+        fx.sfix[tid].n = 0;
+        fx.slot_of[tid] = -1;
       }
     }
     __syncthreads();
-    by_element = nflagged > kSlots;
-    const int nf = min(nflagged, kSlots);
+    by_element = fx.nflagged > kSlots;
+    const int nf = min(fx.nflagged, kSlots);
     for (int k = w; k < nf; k += 4) {
-      const int f = flagged[k], q = 64 * (1 - (f >> 6)) + lane;  // the flagged slot and this lane's partner slot
-      const int lf = min(64 * (f < 64 ? bm : bn) + (f & 63), n_loc - 1), lq = min(64 * (q < 64 ? bm : bn) + lane, n_loc - 1);
+      // the flagged slot f and this lane's partner slot q on the other side (32 column partners only)
+      const int f = fx.flagged[k];
+      const bool f_is_row = f < 64;
+      if (f_is_row && lane >= 32) continue;
+      const int q = f_is_row ? 64 + lane : lane;
+      const int lf = min(f_is_row ? row0 + f : col0 + f - 64, n_loc - 1), lq = min(f_is_row ? col0 + lane : row0 + lane, n_loc - 1);
       const size_t tf = (size_t)b * N + map.token(p, lf), tq = (size_t)b * N + map.token(p, lq);
-      const LimbFix &ff = sfix[f], &fq = sfix[q];
+      const LimbFix &ff = fx.sfix[f], &fq = fx.sfix[q];
       double corr = 0.0;
 #pragma unroll
-      for (int a = 0; a < kFixMax; a++)
-        if (a < ff.n) {
-          double xq = (double)(float)fix.X[tq * fix.C + ff.ch[a]];
+      for (int e = 0; e < kFixMax; e++)
+        if (e < ff.n) {
+          double xq = (double)(float)fix.X[tq * fix.C + ff.ch[e]];
           // a column token's dropped parts meet the row token's fixed-point value, not its full one
-          if (f >= 64)
+          if (!f_is_row)
             for (int u = 0; u < fq.n; u++)
-              if (fq.ch[u] == ff.ch[a]) xq -= fq.res[u];
-          corr = fma(ff.res[a], xq, corr);
+              if (fq.ch[u] == ff.ch[e]) xq -= fq.res[u];
+          corr = fma(ff.res[e], xq, corr);
         }
-      cvec[k][lane] = corr * 1073741824.0 / (fix.nrm[tf] * fix.nrm[tq]);
+      fx.cvec[k][lane] = corr * 1073741824.0 / (fix.nrm[tf] * fix.nrm[tq]);
     }
     __syncthreads();
   }
 
-  // cos * 2^30 = (sum_s acc_s 256^s) * rnp_i * rnp_j; lane holds column (token j) c and rows 4 g + r
+  // cos * 2^30 = (sum_s acc_s 256^s) * rnp_i * rnp_j; lane holds column (token j) c and rows 4 g + r.
+  // Units right of the diagonal 64 x 64 block also store the transposed element; the two units of the
+  // diagonal block cover it between them.
   int32_t *Sr = S + (size_t)bp * n_loc * n_loc;
+  const bool mirror = bn >= 2 * bm + 2;
+  const int cl = 16 * wj + c, col = col0 + cl;
+  const bool col_ok = col < n_loc;
+  const size_t tj = (size_t)b * N + map.token(p, min(col, n_loc - 1));
+  const double rj = rnp[tj];
 #pragma unroll
-  for (int i = 0; i < 2; i++)
+  for (int i = 0; i < 2; i++) {
+    i32x4 v4 = {0, 0, 0, 0};
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-      const int col = 64 * bn + 32 * wj + 16 * j + c;
-      const bool col_ok = col < n_loc;
-      const size_t tj = (size_t)b * N + map.token(p, min(col, n_loc - 1));
-      const double rj = rnp[tj];
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const int row = 64 * bm + 32 * wi + 16 * i + 4 * g + r;
-        if (!col_ok || row >= n_loc) continue;
-        const size_t ti = (size_t)b * N + map.token(p, row);
-        const double ri = rnp[ti];
-        // the three high sums are exact in double (below 2^48); the low four lose at most 2^3 of 2^58 and up
-        const double hi = fma((double)acc[i][j][6][r], 65536.0, fma((double)acc[i][j][5][r], 256.0, (double)acc[i][j][4][r]));
-        const double lo = fma((double)acc[i][j][3][r], 16777216.0,
-                              fma((double)acc[i][j][2][r], 65536.0, fma((double)acc[i][j][1][r], 256.0, (double)acc[i][j][0][r])));
-        const double dot = fma(hi, 4294967296.0, lo);
-        double cs = dot * ri * rj;
-        if (corrected) {
-          const int rs = 32 * wi + 16 * i + 4 * g + r, cl = 32 * wj + 16 * j + c;  // row slot, column slot - 64
-          if (!by_element) {
-            const int ki = slot_of[rs], kj = slot_of[64 + cl];
-            if (ki >= 0) cs += cvec[ki][cl];
-            if (kj >= 0) cs += cvec[kj][rs];
-          } else {
-            const LimbFix &fi = sfix[rs], &fj = sfix[64 + cl];
-            if (fi.n | fj.n) {
-              double corr = 0.0;
-              for (int a = 0; a < fi.n; a++) corr = fma(fi.res[a], (double)(float)fix.X[tj * fix.C + fi.ch[a]], corr);
-              for (int a = 0; a < fj.n; a++) {
-                double xi = (double)(float)fix.X[ti * fix.C + fj.ch[a]];
-                for (int u = 0; u < fi.n; u++)
-                  if (fi.ch[u] == fj.ch[a]) xi -= fi.res[u];
-                corr = fma(fj.res[a], xi, corr);
-              }
-              cs += corr * 1073741824.0 / (fix.nrm[ti] * fix.nrm[tj]);
+    for (int r = 0; r < 4; r++) {
+      const int rs = 32 * wi + 16 * i + 4 * g + r, row = row0 + rs;
+      if (!col_ok || row >= n_loc) continue;
+      const size_t ti = (size_t)b * N + map.token(p, row);
+      const double ri = rnp[ti];
+      // the three high sums are exact in double (below 2^48); the low four lose at most 2^3 of 2^58 and up
+      const double hi = fma((double)acc[i][6][r], 65536.0, fma((double)acc[i][5][r], 256.0, (double)acc[i][4][r]));
+      const double lo = fma((double)acc[i][3][r], 16777216.0,
+                            fma((double)acc[i][2][r], 65536.0, fma((double)acc[i][1][r], 256.0, (double)acc[i][0][r])));
+      const double dot = fma(hi, 4294967296.0, lo);
+      double cs = dot * ri * rj;
+      if (corrected) {
+        if (!by_element) {
+          const int ki = fx.slot_of[rs], kj = fx.slot_of[64 + cl];
+          if (ki >= 0) cs += fx.cvec[ki][cl];
+          if (kj >= 0) cs += fx.cvec[kj][rs];
+        } else {
+          const LimbFix &fi = fx.sfix[rs], &fj = fx.sfix[64 + cl];
+          if (fi.n | fj.n) {
+            double corr = 0.0;
+            for (int e = 0; e < fi.n; e++) corr = fma(fi.res[e], (double)(float)fix.X[tj * fix.C + fi.ch[e]], corr);
+            for (int e = 0; e < fj.n; e++) {
+              double xi = (double)(float)fix.X[ti * fix.C + fj.ch[e]];
+              for (int u = 0; u < fi.n; u++)
+                if (fi.ch[u] == fj.ch[e]) xi -= fi.res[u];
+              corr = fma(fj.res[e], xi, corr);
             }
+            cs += corr * 1073741824.0 / (fix.nrm[ti] * fix.nrm[tj]);
           }
         }
-        const int32_t v = (int32_t)rint(cs);
-        Sr[(size_t)row * n_loc + col] = v;
-        if (bm != bn) Sr[(size_t)col * n_loc + row] = v;
+      }
+      v4[r] = (int32_t)rint(cs);
+      Sr[(size_t)row * n_loc + col] = v4[r];
+    }
+    // the transposed elements: this lane's four rows are four consecutive words of row `col`
+    if (mirror && col_ok) {
+      const int rb = row0 + 32 * wi + 16 * i + 4 * g;
+      int32_t *mr = Sr + (size_t)col * n_loc + rb;
+      if (rb + 3 < n_loc && (n_loc & 3) == 0) {
+        *reinterpret_cast<i32x4 *>(mr) = v4;
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+          if (rb + r < n_loc) mr[r] = v4[r];
       }
     }
+  }
 }
 
 size_t gram_i8_workspace_bytes(const Shape &s) {
-  // (channels: the limb pass keeps a token's row in registers, up to 3072 of them; work: the kernel
-  // goes in 64 x 64 blocks of S, one workgroup each, 64 channels at a time, and with the limb pass in
-  // front it only beats the fp64 kernel's finer units once there are enough block-chunks to fill the
-  // chip several times over - measured: 3200 of them tie, 7680 win by a sixth, 12800 by a quarter)
+  // (channels: the limb pass keeps a token's row in registers, up to 3072 of them; work: with the limb
+  // pass in front and some 10 us of fixed cost per launch (first loads, norms, double-precision
+  // combination, stores) the kernel only beats the fp64 one once there is enough to do - measured in
+  // 64 x 64 blocks of S times 64-channel chunks: 3200 of them win by a tenth, 7680 by a sixth, 12800 by
+  // a quarter; 640 lose)
   const int nb64 = (s.n_loc + 63) / 64;
   const long long block_chunks = (long long)s.B * s.P * (nb64 * (nb64 + 1) / 2) * ((s.C + 63) / 64);
-  if (s.dtype != TOMA_BF16 || s.C > 3072 || block_chunks < 4096) return 0;
+  if (s.dtype != TOMA_BF16 || s.C > 3072 || block_chunks < 3000) return 0;
   const size_t rows = (size_t)s.B * s.N;
   const size_t words = (size_t)((s.C + 63) / 64) * 64;  // one word (four limbs) per channel of the padded row
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -377,11 +411,11 @@ int launch_gram_i8(const Shape &s, const void *X, int32_t *S, char *ws_part, con
     else return TOMA_ERR_UNSUPPORTED;
 #undef TOMA_LIMBS_CASE
   }
-  const int nb64 = (s.n_loc + 63) / 64, units = nb64 * (nb64 + 1) / 2, regions = s.B * s.P;
+  const int units = gram_units(s.n_loc), regions = s.B * s.P;
   KernelTimer kt(K_GRAM, st);
   const GramFix gfix{static_cast<const bf16_t *>(X), nrm, flag, fixes, s.C};
   hipLaunchKernelGGL(k_gram_i8, dim3(units * regions), dim3(256), 0, st, Xq, rnp, S, map, s.N, s.P, s.n_loc, row_words, nchunks,
-                     nb64, units, gfix);
+                     units, gfix);
   *nrm_out = nrm;
   *flag_out = flag;
   return launch_status();

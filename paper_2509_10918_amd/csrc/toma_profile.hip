@@ -105,6 +105,12 @@ TOMA_API int toma_profile_map_product(const toma_desc *desc, int which, int32_t 
   Workspace w;
   plan_workspace(s, &w);
   const int es = s.dtype == TOMA_BF16 ? 2 : 4;
+  if (which == 2) {  // the write pass of the two-pass weights: sources x destinations
+    if (weights_single_pass(s.Nr, s.Dr, s.C, s.B * s.R, es) || !gemm_async_fits(s.Nr, s.Dr, s.C, es)) return TOMA_ERR_UNSUPPORTED;
+    const GemmPlan pl = plan_gemm_async(s.Nr, s.Dr, s.C, s.B * s.R, es, false, false, false, 3);
+    out3[0] = pl.bm; out3[1] = pl.bn; out3[2] = pl.nsplit;
+    return TOMA_OK;
+  }
   const int M = which == 0 ? s.Dr : s.Nr, K = which == 0 ? s.Nr : s.Dr;
   if ((which != 0 && which != 1) || !gemm_async_fits(M, s.C, K, es)) return TOMA_ERR_UNSUPPORTED;
   const GemmPlan pl = plan_map_product(M, s.C, K, s.B * s.R, es, which == 1, true, w.occ_sb != 0);
