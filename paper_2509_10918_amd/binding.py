@@ -10,7 +10,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtoma.so")
+# (a process started with TOMA_SANITIZE=1 loads the host-sanitizer build instead: CPU argument checks only)
+LIB_PATH = os.path.join(_HERE, "libtoma_san.so" if os.environ.get("TOMA_SANITIZE", "0") == "1" else "libtoma.so")
 
 TOMA_F32, TOMA_BF16 = 0, 1
 TOMA_REUSE_IDX, TOMA_REUSE_A, TOMA_RECOMPUTE_WEIGHTS = 1, 2, 4

@@ -10,11 +10,20 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-parameter", "-Wno-inline-asm"]
 
 
-def build(verbose=False, extra=()):
+LIB_SAN = os.path.join(HERE, "libtoma_san.so")
+# host code only (there is no GPU sanitizer here): each option directly after -Xarch_host
+SAN_FLAGS = ["-g", "-fno-omit-frame-pointer", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined"]
+
+
+def build(verbose=False, extra=(), sanitize=False):
+    """sanitize: AddressSanitizer + UndefinedBehaviorSanitizer on the host side, into libtoma_san.so
+    (loaded instead of libtoma.so by a process started with TOMA_SANITIZE=1; CPU checks only)."""
     objs = []
     procs = []
+    if sanitize:
+        extra = (*extra, *SAN_FLAGS)
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        obj = os.path.join(CSRC, src.replace(".hip", ".san.o" if sanitize else ".o"))
         cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -32,10 +41,12 @@ def build(verbose=False, extra=()):
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
-    return LIB
+    lib = LIB_SAN if sanitize else LIB
+    link = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-shared-libsan"] if sanitize else []
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *link, "-o", lib, *objs], check=True)
+    return lib
 
 
 if __name__ == "__main__":
     import sys
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, sanitize="--sanitize" in sys.argv))
