@@ -148,8 +148,11 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
 // next chunk is fetched into registers while the matrix cores work on the current one, and three
 // workgroups share a CU: units this small keep every CU of the chip busy on an SDXL-sized input (640
 // of them) and hide each other's memory latency, which is what bounded 64 x 64 units.
-constexpr int kGramRow = 256 + 16;  // bytes per token and chunk in LDS: 16 packets plus one of padding (bank spread)
+constexpr int kGramRow = 256;  // bytes per token and chunk in LDS: 16 packets, packet kp of row r at slot
+                               // (kp & 8) | ((kp ^ r) & 7) - the swizzle of the GEMM tiles, free of bank conflicts
+                               // for 16 lanes reading one packet column of 16 rows (padded rows were not)
 constexpr int kGramPanel = (64 + 32) * kGramRow;  // row panel, then column panel
+__device__ __forceinline__ int gram_slot(int row, int kp) { return row * kGramRow + (((kp & 8) | ((kp ^ row) & 7)) << 4); }
 
 // with the fixed-point dot product and the norms: cos * 2^30 = dot_q * rnp_i * rnp_j.  A token whose
 // fixed point dropped part of an element (flag 1) has x = xq + res on the listed channels, so
@@ -190,7 +193,7 @@ __global__ __launch_bounds__(256, 3) void k_gram_i8(const uint32_t *__restrict__
     const int q = tid + 256 * u, row = q >> 4, pk = q & 15;  // rows 0..63: row panel, 64..95: column panel
     const int l = min(row < 64 ? row0 + row : col0 + row - 64, n_loc - 1);
     src[u] = Xq + ((size_t)b * N + map.token(p, l)) * row_words + 4 * pk;
-    dst[u] = row * kGramRow + 16 * pk;
+    dst[u] = gram_slot(row, pk);
   }
   // two register sets: chunk k travels in set k % 2, fetched three steps before its products
   i32x4 stage[2][6];
@@ -223,16 +226,20 @@ __global__ __launch_bounds__(256, 3) void k_gram_i8(const uint32_t *__restrict__
 
   // this lane's operand packets: row 32 wi + 16 t + c of the row panel / 16 wj + c of the column panel,
   // channel group g, limb l
-  const int fa = (32 * wi + c) * kGramRow + 64 * g;
-  const int fb = (64 + 16 * wj + c) * kGramRow + 64 * g;
+  int fa[4], fb[4];  // (rows 16 apart share their swizzle)
+#pragma unroll
+  for (int l = 0; l < 4; l++) {
+    fa[l] = gram_slot(32 * wi + c, 4 * g + l);
+    fb[l] = gram_slot(64 + 16 * wj + c, 4 * g + l);
+  }
   auto products = [&](int k) {
     const char *buf = &smem[(k & 1) * kGramPanel];
     i32x4 a[2][4], bb[4];
 #pragma unroll
     for (int l = 0; l < 4; l++) {
-      bb[l] = *reinterpret_cast<const i32x4 *>(buf + fb + 16 * l);
+      bb[l] = *reinterpret_cast<const i32x4 *>(buf + fb[l]);
 #pragma unroll
-      for (int t = 0; t < 2; t++) a[t][l] = *reinterpret_cast<const i32x4 *>(buf + fa + 16 * t * kGramRow + 16 * l);
+      for (int t = 0; t < 2; t++) a[t][l] = *reinterpret_cast<const i32x4 *>(buf + fa[l] + 16 * t * kGramRow);
     }
 #pragma unroll
     for (int la = 0; la < 4; la++)
