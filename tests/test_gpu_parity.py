@@ -127,22 +127,23 @@ def test_select_with_zero_tokens(oracle, dtype):
     assert np.allclose(dv.gain.cpu().numpy(), gain_ref, rtol=1e-6, atol=1e-6)
 
 
-def test_select_with_elements_far_below_a_tokens_largest(oracle):
+@pytest.mark.parametrize("C,heads", [(1024, 16), (672, 21)])   # (672: the last 64-channel chunk of a row is half padding)
+def test_select_with_elements_far_below_a_tokens_largest(oracle, C, heads):
     """bf16 tokens are compared in fixed point against each token's largest exponent; an element more
     than 22 binary orders below it does not fit: a few such elements per token are added back exactly
     after the fixed-point product, a token with many has its similarities recomputed in double precision.
     Tokens with tiny, subnormal and huge elements next to ordinary ones: the picks and the reported
     values must still be the oracle's, which knows nothing of either path."""
-    w = synth.scaled(W["sdxl1"], name="range", B=2, H=64, W=64, C=1024, tile_h=16, tile_w=16, heads=16, sigma=1.5, index=31)
-    assert w.B * w.P * 10 * (w.C // 64) >= 4096   # enough blocks of S x channel chunks for the fixed-point kernel to run
+    w = synth.scaled(W["sdxl1"], name="range", B=2, H=64, W=64, C=C, tile_h=16, tile_w=16, heads=heads, sigma=1.5, index=31)
+    assert w.B * w.P * 10 * ((w.C + 63) // 64) >= 3000   # enough blocks of S x channel chunks for the fixed-point kernel to run
     inp = synth.make_inputs(w)
     _, _, token_of = oracle.region_map(w.H, w.W, w.tile_h, w.tile_w)
     X = inp["X"].copy()
     X[0, token_of[0][5], 17] = 3e-9          # 29 orders below the token's largest: flagged
-    X[0, token_of[0][5], 999] = -7e-12
+    X[0, token_of[0][5], C - 25] = -7e-12
     X[0, token_of[0][6], 17] = 1e-9          # the same channel dropped from two tokens of one region
     X[0, token_of[1][100], 0] = 1e-40        # a bf16 subnormal
-    X[1, token_of[2][31], 640] = 2.5e4       # a huge element: everything else of the token is far below it
+    X[1, token_of[2][31], C - 32] = 2.5e4       # a huge element: everything else of the token is far below it
     X[1, token_of[2][32], 3] = -1.0e6        # (bits of the ordinary elements drop out: flagged)
     X[1, token_of[3][7]] *= 1e-6             # a token that is small as a whole: not flagged, same direction
     X[0, token_of[9][200]] = 0.0             # a token without direction
