@@ -96,6 +96,8 @@ void plan_workspace(const Shape &s, Workspace *w) {
     w->occ_db = w->occ_sb = 0;
     w->occ_bytes = 0;
   }
+  w->z_in_merge = w->occ_sb != 0 && gemm_async_fits(s.Dr, s.C, s.Nr, (int)es) &&
+                  plan_map_product(s.Dr, s.C, s.Nr, s.B * s.R, (int)es, false, true, true).nsplit == 1;
   w->total = off;
 }
 
@@ -237,7 +239,7 @@ TOMA_API int toma_merge(const toma_desc *desc, const void *X, const int32_t *idx
   uint8_t *occ = static_cast<uint8_t *>(amap);
   rc = launch_weights(s, X, idx, A, Z, occ, static_cast<char *>(ws), w, st);
   if (rc != TOMA_OK) return rc;
-  return launch_merge(s, X, A, Z, occ, Xm, static_cast<char *>(ws), w, st);
+  return launch_merge(s, X, A, Z, true, occ, Xm, static_cast<char *>(ws), w, st);
 }
 
 TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void *A, const float *Z,
@@ -249,7 +251,7 @@ TOMA_API int toma_merge_cached(const toma_desc *desc, const void *X, const void 
   if (misaligned(X, 16) || misaligned(A, 16) || misaligned(Xm, 16) || misaligned(Z, 4)) return TOMA_ERR_ALIGN;
   rc = check_map(w, amap);
   if (rc != TOMA_OK) return rc;
-  return launch_merge(s, X, A, Z, static_cast<const uint8_t *>(amap), Xm, static_cast<char *>(ws), w,
+  return launch_merge(s, X, A, const_cast<float *>(Z), false, static_cast<const uint8_t *>(amap), Xm, static_cast<char *>(ws), w,
                       static_cast<hipStream_t>(stream));
 }
 
@@ -389,7 +391,7 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
       rc = launch_weights(s, X, idx, A, Z, occ, wsb, w, st);
       if (rc != TOMA_OK) return rc;
     }
-    rc = launch_merge(s, X, A, Z, occ, Xm, wsb, w, st);
+    rc = launch_merge(s, X, A, Z, !reuse_a, occ, Xm, wsb, w, st);
   }
   if (rc != TOMA_OK) return rc;
   // inside the layer the attention writes its merged rows already divided by Z (the unmerge's

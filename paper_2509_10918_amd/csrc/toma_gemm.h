@@ -66,6 +66,8 @@ template <typename P> struct PolEmptyTiles<P, std::void_t<decltype(P::EMPTY_TILE
 // but moves as a whole from one K step to the next.
 template <typename P, typename = void> struct PolStepB { static constexpr bool value = false; };
 template <typename P> struct PolStepB<P, std::void_t<decltype(P::B_STEP_OFFSET)>> { static constexpr bool value = P::B_STEP_OFFSET; };
+template <typename P, typename = void> struct PolRowSums { static constexpr bool value = false; };
+template <typename P> struct PolRowSums<P, std::void_t<decltype(P::ROW_SUMS)>> { static constexpr bool value = P::ROW_SUMS; };
 template <typename P, typename = void> struct PolSparseK { static constexpr bool value = false; };
 template <typename P> struct PolSparseK<P, std::void_t<decltype(P::SPARSE_K)>> { static constexpr bool value = P::SPARSE_K; };
 
@@ -82,7 +84,9 @@ template <typename T, int BM, int BN> struct GemmTile {
   static constexpr int b_elems(bool ks) { return ks ? BK * (BN + PADN) : BN * LDK; }
 };
 
-template <int TM, int TN> struct WaveAccT { f32x4 t[TM][TN]; };
+// rs: row sums of the A operand (one tile per 16 rows, every column of it the same), kept only by
+// policies that ask for them (ROW_SUMS)
+template <int TM, int TN> struct WaveAccT { f32x4 t[TM][TN]; f32x4 rs[TM]; };
 
 // K split between workgroups: the raw fp32 accumulators go to part[split][z][M][N].
 template <bool ACC_T, int TM, int TN>
@@ -542,6 +546,18 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
   for (int i = 0; i < TM; i++)
 #pragma unroll
     for (int j = 0; j < TN; j++) acc.t[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  // Row sums of A on the side (a policy's choice per launch): one more product per A fragment, against a
+  // fragment of ones - in the transposed orientation every lane then holds the sum of the row it stores.
+  bool row_sums = false;
+  Frag<T> ones;
+  if constexpr (PolRowSums<Pol>::value) {
+    static_assert(Pol::ACC_T && !Pol::A_KS, "row sums are kept in the transposed orientation of a k-contiguous A");
+    row_sums = pol.row_sums();
+#pragma unroll
+    for (int e = 0; e < 8; e++) ones.v[e] = from_f32<T>(1.0f);
+#pragma unroll
+    for (int i = 0; i < TM; i++) acc.rs[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
   auto products = [&](const Frag<T> (&fa)[TM], const Frag<T> (&fb)[TN]) {
 #pragma unroll
     for (int i = 0; i < TM; i++)
@@ -550,6 +566,12 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_async(const Pol pol, int ti
         if constexpr (Pol::ACC_T) mma16(acc.t[i][j], fb[j], fa[i]);
         else mma16(acc.t[i][j], fa[i], fb[j]);
       }
+    if constexpr (PolRowSums<Pol>::value) {
+      if (row_sums) {
+#pragma unroll
+        for (int i = 0; i < TM; i++) mma16(acc.rs[i], ones, fa[i]);
+      }
+    }
   };
   auto next_stage = [](int st) { return st + 1 == STAGES ? 0 : st + 1; };
   auto prev_stage = [](int st) { return st == 0 ? STAGES - 1 : st - 1; };

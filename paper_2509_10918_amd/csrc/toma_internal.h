@@ -27,6 +27,9 @@ struct Workspace {
   // sources per merge region (0: this shape uses none)
   int occ_db, occ_sb;
   size_t occ_bytes;
+  // fresh weights: Z comes out of the merge product (row sums of its own A fragments) instead of a
+  // reduction of the weights kernel's partial sums; needs K whole in every workgroup of that product
+  bool z_in_merge;
 };
 
 // Occupancy map of the stored merge weights.  With a small temperature almost every source token
@@ -146,7 +149,9 @@ int launch_weight_stats(const Shape &s, const void *X, const int32_t *idx, float
 int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, float *Z, uint8_t *occ, char *ws,
                    const Workspace &w, hipStream_t st);
 int launch_occupancy(const Shape &s, const void *A, uint8_t *occ, const Workspace &w, hipStream_t st);
-int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, const uint8_t *occ, void *Xm,
+// make_z: the weights are fresh and launch_weights left Z to this product (w.z_in_merge): Z is written;
+// otherwise Z is read
+int launch_merge(const Shape &s, const void *X, const void *A, float *Z, bool make_z, const uint8_t *occ, void *Xm,
                  char *ws, const Workspace &w, hipStream_t st);
 // Zs (optional): divide the merged rows of O by max(Z, 1e-20) on the way out (the unmerge input)
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,

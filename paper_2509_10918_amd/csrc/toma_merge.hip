@@ -507,7 +507,7 @@ struct OccMap {
 };
 
 template <typename T> struct MergePol {
-  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true, SPARSE_K = true;
+  static constexpr bool A_KS = false, B_KS = true, SPLIT_K = true, ACC_T = true, SPARSE_K = true, ROW_SUMS = true;
   static constexpr int EPI = 1;
   static constexpr bool EPI_LDS = false;
   OccMap occ;
@@ -520,6 +520,10 @@ template <typename T> struct MergePol {
   const T *A;  // [B*R][Dr][lda]
   int lda;
   const float *Z;
+  // Z made here instead (null: read Z): the row sums of A fall out of the product's own A fragments, so
+  // fresh weights need no reduction kernel of their own.  Only with K whole in every workgroup.
+  float *Zout;
+  __host__ __device__ __forceinline__ bool row_sums() const { return Zout != nullptr; }
   T *Xm;
   float *part;
   __device__ __forceinline__ float *split_buffer() const { return part; }
@@ -551,6 +555,25 @@ template <typename T> struct MergePol {
     const float *Zr = Z + (size_t)x.b * v.D + x.rho * v.Dr;
     T *out = Xm + ((size_t)x.b * v.D + x.rho * v.Dr) * v.C;
     const int Cc = v.C;
+    if (Zout) {
+      // lane holds row m = m_w + 16 i + c (four consecutive columns of it per tile) and that row's sum
+      const int g = lane >> 4, c = lane & 15;
+      float *Zw = Zout + (size_t)x.b * v.D + x.rho * v.Dr;
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        const int m = m_w + 16 * i + c;
+        if (m >= x.M) continue;
+        const float zsum = acc.rs[i][0];
+        if (n_w == 0 && g == 0) Zw[m] = zsum;
+        const float sc = 1.0f / fmaxf(zsum, 1e-20f);
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          const int n = n_w + 16 * j + 4 * g;
+          if (n < x.N) store4<T>(out + (size_t)m * Cc + n, acc.t[i][j] * sc);
+        }
+      }
+      return;
+    }
     store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
                   [=](int m) { return out + (size_t)m * Cc; }, [](int n) { return n; },
                   [=](int m) { return 1.0f / fmaxf(Zr[m], 1e-20f); });
@@ -735,7 +758,7 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
         default: return TOMA_ERR_UNSUPPORTED;
       }
     }
-    {
+    if (!w.z_in_merge) {  // (else the merge product that follows makes Z from its own A fragments)
       KernelTimer kt(K_ZSUM, st);
       hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, zpart, Z, zr, w.z_parts, s.Nr / 32);
     }
@@ -758,8 +781,10 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
   // (pass 1 wrote one statistic per wave slice of its tiles: slices of bn / wgn destinations)
   p2.seen = stats; p2.seen_parts = w.stat_parts; p2.slice = gs.bn / gs.wgn;
   const GemmShape gw = launch_gemm<T>(K_WWRITE, p2, s.Nr, s.Dr, s.C, batch, st);
-  { KernelTimer kt(K_ZSUM, st);
-    hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m); }
+  if (!w.z_in_merge) {
+    KernelTimer kt(K_ZSUM, st);
+    hipLaunchKernelGGL(k_zsum, dim3((zr + 15) / 16), dim3(256), 0, st, p2.zpart, Z, zr, w.z_parts, gw.wgm * gw.tiles_m);
+  }
   return launch_status();
 }
 
@@ -770,21 +795,22 @@ int launch_weights(const Shape &s, const void *X, const int32_t *idx, void *A, f
 }
 
 template <typename T>
-static int merge_typed(const Shape &s, const void *X, const void *A, const float *Z, const uint8_t *occ, void *Xm,
+static int merge_typed(const Shape &s, const void *X, const void *A, float *Z, bool make_z, const uint8_t *occ, void *Xm,
                        char *ws, const Workspace &w, hipStream_t st) {
   MergePol<T> p{};
   p.v = make_view<T>(s, X);
   p.A = static_cast<const T *>(A); p.lda = s.Nr; p.Z = Z; p.Xm = static_cast<T *>(Xm);
+  p.Zout = make_z && w.z_in_merge ? Z : nullptr;
   p.occ = OccMap{w.occ_sb ? occ : nullptr, w.occ_db, w.occ_sb};
   p.part = reinterpret_cast<float *>(ws + w.split);
   launch_gemm<T>(K_MERGE, p, s.Dr, s.C, s.Nr, s.B * s.R, st);
   return launch_status();
 }
 
-int launch_merge(const Shape &s, const void *X, const void *A, const float *Z, const uint8_t *occ, void *Xm,
+int launch_merge(const Shape &s, const void *X, const void *A, float *Z, bool make_z, const uint8_t *occ, void *Xm,
                  char *ws, const Workspace &w, hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? merge_typed<bf16_t>(s, X, A, Z, occ, Xm, ws, w, st)
-                              : merge_typed<float>(s, X, A, Z, occ, Xm, ws, w, st);
+  return s.dtype == TOMA_BF16 ? merge_typed<bf16_t>(s, X, A, Z, make_z, occ, Xm, ws, w, st)
+                              : merge_typed<float>(s, X, A, Z, make_z, occ, Xm, ws, w, st);
 }
 
 int launch_scale_rows(const Shape &s, const void *O, const float *Z, int o_rows, void *Os, hipStream_t st) {
