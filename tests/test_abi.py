@@ -147,3 +147,21 @@ def test_column_order_helper_of_the_gpu_tests(H, W, th, tw, R):
     assert got.shape == (R, H * W // R)
     assert got.reshape(-1).tolist() == want
     assert sorted(want) == list(range(H * W))        # every token exactly once
+
+
+def test_profile_map_product_is_host_arithmetic():
+    """The tile a product will run with comes from the descriptor alone (no GPU): merge and unmerge of
+    the SDXL stage-1 workload take the tiled path; its weights are made in one pass, so there is no
+    write-pass tile to report, while the Flux block's weights take two passes and have one."""
+    from paper_2509_10918_amd import synth
+    w = synth.WORKLOADS["sdxl1"]
+    d = tb.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, 1, w.tau, w.dtype)
+    for which in (0, 1):
+        bm, bn, split = tb.toma_profile_map_product(d, which)
+        assert bm in (64, 128, 256) and bn in (64, 128, 256) and split >= 1
+    assert tb.toma_profile_map_product(d, 2) is None
+    assert tb.toma_profile_map_product(d, 3) is None
+    f = synth.WORKLOADS["flux"]
+    df = tb.make_desc(f.B, f.H, f.W, f.C, f.tile_h, f.tile_w, f.d_loc, 1, f.tau, f.dtype)
+    bm, bn, split = tb.toma_profile_map_product(df, 2)
+    assert bm in (64, 128, 256) and bn in (64, 128, 256) and split == 1
