@@ -267,7 +267,7 @@ TOMA_API int toma_attend(const toma_desc *desc, const toma_attn_desc *attn, cons
   if (misaligned(Xm, 16) || misaligned(Wq, 16) || misaligned(Wk, 16) || misaligned(Wv, 16) || misaligned(O, 16) ||
       (X_extra_opt && misaligned(X_extra_opt, 16)) || (Wo_opt && misaligned(Wo_opt, 16)))
     return TOMA_ERR_ALIGN;
-  return launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, nullptr, static_cast<char *>(ws), w,
+  return launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, nullptr, nullptr, static_cast<char *>(ws), w,
                        static_cast<hipStream_t>(stream));
 }
 
@@ -395,13 +395,11 @@ TOMA_API int toma_layer(const toma_desc *desc, const toma_attn_desc *attn, uint3
   }
   if (rc != TOMA_OK) return rc;
   // inside the layer the attention writes its merged rows already divided by Z (the unmerge's
-  // input), so no separate scaling pass runs; the extra-token rows stay as they are
-  rc = launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, Z, wsb, w, st);
+  // input), so no separate scaling pass runs; the extra-token rows go straight to the caller's Y_extra
+  rc = launch_attend(s, Xm, X_extra_opt, Wq, Wk, Wv, Wo_opt, O, Z, s.T > 0 ? Y_extra_opt : nullptr, wsb, w, st);
   if (rc != TOMA_OK) return rc;
   rc = recompute ? launch_unmerge_fused(s, X, idx, wsb + w.fcache, O, s.L, Y, w, st)
                  : launch_unmerge(s, A, Z, occ, O, s.L, true, Y, wsb, w, st);
-  if (rc != TOMA_OK) return rc;
-  if (s.T > 0) rc = launch_copy_extra(s, O, Y_extra_opt, st);
   return rc;
 }
 

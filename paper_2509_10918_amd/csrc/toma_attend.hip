@@ -67,6 +67,7 @@ template <typename T> struct ProjPol {
   const T *In, *Wt;
   T *Out;
   const float *Zs;  // when set: rows l < D of every sample are divided by max(Z, 1e-20)
+  T *Oe;            // when set: rows l >= D (the extra tokens) go to Oe[b][l - D] instead of Out[b][l]
   int rows, C, L, D;
   __device__ __forceinline__ GemmCtx setup(int) const { return GemmCtx{rows, C, C, 0, 0, 0}; }
   __device__ __forceinline__ bool a_linear(int) const { return true; }
@@ -76,10 +77,14 @@ template <typename T> struct ProjPol {
   template <int TM, int TN>
   __device__ __forceinline__ void epilogue(const GemmCtx &x, const WaveAccT<TM, TN> &acc, int m_w, int n_w,
                                            int lane, void *wave_lds) const {
-    T *o = Out;
+    T *o = Out, *oe = Oe;
     const int C_ = C, L_ = L, D_ = D;
     const float *zs = Zs;
-    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N, [=](int m) { return o + (size_t)m * C_; },
+    store_rows<T, TM, TN>(acc, m_w, n_w, lane, x.M, x.N,
+                          [=](int m) {
+                            const int b = m / L_, l = m - b * L_;
+                            return (oe && l >= D_) ? oe + ((size_t)b * (L_ - D_) + (l - D_)) * C_ : o + (size_t)m * C_;
+                          },
                           [](int n) { return n; },
                           [=](int m) {
                             int b = m / L_, l = m % L_;
@@ -135,7 +140,7 @@ __device__ __forceinline__ void pack_probs(Frag<float> &f, const f32x4 &lo, cons
 template <typename T, int DH>
 __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *__restrict__ Kx,
                                              const T *__restrict__ V, T *__restrict__ O, int Lq, int L, int H,
-                                             float scale_log2, const float *__restrict__ Zs, int D) {
+                                             float scale_log2, const float *__restrict__ Zs, int D, T *__restrict__ Oe) {
   constexpr int EPP = 16 / (int)sizeof(T);
   constexpr int LD = DH + EPP;        // LDS row stride (elements) of the K and V tiles [64][DH]
   constexpr int KK = DH / 32;         // fragments along head_dim
@@ -286,7 +291,8 @@ __global__ __launch_bounds__(256) void k_attn(const T *__restrict__ Q, const T *
     int q = q_w + 16 * qt + c;
     if (q >= Lq) continue;
     if (Zs && q < D) inv /= fmaxf(Zs[(size_t)b * D + q], 1e-20f);  // unmerge input: O / Z
-    T *dst = O + ((size_t)b * Lq + q) * Cw + h * DH + 4 * g;
+    // (extra-token rows straight to their own output when the caller has one)
+    T *dst = (Oe && q >= D ? Oe + ((size_t)b * (Lq - D) + (q - D)) * Cw : O + ((size_t)b * Lq + q) * Cw) + h * DH + 4 * g;
 #pragma unroll
     for (int dt = 0; dt < DT; dt++) {
       alignas(16) T o[4];
@@ -347,7 +353,7 @@ __device__ __forceinline__ float rows4_sum_f32(float v) {
 template <typename T, int DH, int QT>
 __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 256 ? 3 : 4) : (DH * sizeof(T) >= 256 ? 1 : 2)) void k_attn_async(
     const T *__restrict__ Q, const T *__restrict__ Kx, const T *__restrict__ V, T *__restrict__ O, int Lq, int L, int H,
-    float scale_log2, const float *__restrict__ Zs, int D) {
+    float scale_log2, const float *__restrict__ Zs, int D, T *__restrict__ Oe) {
   constexpr int ES = (int)sizeof(T), EPP = 16 / ES;
   constexpr int PPR = DH / EPP;       // 16-byte packets per K / V row
   constexpr int KK = DH / 32, DT = DH / 16, STAGES = 4;  // QT: query tiles (of 16) per wave
@@ -569,7 +575,8 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
     int q = q_w + 16 * qt + c;
     if (q >= Lq) continue;
     if (Zs && q < D) inv /= fmaxf(Zs[(size_t)b * D + q], 1e-20f);  // unmerge input: O / Z
-    T *dst = O + ((size_t)b * Lq + q) * Cw + h * DH + 4 * g;
+    // (extra-token rows straight to their own output when the caller has one)
+    T *dst = (Oe && q >= D ? Oe + ((size_t)b * (Lq - D) + (q - D)) * Cw : O + ((size_t)b * Lq + q) * Cw) + h * DH + 4 * g;
 #pragma unroll
     for (int dt = 0; dt < DT; dt++) {
       alignas(16) T o[4];
@@ -622,7 +629,7 @@ static int attn_waves(int L, int heads_x_batch, int ring_bytes, int waves_per_cu
 // nw: waves per workgroup, 0 = chosen by attn_waves
 template <typename T, int DH>
 static void launch_attn(const Shape &s, int Lq, int Lk, const T *Q, const T *K, const T *V, T *O, const float *Zs,
-                        hipStream_t st, int nw = 0) {
+                        T *Oe, hipStream_t st, int nw = 0) {
   float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   KernelTimer kt(K_ATTN, st);
   // load-to-LDS pipeline when a row is at least eight packets and the ring of four tiles fits the LDS
@@ -633,22 +640,23 @@ static void launch_attn(const Shape &s, int Lq, int Lk, const T *Q, const T *K, 
       constexpr bool kWide = DH * sizeof(T) >= 256;  // three waves per SIMD fit the registers, else four
       if (nw < (kWide ? 8 : 4) || nw > 12) nw = attn_waves(Lq, s.heads * s.B, kRing, kWide ? 12 : 16, kWide ? 8 : 4, kWide ? 2.3f : 2.0f);
       dim3 grid((Lq + 16 * nw - 1) / (16 * nw) * s.heads * s.B);
-      hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(64 * nw), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 1>), grid, dim3(64 * nw), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D, Oe);
     } else {
       dim3 grid((Lq + 127) / 128 * s.heads * s.B);
-      hipLaunchKernelGGL((k_attn_async<T, DH, 2>), grid, dim3(256), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D);
+      hipLaunchKernelGGL((k_attn_async<T, DH, 2>), grid, dim3(256), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D, Oe);
     }
     return;
   }
   dim3 grid((Lq + 127) / 128, s.heads, s.B);
-  hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D);
+  hipLaunchKernelGGL((k_attn<T, DH>), grid, dim3(256), 0, st, Q, K, V, O, Lq, Lk, s.heads, scale_log2, Zs, s.D, Oe);
 }
 
 template <typename T>
 static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
-                        const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
-                        hipStream_t st) {
+                        const void *Wv, const void *Wo, void *O, const float *Zs, void *O_extra, char *ws,
+                        const Workspace &w, hipStream_t st) {
   T *Q = reinterpret_cast<T *>(ws + w.q), *K = reinterpret_cast<T *>(ws + w.k), *V = reinterpret_cast<T *>(ws + w.v);
+  T *Oe = static_cast<T *>(O_extra);
   QkvPol<T> p{};
   p.Xm = static_cast<const T *>(Xm); p.Xe = static_cast<const T *>(Xe);
   p.W[0] = static_cast<const T *>(Wq); p.W[1] = static_cast<const T *>(Wk); p.W[2] = static_cast<const T *>(Wv);
@@ -659,25 +667,25 @@ static int attend_typed(const Shape &s, const void *Xm, const void *Xe, const vo
   launch_gemm<T>(K_QKV, p, s.B * s.L, s.C, s.C, 3, st);
   T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
   switch (s.head_dim) {
-    case 32: launch_attn<T, 32>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
-    case 64: launch_attn<T, 64>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
-    case 128: launch_attn<T, 128>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, st); break;
+    case 32: launch_attn<T, 32>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, Wo ? nullptr : Oe, st); break;
+    case 64: launch_attn<T, 64>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, Wo ? nullptr : Oe, st); break;
+    case 128: launch_attn<T, 128>(s, s.L, s.L, Q, K, V, Oh, Wo ? nullptr : Zs, Wo ? nullptr : Oe, st); break;
     default: return TOMA_ERR_UNSUPPORTED;
   }
   if (Wo) {
     ProjPol<T> pp{};
     pp.In = Oh; pp.Wt = static_cast<const T *>(Wo); pp.Out = static_cast<T *>(O);
-    pp.rows = s.B * s.L; pp.C = s.C; pp.L = s.L; pp.D = s.D; pp.Zs = Zs;
+    pp.rows = s.B * s.L; pp.C = s.C; pp.L = s.L; pp.D = s.D; pp.Zs = Zs; pp.Oe = Oe;
     launch_gemm<T>(K_PROJ, pp, s.B * s.L, s.C, s.C, 1, st);
   }
   return launch_status();
 }
 
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
-                  const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
-                  hipStream_t st) {
-  return s.dtype == TOMA_BF16 ? attend_typed<bf16_t>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st)
-                              : attend_typed<float>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, ws, w, st);
+                  const void *Wv, const void *Wo, void *O, const float *Zs, void *O_extra, char *ws,
+                  const Workspace &w, hipStream_t st) {
+  return s.dtype == TOMA_BF16 ? attend_typed<bf16_t>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, O_extra, ws, w, st)
+                              : attend_typed<float>(s, Xm, Xe, Wq, Wk, Wv, Wo, O, Zs, O_extra, ws, w, st);
 }
 
 // Cross-attention: queries from the L rows of U, keys / values from t_ctx context rows of width c_ctx.
@@ -702,15 +710,15 @@ static int cross_typed(const Shape &s, const void *U, const void *Ctx, int t_ctx
   launch_gemm<T>(K_QKV, pk, s.B * t_ctx, s.C, c_ctx, 2, st);
   T *Oh = Wo ? reinterpret_cast<T *>(ws + w.oh) : static_cast<T *>(O);
   switch (s.head_dim) {
-    case 32: launch_attn<T, 32>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, st); break;
-    case 64: launch_attn<T, 64>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, st); break;
-    case 128: launch_attn<T, 128>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, st); break;
+    case 32: launch_attn<T, 32>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, nullptr, st); break;
+    case 64: launch_attn<T, 64>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, nullptr, st); break;
+    case 128: launch_attn<T, 128>(s, s.L, t_ctx, Q, K, V, Oh, nullptr, nullptr, st); break;
     default: return TOMA_ERR_UNSUPPORTED;
   }
   if (Wo) {
     ProjPol<T> pp{};
     pp.In = Oh; pp.Wt = static_cast<const T *>(Wo); pp.Out = static_cast<T *>(O);
-    pp.rows = s.B * s.L; pp.C = s.C; pp.L = s.L; pp.D = s.D; pp.Zs = nullptr;
+    pp.rows = s.B * s.L; pp.C = s.C; pp.L = s.L; pp.D = s.D; pp.Zs = nullptr; pp.Oe = nullptr;
     launch_gemm<T>(K_PROJ, pp, s.B * s.L, s.C, s.C, 1, st);
   }
   return launch_status();

@@ -154,9 +154,10 @@ int launch_occupancy(const Shape &s, const void *A, uint8_t *occ, const Workspac
 int launch_merge(const Shape &s, const void *X, const void *A, float *Z, bool make_z, const uint8_t *occ, void *Xm,
                  char *ws, const Workspace &w, hipStream_t st);
 // Zs (optional): divide the merged rows of O by max(Z, 1e-20) on the way out (the unmerge input)
+// O_extra (optional): the extra-token rows go to O_extra [B, T, C] instead of rows D.. of O
 int launch_attend(const Shape &s, const void *Xm, const void *Xe, const void *Wq, const void *Wk,
-                  const void *Wv, const void *Wo, void *O, const float *Zs, char *ws, const Workspace &w,
-                  hipStream_t st);
+                  const void *Wv, const void *Wo, void *O, const float *Zs, void *O_extra, char *ws,
+                  const Workspace &w, hipStream_t st);
 // U: [B, L, C] query tokens; Ctx: [B, t_ctx, c_ctx] context tokens; Wk, Wv: [c_ctx, C]
 int launch_cross_attend(const Shape &s, const void *U, const void *Ctx, int t_ctx, int c_ctx, const void *Wq,
                         const void *Wk, const void *Wv, const void *Wo, void *O, char *ws, const Workspace &w,
