@@ -411,6 +411,11 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
   // LDS byte addresses of this wave's first chunk in stage 0 (scalar registers)
   const uint32_t ks_addr = lds_addr_of(&Ks[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(wl) * (NI * 1024);
   const uint32_t vs_addr = lds_addr_of(&Vs[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(wl) * (NI * 1024);
+  // (the tile's base address is wave-uniform and the lanes' offsets inside a tile never change: the
+  // loads take the base from scalar registers and cost no vector instruction for their addresses)
+  uint32_t k_offb[NI], v_offb[NI];
+#pragma unroll
+  for (int t = 0; t < NI; t++) { k_offb[t] = (uint32_t)k_off[t] * ES; v_offb[t] = (uint32_t)v_off[t] * ES; }
   auto issue = [&](int st, int it) {
     if (!loader) return;  // (a wave without loads passes every vmcnt wait below at once)
     const ptrdiff_t adv = (ptrdiff_t)it * 64 * DH;
@@ -418,8 +423,8 @@ __global__ __launch_bounds__(QT == 1 ? 768 : 256, QT == 1 ? (DH * sizeof(T) >= 2
       const T *kb = Kh + adv, *vb = Vh + adv;
 #pragma unroll
       for (int t = 0; t < NI; t++) {
-        load_to_lds16_at(kb + k_off[t], ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
-        load_to_lds16_at(vb + v_off[t], vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_from(kb, k_offb[t], ks_addr + (uint32_t)(st * TILE * ES + t * 1024));
+        load_to_lds16_from(vb, v_offb[t], vs_addr + (uint32_t)(st * TILE * ES + t * 1024));
       }
     } else {  // rows past the end repeat row L - 1 and are masked below
 #pragma unroll

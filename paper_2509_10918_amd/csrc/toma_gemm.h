@@ -336,6 +336,13 @@ __device__ __forceinline__ void load_to_lds16_at(const T *gptr, uint32_t lds_add
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr)
                : "memory", "m0");
 }
+// The same from a wave-uniform base (scalar registers) plus a per-lane byte offset (32 bits, unsigned):
+// a pipeline whose lanes keep fixed offsets inside a tile then spends no vector instruction on addresses.
+template <typename T>
+__device__ __forceinline__ void load_to_lds16_from(const T *uniform_base, uint32_t lane_bytes, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_bytes), "s"(uniform_base)
+               : "memory", "m0");
+}
 // wait until at most n of this wave's vector-memory loads are outstanding (n < 64)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | (((N >> 4) & 3) << 14));
