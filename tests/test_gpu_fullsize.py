@@ -24,6 +24,7 @@ def _report(name, got, ref, tol):
     ex = tg.elem_excess(got, ref, tol)
     print(f"  {name}: max|err|/max|ref| = {err:.3e} (tol {tol:g}); element-wise excess {ex:.3f}", flush=True)
     assert np.all(np.isfinite(got)) and err <= tol, name
+    assert ex <= tg.MAX_ELEM_EXCESS, name
 
 
 @pytest.mark.timeout(900)

@@ -166,6 +166,7 @@ def _check_stage(name, got, ref, tol):
     ex = tg.elem_excess(got, ref, tol)
     print(f"  {name}: max|err|/max|ref| = {err:.3e} (tol {tol:g}); element-wise excess {ex:.3f}", flush=True)
     assert np.all(np.isfinite(got)) and err <= tol, name
+    assert ex <= tg.MAX_ELEM_EXCESS, name
 
 
 @pytest.mark.parametrize("tile_local", [False, True])
