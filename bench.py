@@ -128,6 +128,42 @@ def roofline_entry(name, work, avg_us, traffic=None):
     return out
 
 
+def greedy_rounds(w, steps):
+    """Selection (toma_select) of the workload's tokens with 1/16 ... 3/4 of each region kept: the greedy
+    kernel runs one round per pick, so its duration over the number of picks gives the cost of a round and
+    of what does not depend on the rounds (reading S, the first keys, writing the picks)."""
+    import torch
+    from paper_2509_10918_amd import binding as tb
+    from paper_2509_10918_amd import synth
+    X = torch.from_numpy(np.ascontiguousarray(synth.make_inputs(w)["X"], dtype=np.float32)).to("cuda")
+    X = X.to(torch.bfloat16 if w.dtype == "bf16" else torch.float32).contiguous()
+    rows = []
+    for d_loc in sorted({max(w.n_loc // 16, 1), w.n_loc // 8, w.n_loc // 4, 3 * w.n_loc // 8, w.n_loc // 2, 3 * w.n_loc // 4}):
+        desc = tb.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, d_loc, 1, w.tau, w.dtype)
+        ws = tb.alloc_workspace(desc)
+        idx = torch.empty((w.B, w.P, d_loc), dtype=torch.int32, device="cuda")
+        for _ in range(5):
+            tb.toma_select(desc, X, idx, None, None, ws)
+        tb.toma_profile_enable(True)
+        tb.toma_profile_read("greedy")
+        for _ in range(steps):
+            tb.toma_select(desc, X, idx, None, None, ws)
+        torch.cuda.synchronize()
+        n, total = tb.toma_profile_read("greedy")
+        tb.toma_profile_enable(False)
+        rows.append((d_loc, total * 1e3 / n))
+    d = np.array([r[0] for r in rows], float)
+    t = np.array([r[1] for r in rows], float)
+    slope, fixed = np.polyfit(d, t, 1)
+    print(f"# greedy kernel of {w.name}: {w.B * w.P} regions of {w.n_loc} tokens, one workgroup each; average us per launch")
+    print(f"# command: python bench.py --workload {w.name} --greedy-rounds --steps {steps}")
+    print(f"{'picks per region':>18}{'us':>10}{'us per pick':>14}")
+    for dl, us in rows:
+        print(f"{dl:>18}{us:>10.2f}{us / dl:>14.3f}")
+    print(f"linear fit: {fixed:.1f} us + {slope:.3f} us per round ({slope * 2400:.0f} clocks at 2.4 GHz); the first rounds cost "
+          f"more than the later ones (every column changes at the first pick, a handful later)")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +177,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: three uncached layer calls and one "
                          "256 MiB device copy (the calibration kernel), nothing else")
+    ap.add_argument("--greedy-rounds", action="store_true",
+                    help="time the selection of this workload at several numbers of picks per region (the greedy "
+                         "kernel's rounds) and print what a round costs; nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -152,6 +191,9 @@ def main():
     from paper_2509_10918_amd import synth
 
     w = synth.WORKLOADS[args.workload]
+    if args.greedy_rounds:
+        greedy_rounds(w, args.steps)
+        return
     R = 1 if args.merge_regions == "global" else w.P
     inp = synth.make_inputs(w)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
