@@ -87,32 +87,37 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
   for (int it = 0; it < ITER; it++) {
     const int g = lane + 64 * it;
     if (g >= groups_pad) continue;
-    uint32_t lq[16];
+    // q = trunc(x * 2^(156 - emax)): the conversion instructions do the shifting; an element that the
+    // fixed point cannot hold exactly shows as a fractional part (rare: looked at once per group)
+    uint32_t lq[16], inexact = 0u;
 #pragma unroll
     for (int i = 0; i < 16; i++) {
       const uint32_t word = pk[it][i >> 3][(i >> 1) & 3];
-      const uint32_t bits = (i & 1) ? (word >> 16) : (word & 0xffffu);
-      const int e = (int)((bits >> 7) & 0xffu);
-      const uint32_t sig = e ? (0x80u | (bits & 0x7fu)) : (bits & 0x7fu);
-      const int sh = kLimbShift - (emax - max(e, 1));
-      uint32_t mag;
-      if (sh >= 0) {
-        mag = sig << sh;
-      } else {
-        const int down = min(-sh, 31);
-        mag = sig >> down;
-        if ((sig & ((1u << down) - 1u)) != 0u) {
-          // what the fixed point drops: value - (+-mag) * 2^(emax - 156), exact in double
-          const double val = (double)__builtin_bit_cast(float, bits << 16);
-          const double kept = ldexp((double)mag, emax - 156);
-          const int at = atomicAdd(&fixn[w], 1);
-          if (at < kFixMax) { fx->ch[at] = 16 * g + i; fx->res[at] = val - ((bits & 0x8000u) ? -kept : kept); }
-        }
-      }
-      const int32_t q = (bits & 0x8000u) ? -(int32_t)mag : (int32_t)mag;
+      const float x = __builtin_bit_cast(float, (i & 1) ? (word & 0xffff0000u) : (word << 16));
+      const float qf = __builtin_amdgcn_ldexpf(x, 156 - emax);
+      inexact |= __builtin_bit_cast(uint32_t, __builtin_amdgcn_fractf(qf));
+      const int32_t q = (int32_t)qf;
       // signed bytes: adding 128 to each of the three low bytes (carries and all) and flipping
       // their top bits leaves l0 + 256 l1 + 256^2 l2 + 256^3 l3 == q with every l in [-128, 127]
       lq[i] = ((uint32_t)q + 0x00808080u) ^ 0x00808080u;
+    }
+    if (inexact << 1) {  // (a fraction of -0 does not count)
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        const uint32_t word = pk[it][i >> 3][(i >> 1) & 3];
+        const uint32_t bits = (i & 1) ? (word >> 16) : (word & 0xffffu);
+        const int e = (int)((bits >> 7) & 0xffu);
+        const uint32_t sig = e ? (0x80u | (bits & 0x7fu)) : (bits & 0x7fu);
+        const int sh = kLimbShift - (emax - max(e, 1));
+        if (sh >= 0) continue;
+        const int down = min(-sh, 31);
+        if ((sig & ((1u << down) - 1u)) == 0u) continue;
+        // what the fixed point drops: value - (+-mag) * 2^(emax - 156), exact in double
+        const double val = (double)__builtin_bit_cast(float, bits << 16);
+        const double kept = ldexp((double)(sig >> down), emax - 156);
+        const int at = atomicAdd(&fixn[w], 1);
+        if (at < kFixMax) { fx->ch[at] = 16 * g + i; fx->res[at] = val - ((bits & 0x8000u) ? -kept : kept); }
+      }
     }
     // byte k of the sixteen words -> limb plane k (four words)
 #pragma unroll
