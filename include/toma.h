@@ -27,7 +27,8 @@
  *     weights that are entirely zero (with a small tau most of A is): a zero weight then contributes
  *     nothing even where 0 * inf or 0 * NaN would have contributed a NaN.  For finite inputs the
  *     results are those of the full products.
- *   - Limits: C % 32 == 0; N_loc % 16 == 0 and N_loc <= 256; 1 <= d_loc <= N_loc;
+ *   - Limits: C % 32 == 0; N_loc % 16 == 0 and N_loc <= 2048 (regions of more than 256 tokens take a
+ *     slower selection kernel that keeps the similarities in memory); 1 <= d_loc <= N_loc;
  *     merge_regions is 1 or P; head_dim is 32, 64 or 128.
  *     Anything else returns TOMA_ERR_UNSUPPORTED or TOMA_ERR_SHAPE.
  */

@@ -26,7 +26,7 @@ int make_shape(const toma_desc *d, const toma_attn_desc *a, Shape *s) {
   if (d->d_loc > s->n_loc) return TOMA_ERR_SHAPE;
   if (d->merge_regions != 1 && d->merge_regions != s->P) return TOMA_ERR_SHAPE;
   if (d->C % 32) return TOMA_ERR_UNSUPPORTED;
-  if (s->n_loc % 16 || s->n_loc > 256) return TOMA_ERR_UNSUPPORTED;
+  if (s->n_loc % 16 || s->n_loc > 2048) return TOMA_ERR_UNSUPPORTED;  // (the selection kernels' largest region)
   // kernels index inside one sample with 32-bit element offsets and launch one thread per element
   // of a tensor in places: a sample's tokens must stay below 2^31 elements, the batch below 2^38
   if ((long long)s->N * d->C >= (1ll << 31) || (long long)d->B * s->N * d->C >= (1ll << 38)) return TOMA_ERR_UNSUPPORTED;

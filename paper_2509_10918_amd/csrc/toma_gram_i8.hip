@@ -390,7 +390,8 @@ size_t gram_i8_workspace_bytes(const Shape &s) {
   // a quarter; 640 lose)
   const int nb64 = (s.n_loc + 63) / 64;
   const long long block_chunks = (long long)s.B * s.P * (nb64 * (nb64 + 1) / 2) * ((s.C + 63) / 64);
-  if (s.dtype != TOMA_BF16 || s.C > 3072 || block_chunks < 3000) return 0;
+  // (regions of more than 256 tokens take the selection kernel that has no fallback for flagged tokens)
+  if (s.dtype != TOMA_BF16 || s.C > 3072 || block_chunks < 3000 || s.n_loc > 256) return 0;
   const size_t rows = (size_t)s.B * s.N;
   const size_t words = (size_t)((s.C + 63) / 64) * 64;  // one word (four limbs) per channel of the padded row
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };

@@ -430,6 +430,137 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same greedy selection for regions too large for one CU's registers (more than 256 tokens, up to
+// kBigRegion: the few-regions end of the paper's region-count ablation, e.g. four regions of 1024
+// tokens).  One workgroup of 1024 threads per (sample, region); S stays in global memory (it is read
+// through L2), thread i owns row i and column i (and i + 1024): its row's value as a 64-bit integer and
+// its column's coverage live in registers.  A round: (1) argmax of the keys - value + 1 in the high
+// bits, 4095 - row in the low twelve, so the largest key is the largest value at the lowest row - by
+// a wave reduction, an exchange through LDS and a second wave reduction that every wave does for
+// itself; (2) every thread compares row t (one coalesced read) with its columns' coverage and appends
+// the changed columns (column, old, new coverage) to a list in LDS; (3) every thread walks the list and
+// lowers its rows' values by med(S_ij, m_j, m_j') - m_j, reading S_ji = S_ij along row j (coalesced).
+// Integer arithmetic throughout: the values equal the full rescan of Alg. 2 whatever the order of the
+// list.  Three barriers per round.
+constexpr int kBigRegion = 2048, kBigThreads = 1024, kBigRows = kBigRegion / kBigThreads;
+
+__device__ __forceinline__ uint64_t wave_max_key(uint64_t k) { return wave_max_u64(k); }
+
+template <bool GAP>
+__global__ __launch_bounds__(kBigThreads) void k_greedy_big(const int32_t *__restrict__ S, int32_t *__restrict__ idx,
+                                                           float *__restrict__ gain_out, float *__restrict__ gap_out,
+                                                           RegionMap map, int P, int n, int d_loc) {
+  constexpr int32_t kFloor = -(1 << 30);  // similarity -1: the coverage before the first pick
+  constexpr int NW = kBigThreads / 64;
+  __shared__ uint64_t red[NW], red2[GAP ? NW : 1];
+  __shared__ int list_n;
+  __shared__ int32_t list_j[kBigRegion], list_a[kBigRegion], list_b[kBigRegion];
+  const int bp = blockIdx.x, p = bp % P, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int32_t *Sr = S + (size_t)bp * n * n;
+
+  int row[kBigRows];
+  bool live[kBigRows], picked[kBigRows];
+  int32_t m[kBigRows];
+  uint64_t val[kBigRows];
+#pragma unroll
+  for (int u = 0; u < kBigRows; u++) {
+    row[u] = tid + kBigThreads * u;
+    live[u] = row[u] < n;
+    picked[u] = false;
+    m[u] = kFloor;
+    val[u] = 0;
+  }
+  if (tid == 0) list_n = 0;
+  // values under the starting coverage: sum_j (S_ij + 1), summed down the columns (S is symmetric)
+  for (int j = 0; j < n; j++) {
+#pragma unroll
+    for (int u = 0; u < kBigRows; u++)
+      if (live[u]) val[u] += (uint32_t)(Sr[(size_t)j * n + row[u]] - kFloor);
+  }
+
+  for (int step = 0; step < d_loc; step++) {
+    // ---- (1) argmax ----
+    uint64_t best = 0, key[kBigRows];
+#pragma unroll
+    for (int u = 0; u < kBigRows; u++) {
+      key[u] = live[u] && !picked[u] ? ((val[u] + 1) << 12) | (uint64_t)(4095 - row[u]) : 0ull;
+      best = key[u] > best ? key[u] : best;
+    }
+    const uint64_t wbest = wave_max_key(best);
+    if (lane == 0) red[w] = wbest;
+    __syncthreads();
+    const uint64_t top = wave_max_key(lane < NW ? red[lane] : 0ull);
+    const int t = 4095 - (int)(top & 4095);
+    if constexpr (GAP) {
+      uint64_t sb = 0;
+#pragma unroll
+      for (int u = 0; u < kBigRows; u++) {
+        const uint64_t k = row[u] == t ? 0ull : key[u];
+        sb = k > sb ? k : sb;
+      }
+      const uint64_t wsb = wave_max_key(sb);
+      if (lane == 0) red2[w] = wsb;
+    }
+    // ---- (2) row t against the coverage of the own columns ----
+#pragma unroll
+    for (int u = 0; u < kBigRows; u++) {
+      if (!live[u]) continue;
+      const int32_t x = Sr[(size_t)t * n + row[u]];
+      if (x > m[u]) {
+        const int at = atomicAdd(&list_n, 1);
+        list_j[at] = row[u];
+        list_a[at] = m[u];
+        list_b[at] = x;
+        m[u] = x;
+      }
+      if (row[u] == t) picked[u] = true;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      const size_t at = (size_t)bp * d_loc + step;
+      idx[at] = map.token(p, t);
+      const uint64_t value = (top >> 12) - 1;
+      const double shown = (double)value - (step == 0 ? (double)n * kSimScale : 0.0);  // the first value is the row sum
+      if (gain_out) gain_out[at] = (float)(shown / kSimScale);
+      if constexpr (GAP) {
+        uint64_t second = 0;
+        for (int q = 0; q < NW; q++) second = red2[q] > second ? red2[q] : second;
+        gap_out[at] = second ? (float)((double)((top >> 12) - (second >> 12)) / kSimScale) : __builtin_inff();
+      }
+    }
+    // ---- (3) the changed columns lower the rows' values ----
+    constexpr int kBatch = 4;  // list entries (rows of S) whose loads are in flight together (a round seldom has more)
+    const int cnt = list_n;
+    uint64_t dec[kBigRows];
+#pragma unroll
+    for (int u = 0; u < kBigRows; u++) dec[u] = 0;
+    for (int e0 = 0; e0 < cnt; e0 += kBatch) {
+      int32_t sj[kBatch][kBigRows], a[kBatch], b[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; q++) {
+        const int e = min(e0 + q, cnt - 1);
+        const int j = list_j[e];
+        a[q] = list_a[e];
+        b[q] = e0 + q < cnt ? list_b[e] : a[q];  // (a repeated entry with a == b adds nothing)
+#pragma unroll
+        for (int u = 0; u < kBigRows; u++) sj[q][u] = live[u] ? Sr[(size_t)j * n + row[u]] : 0;
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; q++)
+#pragma unroll
+        for (int u = 0; u < kBigRows; u++) {
+          const int32_t cl3 = min(max(sj[q][u], a[q]), b[q]);  // a <= b
+          dec[u] += (uint32_t)(cl3 - a[q]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kBigRows; u++) val[u] -= dec[u];
+    __syncthreads();  // everyone has read the list (and red / red2)
+    if (tid == 0) list_n = 0;
+  }
+}
+
 // Slices of K per 16 x 16 unit: more, smaller pieces of work spread more evenly over the SIMDs when
 // the units alone are only a few per SIMD; each slice still needs a few chunks to fill its pipeline.
 static int gram_k_split(const Shape &s) {
@@ -464,6 +595,13 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, f
                        s.n_loc, tiles, units); }
   int regions = s.B * s.P;
   KernelTimer kt(K_GREEDY, st);
+  if (s.n_loc > 256) {  // (regions too large for the register-resident kernel)
+    if (gap)
+      hipLaunchKernelGGL((k_greedy_big<true>), dim3(regions), dim3(kBigThreads), 0, st, S, idx, gain, gap, map, s.P, s.n_loc, s.d_loc);
+    else
+      hipLaunchKernelGGL((k_greedy_big<false>), dim3(regions), dim3(kBigThreads), 0, st, S, idx, gain, gap, map, s.P, s.n_loc, s.d_loc);
+    return launch_status();
+  }
   switch (s.n_loc / 16) {
 #define TOMA_GREEDY_CASE(NT)                                                                               \
   case NT:                                                                                                 \

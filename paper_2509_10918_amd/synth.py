@@ -68,6 +68,9 @@ WORKLOADS = {
     # the SDXL stage-1 shape with stripe-shaped regions (Sec. 4.3.1: contiguous rows, four grid rows
     # = 256 tokens per region): same inputs as "sdxl1", only the region map differs
     "sdxl1_stripe": Workload("sdxl1_stripe", 1, "bf16", 2, 64, 64, 640, 4, 64, 0.5, 10, 0, 2.0, 0.2),
+    # the SDXL stage-1 shape with four regions of 1024 tokens per sample: the few-regions end of the
+    # region-count ablation (Sec. 4.3.1; more regions are cheaper, fewer select more globally)
+    "sdxl1_4regions": Workload("sdxl1_4regions", 1, "bf16", 2, 64, 64, 640, 32, 32, 0.5, 10, 0, 2.0, 0.2),
 }
 
 

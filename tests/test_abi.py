@@ -45,7 +45,8 @@ def test_workspace_bytes_and_shape_errors():
     assert tb.toma_workspace_bytes(_d(d_loc=257), a) == 0           # more destinations than tokens
     assert tb.toma_workspace_bytes(_d(merge_regions=4), a) == 0     # neither 1 nor P
     assert tb.toma_workspace_bytes(_d(C=650), a) == 0               # width not a multiple of 32
-    assert tb.toma_workspace_bytes(_d(tile_h=32, tile_w=32), a) == 0  # region larger than 256 tokens
+    assert tb.toma_workspace_bytes(_d(tile_h=32, tile_w=32), a) > 0   # regions of 1024 tokens: the large-region selection
+    assert tb.toma_workspace_bytes(_d(tile_h=64, tile_w=64), a) == 0  # region larger than 2048 tokens
     assert tb.toma_workspace_bytes(_d(tau=0.0), a) == 0
     assert tb.toma_workspace_bytes(_d(), tb.toma_attn_desc(10, 32, 0)) == 0   # heads * head_dim != C
     assert tb.toma_workspace_bytes(None, None) == 0
@@ -69,7 +70,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.toma_layer(dp, ap, 0, x, None, x, x, x, x, x, x, x, None, x, None, ws, need - 1, None) == 4
     bad = _d(tile_w=48)
     assert L.toma_select(ctypes.addressof(bad), x, x, None, None, ws, need, None) == 2
-    big = _d(tile_h=32, tile_w=32, d_loc=512)
+    big = _d(tile_h=64, tile_w=64, d_loc=2048)   # a region of 4096 tokens: beyond the selection kernels
     assert L.toma_select(ctypes.addressof(big), x, x, None, None, ws, need, None) == 5
     assert L.toma_merge(dp, x, x, None, x, x, x, ws, need, None) == 1
     assert L.toma_merge_cached(dp, x, x, x, x, None, ws, need, None) == 1

@@ -29,7 +29,7 @@ def _report(name, got, ref, tol):
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("tile_local", [False, True])
-@pytest.mark.parametrize("name", ["sdxl1", "sdxl2", "flux", "sdxl1_stripe"])
+@pytest.mark.parametrize("name", ["sdxl1", "sdxl2", "flux", "sdxl1_stripe", "sdxl1_4regions"])
 def test_full_workload_layer(oracle, name, tile_local):
     w = W[name]
     R = w.P if tile_local else 1

@@ -79,6 +79,52 @@ def test_select_region_sizes(oracle, n_loc_shape, d_loc):
     assert not bad
 
 
+@pytest.mark.parametrize("dtype,grid,tile,keep", [
+    ("f32", (32, 32), (32, 32), 0.25),      # one region of 1024 tokens per sample: the paper's few-regions end
+    ("bf16", (64, 32), (32, 32), 0.5),      # two regions of 1024
+    ("bf16", (24, 48), (24, 24), 0.125),    # 576 tokens: not a multiple of the workgroup's 1024 threads
+    ("f32", (32, 64), (32, 64), 0.0625),    # 2048 tokens: two rows and two columns per thread
+])
+def test_select_large_regions(oracle, dtype, grid, tile, keep):
+    """Regions of more than 256 tokens take the selection kernel that keeps the similarities in memory:
+    picks, reported gains and leads over the runner-up must be the oracle's, exactly."""
+    H, Wd = grid
+    th, tw = tile
+    w = synth.scaled(W["tiny"], name="bigregion", dtype=dtype, B=2, H=H, W=Wd, C=64, tile_h=th, tile_w=tw, keep=keep,
+                     heads=1, index=23)
+    print(f"[select large regions] {dtype} grid {H}x{Wd} tile {th}x{tw} n_loc={w.n_loc} d_loc={w.d_loc}", flush=True)
+    inp = synth.make_inputs(w)
+    dv = tg.Device(w, inp, 1)
+    idx = dv.select()
+    bad, near, forced = tg.compare_picks(oracle, w, _f64(inp["X"]), idx)
+    print(f"  near-tie steps {near}, regions verified teacher-forced {forced}, mismatching {bad}", flush=True)
+    assert not bad
+    d = tg.oracle_desc(oracle, w, 1)
+    idx_ref, gain_ref, gap_ref = oracle.select(d, _f64(inp["X"]))
+    assert np.array_equal(idx, idx_ref)
+    assert np.allclose(dv.gain.cpu().numpy(), gain_ref, rtol=1e-6, atol=1e-6)
+    gap = dv.gap.cpu().numpy().astype(np.float64)
+    assert np.array_equal(np.isinf(gap), np.isinf(gap_ref))
+    fin = np.isfinite(gap_ref)
+    assert np.allclose(gap[fin], gap_ref[fin], rtol=1e-6, atol=0.0)
+    assert np.array_equal(gap[fin] == 0.0, gap_ref[fin] == 0.0)
+    assert np.array_equal(dv.select(gap=False), idx)
+
+
+def test_layer_with_large_regions(oracle):
+    """A whole layer call whose selection regions hold 1024 tokens (global merge), against the oracle."""
+    w = synth.scaled(W["tiny"], name="biglayer", dtype="bf16", B=2, H=32, W=64, C=128, tile_h=32, tile_w=32, keep=0.25,
+                     heads=2, index=29)
+    inp = synth.make_inputs(w)
+    X = _f64(inp["X"])
+    Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+    ref = oracle.layer(tg.oracle_desc(oracle, w, 1), X, *Wts, heads=w.heads)
+    dv = tg.Device(w, inp, 1)
+    Y, _ = dv.layer(0)
+    assert np.array_equal(dv.idx.cpu().numpy(), ref["idx"])
+    _check_stage("Y", Y, ref["Y"], tg.TOL[w.dtype])
+
+
 @pytest.mark.parametrize("dtype,C", [("bf16", 128), ("bf16", 256), ("f32", 64)])
 def test_select_many_regions(oracle, dtype, C):
     """64 regions of 256 tokens: enough 32 x 32 blocks of the similarity matrices for the kernel that

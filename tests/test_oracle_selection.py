@@ -295,7 +295,7 @@ def grid_vs_plain(oracle, w, X, regions):
     return out
 
 
-@pytest.mark.parametrize("name", ["tiny", "sdxl1", "sdxl2", "flux", "hires", "sdxl1_stripe"])
+@pytest.mark.parametrize("name", ["tiny", "sdxl1", "sdxl2", "flux", "hires", "sdxl1_stripe", "sdxl1_4regions"])
 def test_decision_grid_against_the_plain_definition(oracle, name):
     """Pins the precision in which the argmax is decided (the oracle's default sim_bits, which the GPU
     kernel shares) to the ungridded definition, on the benchmark workloads themselves (the 128 x 128
