@@ -18,11 +18,12 @@
 //              back exactly; a token with more than a few such elements has its rows of S recomputed
 //              in double precision by the selection kernel's prologue instead.
 //   k_gram_i8  one workgroup per (region, 64 x 32 block of S on or above the diagonal), the two panels of
-//              limbs staged through LDS per 64 channels, 32 products per wave and chunk; the epilogue
+//              limbs loaded into LDS per 64 channels, 32 products per wave and chunk; the epilogue
 //              scales by the tokens' norms, rounds to the grid and stores both triangles.
 // Limb layout: token row = ceil(C / 64) * 64 channels; per group of 16 channels 64 bytes: limb 0 of the
 // 16 channels, then limb 1, 2, 3.  A lane's operand for one limb and 16 channels is one 16-byte packet.
 #include "toma_common.h"
+#include "toma_gemm.h"
 #include "toma_internal.h"
 
 namespace toma {
@@ -148,11 +149,12 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
 // One workgroup of four waves (2 x 2) per (region, 64-token row block, 32-token column block at or right
 // of the row block's diagonal): wave (wi, wj) owns the 32 x 16 block of S made of tokens 32 wi .. of the
 // row block and 16 wj .. of the column block, as 2 x 1 tiles with seven int32 accumulators each (one per
-// limb-index sum).  Per 64 channels the two panels (256 bytes of limbs per token) go global -> registers
-// -> LDS once and every wave reads its 32 + 16 rows from there.  The LDS panels are double buffered, the
-// next chunk is fetched into registers while the matrix cores work on the current one, and three
-// workgroups share a CU: units this small keep every CU of the chip busy on an SDXL-sized input (640
-// of them) and hide each other's memory latency, which is what bounded 64 x 64 units.
+// limb-index sum).  Per 64 channels the two panels (256 bytes of limbs per token) go from global memory
+// straight into LDS (load-to-LDS path, no register in between: 16-byte register-to-LDS stores run at half
+// the rate of the reads on this machine and were a third of the LDS's busy time) and every wave reads
+// its 32 + 16 rows from there.  Units this small keep every CU of the chip busy on an SDXL-sized input
+// (640 of them) and, several to a CU, hide each other's memory latency, which is what bounded 64 x 64
+// units.
 constexpr int kGramRow = 256;  // bytes per token and chunk in LDS: 16 packets, packet kp of row r at slot
                                // (kp & 8) | ((kp ^ r) & 7) - the swizzle of the GEMM tiles, free of bank conflicts
                                // for 16 lanes reading one packet column of 16 rows (padded rows were not)
@@ -172,13 +174,16 @@ __host__ __device__ inline int gram_units(int n_loc) {
   return u;
 }
 
-__global__ __launch_bounds__(256, 3) void k_gram_i8(const uint32_t *__restrict__ Xq, const double *__restrict__ rnp,
+// NBUF: LDS buffers of one chunk each - three (two workgroups per CU, two chunks in flight) when the
+// grid has few workgroups per CU, two (three workgroups per CU, which hide each other's waits) otherwise
+template <int NBUF>
+__global__ __launch_bounds__(256, NBUF == 3 ? 2 : 3) void k_gram_i8(const uint32_t *__restrict__ Xq, const double *__restrict__ rnp,
                                                    int32_t *__restrict__ S, RegionMap map, int N, int P, int n_loc,
                                                    int row_words, int nchunks, int units, GramFix fix) {
   constexpr int kSlots = 8;  // flagged tokens of a unit that get a vector of corrections (see below)
   struct FixArea { LimbFix sfix[96]; double cvec[kSlots][64]; int8_t slot_of[96]; uint8_t flagged[kSlots]; int nflagged; };
-  static_assert(sizeof(FixArea) <= 2 * kGramPanel, "the corrections reuse the panels' memory");
-  __shared__ __align__(16) char smem[2 * kGramPanel];  // two buffers of [64 row tokens | 32 column tokens]
+  static_assert(sizeof(FixArea) <= NBUF * kGramPanel, "the corrections reuse the panels' memory");
+  __shared__ __align__(1024) char smem[NBUF * kGramPanel];  // buffers of [64 row tokens | 32 column tokens]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
   const int wi = w >> 1, wj = w & 1;
   const int work = xcd_remap(blockIdx.x, gridDim.x);
@@ -190,28 +195,25 @@ __global__ __launch_bounds__(256, 3) void k_gram_i8(const uint32_t *__restrict__
   const int b = bp / P, p = bp % P;
   const int row0 = 64 * bm, col0 = 32 * bn;
 
-  // staging: thread t moves packets t, t + 256, ... of the panels (96 rows x 16 packets per chunk)
+  // Staging by the load-to-LDS path: a chunk's panels are 24 KiB = 24 loads of 1 KiB, six per wave; lane l
+  // of load u of wave w lands at LDS position (row 4 (6 w + u) + l / 16, slot l % 16) and therefore fetches
+  // the packet that the swizzle keeps there.  Three LDS buffers: chunk k + 2 is requested while chunk k
+  // is multiplied, no register holds operands in flight, and only the waits below order loads and reads.
   const uint32_t *src[6];
-  int dst[6];
 #pragma unroll
   for (int u = 0; u < 6; u++) {
-    const int q = tid + 256 * u, row = q >> 4, pk = q & 15;  // rows 0..63: row panel, 64..95: column panel
+    const int row = 4 * (6 * w + u) + (lane >> 4), slot = lane & 15;  // rows 0..63: row panel, 64..95: column panel
+    const int kp = (slot & 8) | ((slot ^ row) & 7);
     const int l = min(row < 64 ? row0 + row : col0 + row - 64, n_loc - 1);
-    src[u] = Xq + ((size_t)b * N + map.token(p, l)) * row_words + 4 * pk;
-    dst[u] = gram_slot(row, pk);
+    src[u] = Xq + ((size_t)b * N + map.token(p, l)) * row_words + 4 * kp;
   }
-  // two register sets: chunk k travels in set k % 2, fetched three steps before its products
-  i32x4 stage[2][6];
-  auto fetch = [&](int k, auto set) {
+  const uint32_t my_lds = lds_addr_of(smem) + (uint32_t)__builtin_amdgcn_readfirstlane(w) * (6 * 1024);
+  auto issue = [&](int k) {  // chunk k into buffer k % 3
+    const uint32_t at = my_lds + (uint32_t)(k % NBUF) * kGramPanel;
 #pragma unroll
-    for (int u = 0; u < 6; u++) stage[set()][u] = *reinterpret_cast<const i32x4 *>(src[u] + 64 * k);
+    for (int u = 0; u < 6; u++) load_to_lds16_at(src[u] + 64 * k, at + (uint32_t)u * 1024);
   };
-  auto stash = [&](int buf, auto set) {
-#pragma unroll
-    for (int u = 0; u < 6; u++) *reinterpret_cast<i32x4 *>(&smem[buf * kGramPanel + dst[u]]) = stage[set()][u];
-  };
-  auto set0 = [] { return 0; };
-  auto set1 = [] { return 1; };
+  auto fence = [&]() { asm volatile("" ::: "memory"); };
 
   // does any of this unit's 96 tokens carry a correction?  (almost never; the flag is asked for here
   // and first looked at after the main loop, so its latency costs nothing)
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(256, 3) void k_gram_i8(const uint32_t *__restrict__
     fb[l] = gram_slot(64 + 16 * wj + c, 4 * g + l);
   }
   auto products = [&](int k) {
-    const char *buf = &smem[(k & 1) * kGramPanel];
+    const char *buf = &smem[(k % NBUF) * kGramPanel];
     i32x4 a[2][4], bb[4];
 #pragma unroll
     for (int l = 0; l < 4; l++) {
@@ -254,23 +256,22 @@ __global__ __launch_bounds__(256, 3) void k_gram_i8(const uint32_t *__restrict__
         for (int i = 0; i < 2; i++)
           acc[i][la + lb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i][la], bb[lb], acc[i][la + lb], 0, 0, 0);
   };
-  // step k: chunk k + 1 from its register set into the other LDS buffer (every wave left that buffer at
-  // the barrier that ended step k - 1), chunk k + 3 into the freed register set, products of chunk k
-  auto step = [&](int k, auto next_set) {
-    if (k + 1 < nchunks) stash((k + 1) & 1, next_set);
-    if (k + 3 < nchunks) fetch(k + 3, next_set);
+  // (the flag load above has returned by the first wait: loads complete in order)
+  issue(0);
+  if (NBUF == 3 && nchunks > 1) issue(1);
+  for (int k = 0; k < nchunks; k++) {
+    // this wave's part of chunk k has landed (with three buffers chunk k + 1 may still be in flight); after
+    // the barrier so has everyone's, and every wave is done with chunk k - 1, whose buffer the next request takes
+    if (NBUF == 3 && k + 1 < nchunks) wait_vmcnt<6>(); else wait_vmcnt<0>();
+    fence();
+    __builtin_amdgcn_s_barrier();
+    fence();
+    if (k + NBUF - 1 < nchunks) issue(k + NBUF - 1);
     products(k);
-    __syncthreads();
-  };
-  fetch(0, set0);
-  stash(0, set0);
-  if (nchunks > 1) fetch(1, set1);
-  if (nchunks > 2) fetch(2, set0);
-  __syncthreads();
-  for (int k = 0; k < nchunks; k += 2) {
-    step(k, set1);
-    if (k + 1 < nchunks) step(k + 1, set0);
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's reads of chunk k have returned
+    fence();
   }
+  __syncthreads();  // the panels are dead: their memory is used for the corrections below
 
   // Corrections (rare).  Slots 0..63 are the unit's row tokens, 64..95 its column tokens.  Up to kSlots
   // flagged slots get a vector of corrections each, one per partner on the other side, computed by
@@ -427,8 +428,12 @@ int launch_gram_i8(const Shape &s, const void *X, int32_t *S, char *ws_part, con
   const int units = gram_units(s.n_loc), regions = s.B * s.P;
   KernelTimer kt(K_GRAM, st);
   const GramFix gfix{static_cast<const bf16_t *>(X), nrm, flag, fixes, s.C};
-  hipLaunchKernelGGL(k_gram_i8, dim3(units * regions), dim3(256), 0, st, Xq, rnp, S, map, s.N, s.P, s.n_loc, row_words, nchunks,
-                     units, gfix);
+  if ((long long)units * regions <= 2 * 256)
+    hipLaunchKernelGGL(k_gram_i8<3>, dim3(units * regions), dim3(256), 0, st, Xq, rnp, S, map, s.N, s.P, s.n_loc, row_words,
+                       nchunks, units, gfix);
+  else
+    hipLaunchKernelGGL(k_gram_i8<2>, dim3(units * regions), dim3(256), 0, st, Xq, rnp, S, map, s.N, s.P, s.n_loc, row_words,
+                       nchunks, units, gfix);
   *nrm_out = nrm;
   *flag_out = flag;
   return launch_status();
