@@ -256,7 +256,21 @@ __global__ __launch_bounds__(256, NBUF == 3 ? 2 : 3) void k_gram_i8(const uint32
         for (int i = 0; i < 2; i++)
           acc[i][la + lb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i][la], bb[lb], acc[i][la + lb], 0, 0, 0);
   };
-  // (the flag load above has returned by the first wait: loads complete in order)
+  // the scaled reciprocal norms of this lane's column and eight rows: asked for now, used after the loop
+  const int cl = 16 * wj + c, col = col0 + cl;
+  const bool col_ok = col < n_loc;
+  const size_t tj = (size_t)b * N + map.token(p, min(col, n_loc - 1));
+  const double rj = rnp[tj];
+  size_t ti_[2][4];
+  double ri_[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      ti_[i][r] = (size_t)b * N + map.token(p, min(row0 + 32 * wi + 16 * i + 4 * g + r, n_loc - 1));
+      ri_[i][r] = rnp[ti_[i][r]];
+    }
+  // (these loads and the flag load above have returned by the first wait: loads complete in order)
   issue(0);
   if (NBUF == 3 && nchunks > 1) issue(1);
   for (int k = 0; k < nchunks; k++) {
@@ -326,10 +340,6 @@ __global__ __launch_bounds__(256, NBUF == 3 ? 2 : 3) void k_gram_i8(const uint32
   // diagonal block cover it between them.
   int32_t *Sr = S + (size_t)bp * n_loc * n_loc;
   const bool mirror = bn >= 2 * bm + 2;
-  const int cl = 16 * wj + c, col = col0 + cl;
-  const bool col_ok = col < n_loc;
-  const size_t tj = (size_t)b * N + map.token(p, min(col, n_loc - 1));
-  const double rj = rnp[tj];
 #pragma unroll
   for (int i = 0; i < 2; i++) {
     i32x4 v4 = {0, 0, 0, 0};
@@ -337,8 +347,8 @@ __global__ __launch_bounds__(256, NBUF == 3 ? 2 : 3) void k_gram_i8(const uint32
     for (int r = 0; r < 4; r++) {
       const int rs = 32 * wi + 16 * i + 4 * g + r, row = row0 + rs;
       if (!col_ok || row >= n_loc) continue;
-      const size_t ti = (size_t)b * N + map.token(p, row);
-      const double ri = rnp[ti];
+      const size_t ti = ti_[i][r];
+      const double ri = ri_[i][r];
       // the three high sums are exact in double (below 2^48); the low four lose at most 2^3 of 2^58 and up
       const double hi = fma((double)acc[i][6][r], 65536.0, fma((double)acc[i][5][r], 256.0, (double)acc[i][4][r]));
       const double lo = fma((double)acc[i][3][r], 16777216.0,
