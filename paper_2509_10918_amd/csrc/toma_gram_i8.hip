@@ -46,6 +46,7 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
                                               uint8_t *__restrict__ flag, LimbFix *__restrict__ fixes, int rows, int C,
                                               int groups_pad) {
   __shared__ int fixn[4];
+  __shared__ u32x4 wbuf[4][256];  // per wave: the 256 packets of one pass over 64 groups
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, token = blockIdx.x * 4 + w;
   if (lane == 0) fixn[w] = 0;
   if (token >= rows) return;  // (whole waves leave together; nothing below crosses waves)
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
 #pragma unroll
   for (int it = 0; it < ITER; it++) {
     const int g = lane + 64 * it;
-    if (g >= groups_pad) continue;
+    if (64 * it >= groups_pad) break;  // (uniform; lanes past the row's end carry zeros through the exchange)
     // q = trunc(x * 2^(156 - emax)): the conversion instructions do the shifting; an element that the
     // fixed point cannot hold exactly shows as a fractional part (rare: looked at once per group)
     uint32_t lq[16], inexact = 0u;
@@ -120,7 +121,11 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
         if (at < kFixMax) { fx->ch[at] = 16 * g + i; fx->res[at] = val - ((bits & 0x8000u) ? -kept : kept); }
       }
     }
-    // byte k of the sixteen words -> limb plane k (four words)
+    // byte k of the sixteen words -> limb plane k (four words).  The four planes of a lane's group are 64
+    // consecutive bytes of the token's row; they go through the wave's corner of LDS so that a store
+    // instruction writes 1 KiB of consecutive bytes (lane l the packets l, l + 64, ... of this pass)
+    // instead of 16-byte pieces 64 bytes apart.
+    u32x4 *mine = wbuf[w];
 #pragma unroll
     for (int k = 0; k < 4; k++) {
       u32x4 o;
@@ -131,8 +136,15 @@ __global__ __launch_bounds__(256) void k_limbs(const bf16_t *__restrict__ X, uin
         const uint32_t p23 = __builtin_amdgcn_perm(lq[4 * m + 3], lq[4 * m + 2], sel);
         o[m] = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
       }
-      *reinterpret_cast<u32x4 *>(dst + 16 * g + 4 * k) = o;
+      mine[4 * lane + k] = o;
     }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int pkt = 256 * it + 64 * j + lane;  // packet of the token's row: 4 * group + plane
+      if (pkt < 4 * groups_pad) *reinterpret_cast<u32x4 *>(dst + 4 * pkt) = mine[64 * j + lane];
+    }
+    __builtin_amdgcn_wave_barrier();
   }
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
