@@ -443,6 +443,49 @@ def test_layer_chained_and_reuse(oracle, cases, name, tile_local):
     assert np.array_equal(tg.host(dv.A), A1) and np.array_equal(tg.host(dv.Z), Z1)
 
 
+@pytest.mark.parametrize("name,tile_local", [("small_bf16", False), ("small_bf16", True), ("ragged_f32", False),
+                                             ("extra", False)])
+def test_layer_replayed_from_a_graph(cases, name, tile_local):
+    """The library only queues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a layer call can be captured into a graph.  The three kinds of call of the
+    reuse schedule (nothing cached, cached idx, cached idx + weights) are captured once each and
+    replayed twice along the schedule on drifting tokens, with eager copies and synchronisations
+    between the replays; every replay must give the eager call's bits."""
+    w, inp = cases[name]
+    R = w.P if tile_local else 1
+    print(f"[graph] {name} merge_regions={R}", flush=True)
+    rng = np.random.default_rng(41)
+    Xs = [inp["X"]]
+    for _ in range(2):
+        Xs.append(synth.quantize(w, Xs[-1] + 0.02 * rng.standard_normal(inp["X"].shape).astype(np.float32)))
+    schedule = list(zip((0, tb.TOMA_REUSE_IDX, tb.TOMA_REUSE_A), Xs))
+    eager = tg.Device(w, inp, R)
+    want = []
+    for flags, X in schedule:
+        Y, Ye = eager.layer(flags, X=X)
+        want.append((Y, Ye, eager.idx.cpu().numpy().copy(), tg.host(eager.Z)))
+    dv = tg.Device(w, inp, R)
+    side = torch.cuda.Stream()
+    graphs = {}
+    for flags, _ in schedule:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            tb.toma_layer(dv.desc, dv.attn, flags, dv.X, dv.Xe, dv.idx, dv.A, dv.Z, dv.amap, dv.Wq, dv.Wk, dv.Wv,
+                          None, dv.Y, dv.Ye, dv.ws)
+        graphs[flags] = g
+    for rep in range(2):
+        for (flags, X), (Y, Ye, idx, Z) in zip(schedule, want):
+            dv.X.copy_(tg.dev(X, w.dtype))
+            dv.Y.zero_()
+            graphs[flags].replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(dv.idx.cpu().numpy(), idx), (rep, flags)
+            assert np.array_equal(tg.host(dv.Z), Z), (rep, flags)
+            assert np.array_equal(tg.host(dv.Y), Y), (rep, flags)
+            if Ye is not None:
+                assert np.array_equal(tg.host(dv.Ye), Ye), (rep, flags)
+
+
 @pytest.mark.parametrize("dtype,heads,C,L,T", [("bf16", 2, 256, 200, 0), ("bf16", 1, 32, 77, 5),
                                                ("f32", 2, 128, 130, 0), ("f32", 1, 128, 64, 3),
                                                ("bf16", 10, 640, 256, 1744), ("bf16", 12, 1536, 256, 1244)])
