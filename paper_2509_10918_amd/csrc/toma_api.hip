@@ -96,8 +96,10 @@ void plan_workspace(const Shape &s, Workspace *w) {
     w->occ_db = w->occ_sb = 0;
     w->occ_bytes = 0;
   }
-  w->z_in_merge = w->occ_sb != 0 && gemm_async_fits(s.Dr, s.C, s.Nr, (int)es) &&
-                  plan_map_product(s.Dr, s.C, s.Nr, s.B * s.R, (int)es, false, true, true).nsplit == 1;
+  // Z from the merge product's own A fragments: wherever that product keeps K whole in every workgroup
+  // (planned here exactly as at launch)
+  w->z_in_merge = gemm_async_fits(s.Dr, s.C, s.Nr, (int)es) &&
+                  plan_map_product(s.Dr, s.C, s.Nr, s.B * s.R, (int)es, false, true, w->occ_sb != 0).nsplit == 1;
   w->total = off;
 }
 
