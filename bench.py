@@ -164,6 +164,43 @@ def greedy_rounds(w, steps):
           f"more than the later ones (every column changes at the first pick, a handful later)")
 
 
+def greedy_parts(w):
+    """One selection of the workload's tokens through the greedy kernel that times the parts of its rounds
+    (toma_profile_greedy_parts): shader clocks per round and part, per wave, averaged over the regions."""
+    import torch
+    from paper_2509_10918_amd import binding as tb
+    from paper_2509_10918_amd import synth
+    X = torch.from_numpy(np.ascontiguousarray(synth.make_inputs(w)["X"], dtype=np.float32)).to("cuda")
+    X = X.to(torch.bfloat16 if w.dtype == "bf16" else torch.float32).contiguous()
+    desc = tb.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, 1, w.tau, w.dtype)
+    ws = tb.alloc_workspace(desc)
+    waves = (w.n_loc // 16 + 1) // 2
+    idx = torch.empty((w.B, w.P, w.d_loc), dtype=torch.int32, device="cuda")
+    ref = torch.empty_like(idx)
+    parts = torch.zeros((w.B * w.P, waves, 8), dtype=torch.int64, device="cuda")
+    tb.toma_select(desc, X, ref, None, None, ws)
+    for _ in range(3):
+        tb.toma_profile_greedy_parts(desc, X, idx, parts, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, ref), "the timing variant must pick what toma_select picks"
+    p = parts.cpu().numpy().astype(np.float64)
+    rounds = p[:, :, 5]
+    assert np.all(rounds == w.d_loc)
+    per = p[:, :, :5] / rounds[:, :, None]          # clocks per round and part
+    names = ["keys, argmax", "post row, barrier", "own columns", "changed columns", "second barrier"]
+    print(f"# greedy kernel of {w.name}: shader clocks per round and part (sums over all {w.d_loc} rounds of a region / "
+          f"{w.d_loc}), mean over the {w.B * w.P} regions; each part includes one read of the cycle counter (about 30 clocks)")
+    print(f"# command: python bench.py --workload {w.name} --greedy-parts")
+    print(f"{'wave':>6}" + "".join(f"{n:>20}" for n in names) + f"{'sum':>10}{'changed columns / round':>26}")
+    mean = per.mean(axis=0)
+    chg = (p[:, :, 6] / rounds).mean(axis=0)
+    for wv in range(waves):
+        print(f"{wv:>6}" + "".join(f"{mean[wv, i]:>20.0f}" for i in range(5)) + f"{mean[wv].sum():>10.0f}{chg[wv]:>26.2f}")
+    busiest = per[:, :, 3].max(axis=1).mean()
+    print(f"all waves: {mean.sum(axis=1).mean():.0f} clocks per round; changed columns per round over all waves "
+          f"{chg.sum():.2f}; the wave with the most work in 'changed columns' spends {busiest:.0f} there (mean over regions)")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -180,6 +217,9 @@ def main():
     ap.add_argument("--greedy-rounds", action="store_true",
                     help="time the selection of this workload at several numbers of picks per region (the greedy "
                          "kernel's rounds) and print what a round costs; nothing else")
+    ap.add_argument("--greedy-parts", action="store_true",
+                    help="one selection of this workload through the greedy kernel that times the parts of its "
+                         "rounds (regions of 256 or 64 tokens); prints clocks per round and part; nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -193,6 +233,9 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.greedy_rounds:
         greedy_rounds(w, args.steps)
+        return
+    if args.greedy_parts:
+        greedy_parts(w)
         return
     R = 1 if args.merge_regions == "global" else w.P
     inp = synth.make_inputs(w)

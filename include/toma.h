@@ -295,6 +295,17 @@ int toma_profile_read(const char *kernel, int32_t *launches, float *total_ms);
  * products actually executed.  Host arithmetic only; TOMA_ERR_UNSUPPORTED when the product does not
  * take the tiled path. */
 int toma_profile_map_product(const toma_desc *desc, int which, int32_t *out3);
+/* toma_select (Sec. 4.1, Alg. 2) with the greedy kernel replaced by a variant of itself that also
+ * adds up, per wave, the shader clocks spent in each part of a round - a measurement aid for the one
+ * kernel whose time is a chain of dependent steps rather than bytes or products.  idx as toma_select.
+ * parts: device, 8 words per (sample, region) and wave, [B * P][waves][8], waves = 8 for regions of
+ * 256 tokens and 2 for regions of 64 (other region sizes: TOMA_ERR_UNSUPPORTED): sums over the
+ * rounds of 0 keys read and argmax found, 1 row of the pick posted and first barrier, 2 own columns
+ * read and the changed ones found, 3 changed columns applied and atomics issued, 4 second barrier
+ * (with the wait for the busiest wave); 5 rounds; 6 changed columns this wave owned; 7 zero.
+ * Reading the counter costs about 30 clocks per part. */
+int toma_profile_greedy_parts(const toma_desc *desc, const void *X, int32_t *idx, uint64_t *parts, void *ws,
+                              size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

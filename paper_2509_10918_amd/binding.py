@@ -18,7 +18,7 @@ TOMA_REUSE_IDX, TOMA_REUSE_A, TOMA_RECOMPUTE_WEIGHTS = 1, 2, 4
 EXPORTS = ("toma_workspace_bytes", "toma_status_string", "toma_select", "toma_select_static", "toma_merge", "toma_map_bytes",
            "toma_map_build", "toma_merge_cached", "toma_attend", "toma_cross_attend", "toma_unmerge", "toma_unmerge_pinv", "toma_recompute_cache_bytes", "toma_merge_recompute",
            "toma_unmerge_recompute", "toma_layer", "toma_mlp", "toma_profile_enable",
-           "toma_profile_kernel_name", "toma_profile_read", "toma_profile_map_product")
+           "toma_profile_kernel_name", "toma_profile_read", "toma_profile_map_product", "toma_profile_greedy_parts")
 
 
 class TomaError(RuntimeError):
@@ -98,6 +98,8 @@ def lib():
         L.toma_profile_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
         L.toma_profile_map_product.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
         L.toma_profile_map_product.restype = ctypes.c_int
+        L.toma_profile_greedy_parts.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.toma_profile_greedy_parts.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -252,6 +254,13 @@ def toma_profile_map_product(desc, which):
     out = (ctypes.c_int32 * 3)()
     rc = lib().toma_profile_map_product(_ref(desc), int(which), out)
     return None if rc != 0 else tuple(out)
+
+
+def toma_profile_greedy_parts(desc, X, idx, parts, ws):
+    """toma_select through the greedy kernel that times the parts of its rounds; parts: int64
+    [B * P, waves, 8] (waves = 8 for regions of 256 tokens, 2 for regions of 64)."""
+    _check(lib().toma_profile_greedy_parts(_ref(desc), _ptr(X), _ptr(idx), _ptr(parts), _ptr(ws), ws.numel(), _stream()),
+           "toma_profile_greedy_parts")
 
 
 def alloc_cache(desc, device="cuda"):

@@ -135,9 +135,10 @@ void plan_workspace(const Shape &s, Workspace *w);
 size_t gram_i8_workspace_bytes(const Shape &s);
 int launch_gram_i8(const Shape &s, const void *X, int32_t *S, char *ws_part, const double **nrm_out,
                    const uint8_t **flag_out, hipStream_t st);
-// gain, gap: optional outputs (null: not wanted)
+// gain, gap: optional outputs (null: not wanted); parts: null, or where the profiling variant of the
+// greedy kernel leaves the clocks of the parts of its rounds (eight words per region and wave)
 int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, float *gap, char *ws,
-                  const Workspace &w, hipStream_t st);
+                  const Workspace &w, hipStream_t st, unsigned long long *parts = nullptr);
 // Pass 1 of the merge weights alone: stats[region][source][part] = (largest logit, sum of exponentials)
 // over each slice of *slice destinations, lse[region][source] = log-sum-exp over all destinations,
 // lse2 = the same as (largest logit, log of the sum)

@@ -117,3 +117,19 @@ TOMA_API int toma_profile_map_product(const toma_desc *desc, int which, int32_t 
   out3[0] = pl.bm; out3[1] = pl.bn; out3[2] = pl.nsplit;
   return TOMA_OK;
 }
+
+TOMA_API int toma_profile_greedy_parts(const toma_desc *desc, const void *X, int32_t *idx, uint64_t *parts, void *ws,
+                                       size_t ws_bytes, void *stream) {
+  Shape s;
+  int rc = make_shape(desc, nullptr, &s);
+  if (rc != TOMA_OK) return rc;
+  Workspace w;
+  plan_workspace(s, &w);
+  if (!X || !idx || !parts || !ws) return TOMA_ERR_NULL;
+  if (ws_bytes < w.total) return TOMA_ERR_WORKSPACE;
+  if (((uintptr_t)X & 15) || ((uintptr_t)ws & 255) || ((uintptr_t)parts & 7) || ((uintptr_t)idx & 3)) return TOMA_ERR_ALIGN;
+  if (s.n_loc != 256 && s.n_loc != 64) return TOMA_ERR_UNSUPPORTED;
+  static_assert(sizeof(unsigned long long) == sizeof(uint64_t), "clock words");
+  return launch_select(s, X, idx, nullptr, nullptr, static_cast<char *>(ws), w, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<unsigned long long *>(parts));
+}

@@ -209,11 +209,16 @@ struct RowFix { const bf16_t *X; const double *nrm; const uint8_t *flag; int N, 
 
 constexpr uint64_t kNoRunnerUp = ~0ull;  // recorded gap when the pick was the last candidate
 
-template <int NT, bool GAP>
+// CLOCKS (a profiling aid, never the product's kernel): every wave also adds up the shader clocks it
+// spends in each part of a round and leaves the sums in clk_out[(region * NW + wave) * 8 + ...]:
+// 0 keys read and argmax, 1 row t posted and first barrier, 2 own columns read and the changed ones
+// found, 3 changed columns and atomics, 4 second barrier; 5 rounds, 6 changed columns this wave owned.
+template <int NT, bool GAP, bool CLOCKS = false>
 __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int32_t *__restrict__ idx,
                                                              float *__restrict__ gain_out,
                                                              float *__restrict__ gap_out, RegionMap map,
-                                                             int P, int d_loc, RowFix fix) {
+                                                             int P, int d_loc, RowFix fix,
+                                                             unsigned long long *__restrict__ clk_out) {
   constexpr int NL = 16 * NT;          // tokens in the region
   constexpr int NW = (NT + 1) / 2;     // waves, up to 32 columns each
   constexpr int RPL = (NL + 63) / 64;  // rows per lane: lane l holds rows RPL l .. RPL l + RPL - 1
@@ -330,8 +335,13 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
   // for good, and no row's decrease in a round can exceed 32 bits either: the wide rounds (the first
   // ten or so of a 256-token region) hand over to the narrow ones, which run on the low words.
   // A wide round that finds the keys narrow enough returns true before it changes anything.
+  unsigned long long clk[7] = {0, 0, 0, 0, 0, 0, 0};
+  auto now = [&]() -> unsigned long long {
+    if constexpr (CLOCKS) return __builtin_readcyclecounter(); else return 0;
+  };
   auto round = [&](auto wide_c, int step) -> bool {
     constexpr bool WIDE = decltype(wide_c)::value;
+    const unsigned long long t0 = now();
     using K = std::conditional_t<WIDE, uint64_t, uint32_t>;
     auto key_at = [&](int at) -> K * {
       if constexpr (WIDE) return &keys[at]; else return &keys32[at];
@@ -357,6 +367,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     const int tl = __builtin_ctzll(__ballot(bk == top));
     const int tv = __builtin_amdgcn_readlane(bv, tl);
     const int t = RPL * tl + tv;
+    const unsigned long long t1 = now();
 
     // ---- the owner of column t posts row t ----
     if (w == t % NW) {
@@ -379,6 +390,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
       }
     }
     lds_barrier();  // every wave has read the keys; row t is posted
+    const unsigned long long t2 = now();
 
     // ---- new coverage of the own columns; the changed ones lower the rows' values ----
     if (threadIdx.x == 0) key_add(64 * tv + tl, ~(K)0);  // t is picked: its key ends at 0
@@ -386,6 +398,8 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     const int32_t m_old = m;
     m = max(m, x);
     uint32_t changed = (uint32_t)__ballot(reports && x > m_old);
+    const unsigned long long t3 = now();
+    if constexpr (CLOCKS) clk[6] += (unsigned)__builtin_popcount(changed);
     if (changed) {
       K dec[RPL];
 #pragma unroll
@@ -407,7 +421,12 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
       for (int v = 0; v < RPL; v++)
         if (RPL * lane + v < NL) key_add(64 * v + lane, (K)0 - dec[v]);
     }
+    const unsigned long long t4 = now();
     lds_barrier();  // the keys are final for the next round; every wave has read row t
+    if constexpr (CLOCKS) {
+      const unsigned long long t5 = now();
+      clk[0] += t1 - t0; clk[1] += t2 - t1; clk[2] += t3 - t2; clk[3] += t4 - t3; clk[4] += t5 - t4; clk[5] += 1;
+    }
     return false;
   };
 
@@ -418,6 +437,9 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     for (int i = threadIdx.x; i < RPL * 64; i += 64 * NW) keys32[i] = (uint32_t)keys[i];
     lds_barrier();
     for (; step < d_loc; step++) round(std::false_type{}, step);
+  }
+  if constexpr (CLOCKS) {
+    if (lane < 8) clk_out[((size_t)bp * NW + w) * 8 + lane] = lane < 7 ? clk[lane] : 0ull;
   }
   for (int k = threadIdx.x; k < d_loc; k += 64 * NW) {
     const size_t at = (size_t)bp * d_loc + k;
@@ -573,7 +595,7 @@ static int gram_k_split(const Shape &s) {
 
 template <typename T>
 static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, float *gap, char *ws,
-                        const Workspace &w, hipStream_t st) {
+                        const Workspace &w, hipStream_t st, unsigned long long *parts) {
   int32_t *S = reinterpret_cast<int32_t *>(ws + w.sim);
   RegionMap map{s.W, s.tile_h, s.tile_w, s.W / s.tile_w};
   const int tiles = s.n_loc / 16, units = tiles * (tiles + 1) / 2;
@@ -594,6 +616,17 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, f
     hipLaunchKernelGGL((k_gram<T, 1>), dim3((units + 3) / 4 * s.B * s.P), dim3(256), 0, st, X, S, map, s.N, s.C, s.P,
                        s.n_loc, tiles, units); }
   int regions = s.B * s.P;
+  if (parts) {  // the kernel that also times the parts of its rounds (64- and 256-token regions only)
+    if (s.n_loc == 256)
+      hipLaunchKernelGGL((k_greedy<16, false, true>), dim3(regions), dim3(512), 0, st, S, idx, gain, nullptr, map, s.P,
+                         s.d_loc, fix, parts);
+    else if (s.n_loc == 64)
+      hipLaunchKernelGGL((k_greedy<4, false, true>), dim3(regions), dim3(128), 0, st, S, idx, gain, nullptr, map, s.P,
+                         s.d_loc, fix, parts);
+    else
+      return TOMA_ERR_UNSUPPORTED;
+    return launch_status();
+  }
   KernelTimer kt(K_GREEDY, st);
   if (s.n_loc > 256) {  // (regions too large for the register-resident kernel)
     if (gap)
@@ -607,10 +640,10 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, f
   case NT:                                                                                                 \
     if (gap)                                                                                               \
       hipLaunchKernelGGL((k_greedy<NT, true>), dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, gap, \
-                         map, s.P, s.d_loc, fix);                                                          \
+                         map, s.P, s.d_loc, fix, nullptr);                                                 \
     else                                                                                                   \
       hipLaunchKernelGGL((k_greedy<NT, false>), dim3(regions), dim3(64 * ((NT + 1) / 2)), 0, st, S, idx, gain, gap, \
-                         map, s.P, s.d_loc, fix);                                                          \
+                         map, s.P, s.d_loc, fix, nullptr);                                                 \
     break;
     TOMA_GREEDY_CASE(1)
     TOMA_GREEDY_CASE(2)
@@ -636,9 +669,10 @@ static int select_typed(const Shape &s, const T *X, int32_t *idx, float *gain, f
 }
 
 int launch_select(const Shape &s, const void *X, int32_t *idx, float *gain, float *gap, char *ws,
-                  const Workspace &w, hipStream_t st) {
-  if (s.dtype == TOMA_BF16) return select_typed<bf16_t>(s, static_cast<const bf16_t *>(X), idx, gain, gap, ws, w, st);
-  return select_typed<float>(s, static_cast<const float *>(X), idx, gain, gap, ws, w, st);
+                  const Workspace &w, hipStream_t st, unsigned long long *parts) {
+  if (s.dtype == TOMA_BF16)
+    return select_typed<bf16_t>(s, static_cast<const bf16_t *>(X), idx, gain, gap, ws, w, st, parts);
+  return select_typed<float>(s, static_cast<const float *>(X), idx, gain, gap, ws, w, st, parts);
 }
 
 }  // namespace toma

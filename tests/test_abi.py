@@ -121,6 +121,14 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.toma_mlp(1, 4096, 640, 2500, x, x, x, x, x, None) == 5
     assert L.toma_mlp(7, 4096, 640, 2560, x, x, x, x, x, None) == 5
     assert L.toma_mlp(0, 4096, 640, 2560, x, x + 4, x, x, x, None) == 3
+    # the timing variant of the selection: same checks as toma_select, plus the region sizes it exists for
+    need_s = tb.toma_workspace_bytes(d, None)
+    assert L.toma_profile_greedy_parts(dp, x, x, None, ws, need_s, None) == 1
+    assert L.toma_profile_greedy_parts(dp, None, x, x, ws, need_s, None) == 1
+    assert L.toma_profile_greedy_parts(dp, x, x, x + 4, ws, need_s, None) == 3
+    assert L.toma_profile_greedy_parts(dp, x, x, x, ws, need_s - 1, None) == 4
+    other = _d(tile_h=8, tile_w=16, d_loc=64)   # regions of 128 tokens
+    assert L.toma_profile_greedy_parts(ctypes.addressof(other), x, x, x, ws, need_s, None) == 5
 
 
 def test_binding_raises_with_status():

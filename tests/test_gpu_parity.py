@@ -443,6 +443,36 @@ def test_layer_chained_and_reuse(oracle, cases, name, tile_local):
     assert np.array_equal(tg.host(dv.A), A1) and np.array_equal(tg.host(dv.Z), Z1)
 
 
+@pytest.mark.parametrize("name", ["small_bf16", "tiny"])
+def test_greedy_kernel_that_times_its_rounds(cases, name):
+    """The profiling variant of the greedy kernel (regions of 256 and of 64 tokens) picks exactly what
+    toma_select picks, counts one round per pick in every wave, and its clock sums are plausible (a part
+    of a round takes tens to thousands of clocks); other region sizes are refused."""
+    w, inp = cases[name]
+    print(f"[greedy parts] {name} n_loc={w.n_loc}", flush=True)
+    assert w.n_loc in (256, 64)
+    dv = tg.Device(w, inp, 1)
+    ref = dv.select(gap=False).copy()
+    waves = (w.n_loc // 16 + 1) // 2
+    parts = torch.full((w.B * w.P, waves, 8), -1, dtype=torch.int64, device="cuda")
+    dv.idx.zero_()
+    tb.toma_profile_greedy_parts(dv.desc, dv.X, dv.idx, parts, dv.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(dv.idx.cpu().numpy(), ref)
+    p = parts.cpu().numpy()
+    assert np.all(p[:, :, 5] == w.d_loc) and np.all(p[:, :, 7] == 0)
+    per_round = p[:, :, :5] / float(w.d_loc)
+    assert np.all(per_round > 5) and np.all(per_round < 50000)
+    # every column of a region changes at least once (at the first pick), none more often than once per round
+    changed = p[:, :, 6].sum(axis=1)
+    assert np.all(changed >= w.n_loc) and np.all(changed <= w.n_loc * w.d_loc)
+    w2, inp2 = cases["ragged_f32"]
+    dv2 = tg.Device(w2, inp2, 1)
+    with pytest.raises(tb.TomaError) as e:
+        tb.toma_profile_greedy_parts(dv2.desc, dv2.X, dv2.idx, parts, dv2.ws)
+    assert e.value.status == 5
+
+
 @pytest.mark.parametrize("name,tile_local", [("small_bf16", False), ("small_bf16", True), ("ragged_f32", False),
                                              ("extra", False)])
 def test_layer_replayed_from_a_graph(cases, name, tile_local):
