@@ -400,7 +400,48 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     uint32_t changed = (uint32_t)__ballot(reports && x > m_old);
     const unsigned long long t3 = now();
     if constexpr (CLOCKS) clk[6] += (unsigned)__builtin_popcount(changed);
-    if (changed) {
+    if constexpr (!WIDE && RPL == 4) {
+      // The common case (a region of 208 to 256 tokens, keys in 32-bit words) written out as
+      // instructions: the column's four registers are fetched under one switch of the register-index
+      // mode (instead of one switch on and off around every fetch), each bank asked for
+      // in the registers where the compiler's own relative addressing keeps it anyway, and only the
+      // clamped values are summed per column - the lower ends a are added up once, in a scalar
+      // register (32-bit wrap-around is exact here: the true decrease fits the key's 32 bits).
+      if (changed) {
+        uint32_t q_sum[4] = {0u, 0u, 0u, 0u}, a_sum = 0u;
+        do {
+          const int c = __builtin_ctz(changed);
+          changed &= changed - 1;
+          const int32_t a = __builtin_amdgcn_readlane(m_old, c), b = __builtin_amdgcn_readlane(m, c);
+          a_sum += (uint32_t)a;
+          int32_t q0, q1, q2, q3, bv;
+          asm volatile(
+              "v_mov_b32 %[bv], %[b]\n\t"
+              "s_set_gpr_idx_on %[c], gpr_idx(SRC0)\n\t"
+              "v_mov_b32 %[q0], v0\n\t"
+              "v_mov_b32 %[q1], v32\n\t"
+              "v_mov_b32 %[q2], v64\n\t"
+              "v_mov_b32 %[q3], v96\n\t"
+              "s_set_gpr_idx_off\n\t"
+              "v_med3_i32 %[q0], %[q0], %[a], %[bv]\n\t"
+              "v_med3_i32 %[q1], %[q1], %[a], %[bv]\n\t"
+              "v_med3_i32 %[q2], %[q2], %[a], %[bv]\n\t"
+              "v_med3_i32 %[q3], %[q3], %[a], %[bv]\n\t"
+              "v_add_u32 %[d0], %[d0], %[q0]\n\t"
+              "v_add_u32 %[d1], %[d1], %[q1]\n\t"
+              "v_add_u32 %[d2], %[d2], %[q2]\n\t"
+              "v_add_u32 %[d3], %[d3], %[q3]"
+              : [d0] "+v"(q_sum[0]), [d1] "+v"(q_sum[1]), [d2] "+v"(q_sum[2]), [d3] "+v"(q_sum[3]), [q0] "=&v"(q0),
+                [q1] "=&v"(q1), [q2] "=&v"(q2), [q3] "=&v"(q3), [bv] "=&v"(bv)
+              : [c] "s"(c), [a] "s"(a), [b] "s"(b), "{v[0:31]}"(sv[0]), "{v[32:63]}"(sv[1]), "{v[64:95]}"(sv[2]),
+                "{v[96:127]}"(sv[RPL == 4 ? 3 : 0])
+              : "m0");
+        } while (changed);
+#pragma unroll
+        for (int v = 0; v < 4; v++)
+          if (4 * lane + v < NL) key_add(64 * v + lane, (K)(a_sum - q_sum[v]));
+      }
+    } else if (changed) {
       K dec[RPL];
 #pragma unroll
       for (int v = 0; v < RPL; v++) dec[v] = 0;
