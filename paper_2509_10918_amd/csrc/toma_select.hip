@@ -372,9 +372,26 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     // ---- the owner of column t posts row t ----
     if (w == t % NW) {
       const int ct = t / NW;  // wave-uniform register index
+      if constexpr (RPL == 4) {  // (the four fetches under one switch of the index mode, as in the column step below)
+        int32_t q[4];
+        asm volatile(
+            "s_set_gpr_idx_on %[ct], gpr_idx(SRC0)\n\t"
+            "v_mov_b32 %[q0], v0\n\t"
+            "v_mov_b32 %[q1], v32\n\t"
+            "v_mov_b32 %[q2], v64\n\t"
+            "v_mov_b32 %[q3], v96\n\t"
+            "s_set_gpr_idx_off"
+            : [q0] "=&v"(q[0]), [q1] "=&v"(q[1]), [q2] "=&v"(q[2]), [q3] "=&v"(q[3])
+            : [ct] "s"(ct), "{v[0:31]}"(sv[0]), "{v[32:63]}"(sv[1]), "{v[64:95]}"(sv[2]), "{v[96:127]}"(sv[RPL == 4 ? 3 : 0])
+            : "m0");
 #pragma unroll
-      for (int v = 0; v < RPL; v++)
-        if (post_at[v] >= 0) rowt[post_at[v]] = sv[v][ct];
+        for (int v = 0; v < 4; v++)
+          if (post_at[v] >= 0) rowt[post_at[v]] = q[v];
+      } else {
+#pragma unroll
+        for (int v = 0; v < RPL; v++)
+          if (post_at[v] >= 0) rowt[post_at[v]] = sv[v][ct];
+      }
     }
     if (threadIdx.x == 0) { pick_row[step] = t; pick_val[step] = (uint64_t)top - 1u; }
     if constexpr (GAP) {
@@ -393,7 +410,14 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     const unsigned long long t2 = now();
 
     // ---- new coverage of the own columns; the changed ones lower the rows' values ----
-    if (threadIdx.x == 0) key_add(64 * tv + tl, ~(K)0);  // t is picked: its key ends at 0
+    if (threadIdx.x == 0) {  // t is picked: its key ends at 0
+      if constexpr (WIDE) {
+        key_add(64 * tv + tl, ~(K)0);
+      } else {  // (as a bare instruction: the compiler wraps an atomic on a uniform address in a count of the active lanes)
+        const uint32_t at = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)&keys32[64 * tv + tl];
+        asm volatile("ds_add_u32 %0, %1" ::"v"(at), "v"(~0u) : "memory");
+      }
+    }
     const int32_t x = rowt[32 * w + cl];
     const int32_t m_old = m;
     m = max(m, x);
