@@ -161,9 +161,11 @@ __global__ __launch_bounds__(256) void k_gram(const T *__restrict__ X, int32_t *
 // of changed columns (a handful per round once a few destinations exist) instead of N_loc^2.
 // The first pick (largest row sum) is the same rule started from the coverage m = -1 everywhere:
 // sum_j max(0, S_ij + 1) = row sum + N_loc, so the loop has no special first round.
-// Layout.  With NW waves, wave w owns the columns NW c + w (c < 32) of S for ALL rows (neighbouring
-// columns, which tend to change together, belong to different waves); lane l holds the rows
-// RPL l + v, sv[v][c] = S[RPL l + v][NW c + w] (128 registers for a 256-token region).  The
+// Layout.  With NW waves, every wave owns one of each NW consecutive columns of S, for ALL rows, in
+// its register c = column / NW (c < 32) - which one rotates from tile row to tile row, so that the
+// columns that tend to change together, a pick's neighbours along and across the tile's rows, are
+// spread over the waves; lane l holds the rows RPL l + v, sv[v][c] = S[RPL l + v][column of
+// register c] (128 registers for a 256-token region).  The
 // coverage of the own columns lives in lanes 0..31.  A changed column costs its owner a few
 // instructions with the column's (m, m') as scalar operands and the column's registers addressed
 // relative to the wave-uniform column number (scalar branches cost far more here than indexing).
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
   constexpr int32_t kFloor = -(1 << 30);   // similarity -1: the coverage before the first pick
   __shared__ uint64_t keys[RPL * 64];      // [64 v + l]: value + 1 of row RPL l + v, 0 once picked
   __shared__ uint32_t keys32[RPL * 64];    // the same once every key fits 32 bits
-  __shared__ int32_t rowt[NW * 32];        // row t, column NW c + w at [32 w + c]
+  __shared__ int32_t rowt[NW * 32];        // row t: wave w's column of register c at [32 w + c]
   __shared__ int32_t pick_row[RPL * 64];   // row of every pick
   __shared__ uint64_t pick_val[RPL * 64];  // its value
   __shared__ uint64_t pick_gap[GAP ? RPL * 64 : 1];  // its lead over the runner-up
@@ -280,14 +282,28 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     }
   }
 
-  // Loaded through the symmetric element S[NW c + w][RPL l + v]: a lane reads RPL consecutive
+  // Which wave owns which column.  Of every NW consecutive columns each wave owns one, kept in its
+  // register c = column / NW; plainly, wave w would own the columns congruent to w.  A pick raises the
+  // coverage of the tokens around it in the tile, and tokens above one another are tile_w columns apart - a
+  // multiple of NW for the usual tiles, so whole vertical runs would fall to one wave, which then
+  // applies them one after the other while the rest wait.  Where the tile's width allows it (a power of
+  // two and a multiple of NW) the assignment is therefore rotated by three from one tile row to the next.
+  const int tile_w = map.tile_w;
+  const bool skewed = (tile_w & (tile_w - 1)) == 0 && tile_w % NW == 0 && NL % NW == 0;
+  const int skew = skewed ? 3 : 0, tw_sh = skewed ? __builtin_ctz(tile_w) : 0;
+  auto wave_of = [&](int col) { return (col + skew * (col >> tw_sh)) % NW; };
+  auto col_of = [&](int c) {  // the column this wave keeps in register c
+    const int base = NW * c;
+    return base + ((w - skew * (base >> tw_sh)) % NW + NW) % NW;
+  };
+  // Loaded through the symmetric element S[column][RPL l + v]: a lane reads RPL consecutive
   // words and consecutive lanes continue the run.
   typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
   typedef int32_t i32x32 __attribute__((ext_vector_type(32)));
   i32x32 sv[RPL];  // register vectors, indexed by wave-uniform column numbers (relative addressing)
 #pragma unroll
   for (int c = 0; c < 32; c++) {
-    const int col = NW * c + w;
+    const int col = col_of(c);
     if constexpr (RPL == 4) {  // NL is a multiple of 16: the four rows of a lane exist together
       const bool ok = col < NL && 4 * lane < NL;
       const i32x4 q = ok ? *reinterpret_cast<const i32x4 *>(Sr + (size_t)col * NL + 4 * lane) : (i32x4){0, 0, 0, 0};
@@ -300,16 +316,16 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
       }
     }
   }
-  // this lane keeps the coverage of column NW cl + w (lanes l and l + 32 hold the same; only the
-  // first 32 report changes, and never for a column past the region's end)
-  const bool col_ok = NW * cl + w < NL, reports = col_ok && lane < 32;
+  // this lane keeps the coverage of the column of register cl (lanes l and l + 32 hold the same; only
+  // the first 32 report changes, and never for a column past the region's end)
+  const bool col_ok = col_of(cl) < NL, reports = col_ok && lane < 32;
   int32_t m = col_ok ? kFloor : kPad;
   // where this lane's rows go in rowt (as columns, by symmetry)
   int post_at[RPL];
 #pragma unroll
   for (int v = 0; v < RPL; v++) {
     const int j = RPL * lane + v;
-    post_at[v] = j < NL ? (j % NW) * 32 + j / NW : -1;
+    post_at[v] = j < NL ? wave_of(j) * 32 + j / NW : -1;
   }
 
   auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
@@ -324,7 +340,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     uint64_t part = 0;
 #pragma unroll
     for (int c = 0; c < 32; c++)
-      if (NW * c + w < NL) part += (uint32_t)(sv[v][c] - kFloor);
+      if (col_of(c) < NL) part += (uint32_t)(sv[v][c] - kFloor);
     if (RPL * lane + v < NL)
       __hip_atomic_fetch_add(&keys[64 * v + lane], part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
@@ -370,7 +386,7 @@ __global__ __launch_bounds__(64 * ((NT + 1) / 2)) void k_greedy(int32_t *S, int3
     const unsigned long long t1 = now();
 
     // ---- the owner of column t posts row t ----
-    if (w == t % NW) {
+    if (w == wave_of(t)) {
       const int ct = t / NW;  // wave-uniform register index
       if constexpr (RPL == 4) {  // (the four fetches under one switch of the index mode, as in the column step below)
         int32_t q[4];
