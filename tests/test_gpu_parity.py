@@ -111,6 +111,42 @@ def test_select_large_regions(oracle, dtype, grid, tile, keep):
     assert np.array_equal(dv.select(gap=False), idx)
 
 
+@pytest.mark.parametrize("dtype,tile,keep", [
+    ("bf16", (4, 4), 0.5),       # 16 tokens: one wave, one row per lane
+    ("f32", (8, 16), 0.5),       # 128 tokens: four waves, two rows per lane, rotated column ownership
+    ("bf16", (16, 8), 0.25),     # 128 tokens in a narrow tile
+    ("f32", (10, 16), 0.3),      # 160 tokens: five waves (the tile width is no multiple: plain ownership)
+    ("bf16", (16, 12), 0.25),    # 192 tokens, a tile width that is no power of two
+    ("bf16", (13, 16), 0.5),     # 208 tokens: four rows per lane with lanes and registers past the end
+    ("f32", (15, 16), 0.5),      # 240 tokens: eight waves, 30 of 32 registers per wave in use
+    ("bf16", (8, 32), 0.75),     # 256 tokens in a wide tile, three quarters kept
+])
+def test_select_region_sizes(oracle, dtype, tile, keep):
+    """Region sizes between the smallest and 256 tokens: every number of waves and rows per lane of the
+    register-resident selection kernel, with and without the rotated assignment of columns to waves,
+    and regions that leave lanes, registers and LDS slots past their end unused.  Picks, gains and leads
+    must be the oracle's."""
+    th, tw = tile
+    w = synth.scaled(W["tiny"], name="regionsize", dtype=dtype, B=2, H=2 * th, W=tw, C=64, tile_h=th, tile_w=tw,
+                     keep=keep, heads=1, index=29)
+    print(f"[select region sizes] {dtype} tile {th}x{tw} n_loc={w.n_loc} d_loc={w.d_loc}", flush=True)
+    inp = synth.make_inputs(w)
+    dv = tg.Device(w, inp, 1)
+    idx = dv.select()
+    bad, near, forced = tg.compare_picks(oracle, w, _f64(inp["X"]), idx)
+    print(f"  near-tie steps {near}, regions verified teacher-forced {forced}, mismatching {bad}", flush=True)
+    assert not bad
+    d = tg.oracle_desc(oracle, w, 1)
+    idx_ref, gain_ref, gap_ref = oracle.select(d, _f64(inp["X"]))
+    same = np.all(idx == idx_ref, axis=2)
+    assert same.any()
+    assert np.allclose(dv.gain.cpu().numpy()[same], gain_ref[same], rtol=1e-6, atol=1e-6)
+    gap = dv.gap.cpu().numpy().astype(np.float64)
+    fin = same[..., None] & np.isfinite(gap_ref)
+    assert np.allclose(gap[fin], gap_ref[fin], rtol=1e-6, atol=0.0)
+    assert np.array_equal(dv.select(gap=False), idx)
+
+
 def test_layer_with_large_regions(oracle):
     """A whole layer call whose selection regions hold 1024 tokens (global merge), against the oracle."""
     w = synth.scaled(W["tiny"], name="biglayer", dtype="bf16", B=2, H=32, W=64, C=128, tile_h=32, tile_w=32, keep=0.25,
