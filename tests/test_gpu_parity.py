@@ -147,6 +147,37 @@ def test_select_region_sizes(oracle, dtype, tile, keep):
     assert np.array_equal(dv.select(gap=False), idx)
 
 
+def test_select_on_random_shapes(oracle):
+    """A seeded sweep over grids, tile shapes, channel counts, keep ratios and both dtypes (regions of 16
+    to 256 tokens, several regions along both axes, three samples): picks must be the oracle's."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 14:
+        th, tw = int(rng.integers(1, 17)), int(rng.choice([2, 4, 8, 12, 16, 24, 32, 64]))
+        n_loc = th * tw
+        if n_loc % 16 or n_loc > 256:
+            continue
+        gh, gw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        d_loc = int(rng.integers(1, n_loc + 1))
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        C = int(rng.choice([32, 64, 96, 160]))
+        w = synth.scaled(W["tiny"], name="rand", dtype=dtype, B=3, H=gh * th, W=gw * tw, C=C, tile_h=th, tile_w=tw,
+                         keep=d_loc / n_loc, heads=1, index=100 + done)
+        if w.d_loc != d_loc:
+            continue
+        print(f"[select random shapes] {dtype} grid {gh}x{gw} tiles of {th}x{tw}, C={C}, d_loc={d_loc}", flush=True)
+        inp = synth.make_inputs(w)
+        desc = tb.make_desc(w.B, w.H, w.W, w.C, w.tile_h, w.tile_w, w.d_loc, 1, w.tau, w.dtype)
+        X = tg.dev(inp["X"], dtype)
+        ws = tb.alloc_workspace(desc)
+        idx = torch.empty((w.B, w.P, w.d_loc), dtype=torch.int32, device="cuda")
+        tb.toma_select(desc, X, idx, None, None, ws)
+        torch.cuda.synchronize()
+        bad, near, forced = tg.compare_picks(oracle, w, _f64(inp["X"]), idx.cpu().numpy())
+        assert not bad, (th, tw, gh, gw, d_loc, dtype, C)
+        done += 1
+
+
 def test_layer_with_large_regions(oracle):
     """A whole layer call whose selection regions hold 1024 tokens (global merge), against the oracle."""
     w = synth.scaled(W["tiny"], name="biglayer", dtype="bf16", B=2, H=32, W=64, C=128, tile_h=32, tile_w=32, keep=0.25,
