@@ -510,6 +510,46 @@ def test_layer_chained_and_reuse(oracle, cases, name, tile_local):
     assert np.array_equal(tg.host(dv.A), A1) and np.array_equal(tg.host(dv.Z), Z1)
 
 
+def test_layer_on_random_shapes(oracle):
+    """A seeded sweep of whole layer calls (select, weights, merge, attention, unmerge): grids of one to
+    nine regions, tile shapes, widths with heads of 32 or 64, extra tokens, keep ratios, both merge modes
+    and both dtypes, against the oracle's layer at the stated tolerances."""
+    rng = np.random.default_rng(77)
+    done = 0
+    while done < 10:
+        th, tw = int(rng.choice([2, 4, 6, 8, 16])), int(rng.choice([4, 8, 16, 32]))
+        n_loc = th * tw
+        if n_loc % 16 or n_loc > 256:
+            continue
+        gh, gw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        d_loc = int(rng.integers(max(1, n_loc // 8), n_loc // 2 + 1))
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        dh = int(rng.choice([32, 64]))
+        heads = int(rng.integers(1, 5))
+        T = int(rng.choice([0, 0, 5, 40]))
+        w = synth.scaled(W["tiny"], name="randlayer", dtype=dtype, B=2, H=gh * th, W=gw * tw, C=heads * dh, tile_h=th,
+                         tile_w=tw, keep=d_loc / n_loc, heads=heads, T_extra=T, index=200 + done)
+        if w.d_loc != d_loc:
+            continue
+        R = w.P if rng.random() < 0.5 else 1
+        print(f"[layer random shapes] {dtype} grid {gh}x{gw} tiles of {th}x{tw}, {heads} heads x {dh}, d_loc={d_loc}, "
+              f"extra {T}, merge_regions={R}", flush=True)
+        inp = synth.make_inputs(w)
+        X = _f64(inp["X"])
+        Xe = None if inp["X_extra"] is None else _f64(inp["X_extra"])
+        Wts = [_f64(inp[k]) for k in ("Wq", "Wk", "Wv")]
+        ref = oracle.layer(tg.oracle_desc(oracle, w, R), X, *Wts, heads=w.heads, Xe=Xe)
+        dv = tg.Device(w, inp, R)
+        Y, Ye = dv.layer(0)
+        bad, near, forced = tg.compare_picks(oracle, w, X, dv.idx.cpu().numpy())
+        assert not bad
+        if np.array_equal(dv.idx.cpu().numpy(), ref["idx"]):   # (a near tie taken the other way changes everything after it)
+            _check_stage("Y", Y, ref["Y"], tg.TOL[w.dtype])
+            if Ye is not None:
+                _check_stage("Y_extra", Ye, ref["Y_extra"], tg.TOL[w.dtype])
+        done += 1
+
+
 @pytest.mark.parametrize("name", ["small_bf16", "tiny"])
 def test_greedy_kernel_that_times_its_rounds(cases, name):
     """The profiling variant of the greedy kernel (regions of 256 and of 64 tokens) picks exactly what
