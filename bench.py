@@ -94,7 +94,6 @@ def kernel_work(w, R, esize, exec_frac=None, int8_gram=False):
         "proj": dict(bound=mm, amount=2 * w.B * L * w.C * w.C),
         "scale_rows": dict(bound="hbm", amount=2 * w.B * w.D * w.C * esize),
         "unmerge": dict(bound=mm, amount=f["unmerge"] * ef.get("unmerge", 1.0), equiv=f["unmerge"]),
-        "copy_extra": dict(bound="hbm", amount=2 * w.B * w.T_extra * w.C * esize),
         # second pass of a K-split merge / unmerge product: at least two fp32 partials in, one tile out
         "split_finish": dict(bound="hbm", amount=w.B * w.D * w.C * (2 * 4 + esize)),
         "occupancy": dict(bound="hbm", amount=a_bytes),   # one read of the stored weights

@@ -180,14 +180,13 @@ int launch_unmerge_fused(const Shape &s, const void *X, const int32_t *idx, cons
 size_t pinv_workspace_bytes(const Shape &s);
 int launch_unmerge_pinv(const Shape &s, const void *A, const float *Z, const void *O, int o_rows, float rcond, void *Y,
                         char *ws, const Workspace &w, hipStream_t st);
-int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t st);
 // Out = gelu(In W1) W2 on `rows` rows; Hbuf is [rows, hidden] scratch of the same dtype
 int launch_mlp(int dtype, int rows, int C, int hidden, const void *In, const void *W1, const void *W2, void *Hbuf,
                void *Out, hipStream_t st);
 
 // Kernel identifiers of the profiling aid (toma_profile_*): one per kernel of the path.
 enum KernelId { K_LIMBS = 0, K_GRAM, K_GREEDY, K_WSTATS, K_LSE, K_WWRITE, K_ZSUM, K_MERGE, K_QKV, K_ATTN, K_PROJ,
-                K_SCALE, K_UNMERGE, K_COPY, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_PINV_EIG, K_PINV_APPLY, K_MERGE_FUSED, K_UNMERGE_FUSED, K_COUNT };
+                K_SCALE, K_UNMERGE, K_SPLIT, K_MLP_UP, K_MLP_DOWN, K_OCC, K_PINV_EIG, K_PINV_APPLY, K_MERGE_FUSED, K_UNMERGE_FUSED, K_COUNT };
 
 // Brackets one launch with HIP events on its stream while profiling is enabled; free otherwise.
 struct KernelTimer {

@@ -638,15 +638,6 @@ __global__ void k_scale_rows(const T *__restrict__ O, const float *__restrict__ 
   Os[e] = from_f32<T>(to_f32(O[((size_t)b * o_rows + j) * C + cc]) * rz);
 }
 
-template <typename T>
-__global__ void k_copy_extra(const T *__restrict__ O, T *__restrict__ Ye, int D, int T_extra, int C, size_t total) {
-  size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= total) return;
-  size_t per = (size_t)T_extra * C;
-  size_t b = e / per, r = e % per;
-  Ye[e] = O[(b * (size_t)(D + T_extra) + D) * C + r];
-}
-
 // Occupancy map of A (see toma_internal.h).  One workgroup per (WIDE packets of a row, destination
 // block, region): the rows of the block stream through 256 / WIDE at a time, every thread ORs the
 // raw bits of the packets of its column (eight loads in flight), and the columns of one source
@@ -852,20 +843,6 @@ int launch_unmerge(const Shape &s, const void *A, const float *Z, const uint8_t 
                    bool prescaled, void *Y, char *ws, const Workspace &w, hipStream_t st) {
   return s.dtype == TOMA_BF16 ? unmerge_typed<bf16_t>(s, A, Z, occ, O, o_rows, prescaled, Y, ws, w, st)
                               : unmerge_typed<float>(s, A, Z, occ, O, o_rows, prescaled, Y, ws, w, st);
-}
-
-int launch_copy_extra(const Shape &s, const void *O, void *Y_extra, hipStream_t st) {
-  size_t total = (size_t)s.B * s.T * s.C;
-  if (total == 0) return TOMA_OK;
-  dim3 grid((unsigned)((total + 255) / 256));
-  KernelTimer kt(K_COPY, st);
-  if (s.dtype == TOMA_BF16)
-    hipLaunchKernelGGL(k_copy_extra<bf16_t>, grid, dim3(256), 0, st, static_cast<const bf16_t *>(O),
-                       static_cast<bf16_t *>(Y_extra), s.D, s.T, s.C, total);
-  else
-    hipLaunchKernelGGL(k_copy_extra<float>, grid, dim3(256), 0, st, static_cast<const float *>(O),
-                       static_cast<float *>(Y_extra), s.D, s.T, s.C, total);
-  return launch_status();
 }
 
 }  // namespace toma

@@ -10,7 +10,7 @@ namespace toma {
 
 static const char *const kNames[K_COUNT] = {"limbs", "gram", "greedy", "weights_stats", "lse", "weights_write",
                                             "zsum", "merge", "qkv", "attention", "proj", "scale_rows",
-                                            "unmerge", "copy_extra", "split_finish", "mlp_up", "mlp_down", "occupancy",
+                                            "unmerge", "split_finish", "mlp_up", "mlp_down", "occupancy",
                                             "pinv_eig", "pinv_apply", "merge_recompute", "unmerge_recompute"};
 struct Rec { int id; hipEvent_t a, b; };
 static std::mutex g_mu;
