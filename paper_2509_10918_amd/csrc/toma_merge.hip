@@ -34,7 +34,7 @@ template <typename T, bool WRITE> struct WeightsPol {
   const float *lse;  // pass 2 in: [B*R][Nr]
   T *A;              // pass 2 out: [B*R][Dr][lda], lda >= Nr
   int lda;
-  float *zpart;      // pass 2 out: [B*R][Dr][zparts]
+  float *zpart;      // pass 2 out: [B*R][Dr][zparts] (null: not wanted)
   int zparts;
   uint8_t *occ;      // pass 2 out (optional): occupancy map of A, zeroed before the launch
   int occ_db, occ_sb;
@@ -74,6 +74,7 @@ template <typename T, bool WRITE> struct WeightsPol {
     }
     // the partial row sums of all of this tile's wave slices (also those past a ragged end: the
     // row-sum kernel adds up every slice of every tile)
+    if (!zpart) return;  // (the merge product makes Z)
     const int parts = bm / wave_rows, part0 = m0 / wave_rows;
     for (int e = tid; e < (n1 - n0) * parts; e += nthreads)
       zpart[((size_t)x.z * x.N + n0 + e / parts) * zparts + part0 + e % parts] = 0.f;
@@ -193,13 +194,15 @@ template <typename T, bool WRITE> struct WeightsPol {
         }
       }
       const int part = m_w / (16 * TM);
+      if (zpart) {
 #pragma unroll
-      for (int j = 0; j < TN; j++) {
-        float v4 = colsum[j];
-        v4 += wave_xor_f32(v4, 16);
-        v4 += wave_xor_f32(v4, 32);
-        int n = n_w + 16 * j + c;
-        if (g == 0 && n < N) zpart[((size_t)z * N + n) * zparts + part] = v4;
+        for (int j = 0; j < TN; j++) {
+          float v4 = colsum[j];
+          v4 += wave_xor_f32(v4, 16);
+          v4 += wave_xor_f32(v4, 32);
+          int n = n_w + 16 * j + c;
+          if (g == 0 && n < N) zpart[((size_t)z * N + n) * zparts + part] = v4;
+        }
       }
     }
   }
@@ -341,9 +344,11 @@ __device__ __forceinline__ void weights_one_pass_finish(f32x4 (&acc)[2][NJ], con
 #pragma unroll
       for (int i = 0; i < 2; i++) *reinterpret_cast<u32x4 *>(row + 16 * i + 4 * g) = *reinterpret_cast<u32x4 *>(o[i]);
     }
-    colsum += wave_xor_f32(colsum, 16);
-    colsum += wave_xor_f32(colsum, 32);
-    if (g == 0) zpart[((size_t)z * v.Dr + n) * zparts + mt] = colsum;
+    if (zpart) {  // (null: the merge product that follows makes Z from its own A fragments)
+      colsum += wave_xor_f32(colsum, 16);
+      colsum += wave_xor_f32(colsum, 32);
+      if (g == 0) zpart[((size_t)z * v.Dr + n) * zparts + mt] = colsum;
+    }
   }
   if (occ) {
     static_assert(kOccSrc == 32, "one source block per workgroup");
@@ -724,7 +729,8 @@ static int weights_typed(const Shape &s, const void *X, const int32_t *idx, void
                          char *ws, const Workspace &w, hipStream_t st) {
   int batch = s.B * s.R;
   const int zr = s.B * s.D;
-  float *zpart = reinterpret_cast<float *>(ws + w.zpart);
+  // partial row sums of the stored weights, for k_zsum: not needed where the merge product makes Z
+  float *zpart = w.z_in_merge ? nullptr : reinterpret_cast<float *>(ws + w.zpart);
   if (weights_single_pass(s.Nr, s.Dr, s.C, batch, (int)sizeof(T))) {
     const RegionView<T> v = make_view<T>(s, X);
     const int tiles = s.Nr / 32;
